@@ -1,0 +1,180 @@
+"""TEST INFRASTRUCTURE ONLY: numpy front end of the fp64 CPU checker (rs_oracle.c).
+
+Only tests, the smoke check and the bench's cpu_baseline leg may import this
+package.  It shares no code with the HIP path and never imports it.
+
+Every function takes numpy arrays (any float dtype, widened to fp64 here) and
+returns fp64 / int32 numpy arrays.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+import subprocess
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_SRC = os.path.join(_HERE, "rs_oracle.c")
+_LIB = os.path.join(_HERE, "librs_oracle.so")
+
+DIST_L2, DIST_L1, DIST_COS = 0, 1, 2
+
+
+def build(force: bool = False) -> str:
+    """Compile rs_oracle.c with gcc -O2 -fopenmp into oracle/librs_oracle.so."""
+    if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
+        tmp = _LIB + ".tmp%d" % os.getpid()
+        subprocess.check_call(["gcc", "-O2", "-std=c11", "-fopenmp", "-fPIC", "-shared",
+                               _SRC, "-o", tmp, "-lm"])
+        os.replace(tmp, _LIB)
+    return _LIB
+
+
+_lib = None
+_pd = ctypes.POINTER(ctypes.c_double)
+_pi = ctypes.POINTER(ctypes.c_int32)
+_i64 = ctypes.c_int64
+
+
+def lib():
+    global _lib
+    if _lib is None:
+        L = ctypes.CDLL(build())
+        L.rs_oracle_num_threads.restype = ctypes.c_int
+        L.rs_oracle_set_num_threads.argtypes = [ctypes.c_int]
+        L.rs_oracle_layernorm.argtypes = [_pd, _pd, _pd, ctypes.c_double, _i64, _i64, _pd]
+        L.rs_oracle_gelu.argtypes = [ctypes.c_double]
+        L.rs_oracle_gelu.restype = ctypes.c_double
+        L.rs_oracle_linear.argtypes = [_pd, _pd, _pd, _i64, _i64, _i64, _pd]
+        L.rs_oracle_attention.argtypes = [_pd, _pd, _pd, _pd] + [_i64] * 10 + [ctypes.c_double]
+        L.rs_oracle_shift_scores.argtypes = [_pd, _pd, _i64, _i64, ctypes.c_int, _pd]
+        L.rs_oracle_topk.argtypes = [_pd, _i64, _i64, _i64, _i64, _pi]
+        L.rs_oracle_gather.argtypes = [_pd, _pi, _i64, _i64, _i64, _i64, _pd]
+        L.rs_oracle_block.argtypes = ([_i64] * 5 + [ctypes.c_double, ctypes.c_double, ctypes.c_int]
+                                      + [_pd] * 13 + [_pd] * 4)
+        L.rs_oracle_block.restype = ctypes.c_int
+        _lib = L
+    return _lib
+
+
+def num_threads() -> int:
+    return int(lib().rs_oracle_num_threads())
+
+
+def set_num_threads(n: int) -> None:
+    lib().rs_oracle_set_num_threads(int(n))
+
+
+def _d(a):
+    return None if a is None else np.ascontiguousarray(a, dtype=np.float64)
+
+
+def _p(a):
+    return None if a is None else a.ctypes.data_as(_pd)
+
+
+def layernorm(x, gamma=None, beta=None, eps=1e-6):
+    x = _d(x)
+    D = x.shape[-1]
+    g, b = _d(gamma), _d(beta)
+    out = np.empty_like(x)
+    lib().rs_oracle_layernorm(_p(x), _p(g), _p(b), float(eps), x.size // D, D, _p(out))
+    return out
+
+
+def gelu(x):
+    x = _d(x)
+    f = lib().rs_oracle_gelu
+    return np.array([f(float(t)) for t in x.ravel()]).reshape(x.shape)
+
+
+def linear(a, w, bias=None):
+    a, w, bias = _d(a), _d(w), _d(bias)
+    K, N = w.shape
+    M = a.size // K
+    out = np.empty(a.shape[:-1] + (N,), np.float64)
+    lib().rs_oracle_linear(_p(a), _p(w), _p(bias), M, K, N, _p(out))
+    return out
+
+
+def attention(q, k, v, scale):
+    """q, k, v: [B, N, H, dh] -> o [B, N, H, dh]."""
+    q, k, v = _d(q), _d(k), _d(v)
+    B, N, H, dh = q.shape
+    o = np.empty_like(q)
+    lib().rs_oracle_attention(_p(q), _p(k), _p(v), _p(o), B, H, N, dh,
+                              N * H * dh, H * dh, dh, N * H * dh, H * dh, dh, float(scale))
+    return o
+
+
+def shift_scores(f_out, f_in, dist=DIST_L2):
+    """f_out, f_in: [..., D] -> scores [...]."""
+    a, b = _d(f_out), _d(f_in)
+    D = a.shape[-1]
+    s = np.empty(a.shape[:-1], np.float64)
+    lib().rs_oracle_shift_scores(_p(a), _p(b), a.size // D, D, int(dist), _p(s))
+    return s
+
+
+def topk(scores, n_prefix, n_keep):
+    """scores [B, N] -> kept_idx int32 [B, n_prefix + n_keep], ascending per image."""
+    s = _d(scores)
+    B, N = s.shape
+    assert 0 <= n_prefix <= N and 0 <= n_keep <= N - n_prefix
+    kept = np.empty((B, n_prefix + n_keep), np.int32)
+    lib().rs_oracle_topk(_p(s), B, N, n_prefix, n_keep, kept.ctypes.data_as(_pi))
+    return kept
+
+
+def gather(src, kept_idx):
+    """src [B, N, D], kept_idx [B, K] -> [B, K, D]."""
+    src = _d(src)
+    kept = np.ascontiguousarray(kept_idx, dtype=np.int32)
+    B, N, D = src.shape
+    K = kept.shape[1]
+    out = np.empty((B, K, D), np.float64)
+    lib().rs_oracle_gather(_p(src), kept.ctypes.data_as(_pi), B, N, K, D, _p(out))
+    return out
+
+
+def shift_topk(f_out, f_in, src, n_prefix, n_keep, dist=DIST_L2):
+    """Scores, kept indices and gathered rows of `src` (f_in when src is None)."""
+    s = shift_scores(f_out, f_in, dist)
+    kept = topk(s, n_prefix, n_keep)
+    return s, kept, gather(f_in if src is None else src, kept)
+
+
+def block(x, w, H, ln_eps=1e-6, attn_scale=None, dist=DIST_L2):
+    """One encoder block on x [B, N, D] with weight dict `w` (missing/None bias = 0).
+
+    Returns dict(x1, mlp, xhat [B,N,D], scores [B,N])."""
+    x = _d(x)
+    B, N, D = x.shape
+    Dm = w["w_fc1"].shape[1]
+    if attn_scale is None:
+        attn_scale = 1.0 / np.sqrt(D // H)
+    ws = {k: _d(w.get(k)) for k in ("ln1_g", "ln1_b", "w_qkv", "b_qkv", "w_proj", "b_proj",
+                                     "ln2_g", "ln2_b", "w_fc1", "b_fc1", "w_fc2", "b_fc2")}
+    assert ws["w_qkv"].shape == (D, 3 * D) and ws["w_proj"].shape == (D, D)
+    assert ws["w_fc1"].shape == (D, Dm) and ws["w_fc2"].shape == (Dm, D)
+    x1 = np.empty_like(x)
+    mlp = np.empty_like(x)
+    xhat = np.empty_like(x)
+    s = np.empty((B, N), np.float64)
+    rc = lib().rs_oracle_block(B, N, D, H, Dm, float(ln_eps), float(attn_scale), int(dist),
+                               _p(x), *[_p(ws[k]) for k in
+                                        ("ln1_g", "ln1_b", "w_qkv", "b_qkv", "w_proj", "b_proj",
+                                         "ln2_g", "ln2_b", "w_fc1", "b_fc1", "w_fc2", "b_fc2")],
+                               _p(x1), _p(mlp), _p(xhat), _p(s))
+    if rc != 0:
+        raise MemoryError("rs_oracle_block")
+    return dict(x1=x1, mlp=mlp, xhat=xhat, scores=s)
+
+
+def block_pruned(x, w, H, n_prefix, n_keep, **kw):
+    """Block followed by selection and gather: adds kept_idx [B,K] and y [B,K,D]."""
+    r = block(x, w, H, **kw)
+    r["kept_idx"] = topk(r["scores"], n_prefix, n_keep)
+    r["y"] = gather(r["xhat"], r["kept_idx"])
+    return r
