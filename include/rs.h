@@ -1,0 +1,166 @@
+/*
+ * rs.h -- C ABI of the representation-shift hot path for MI355X (gfx950).
+ *
+ * The library runs, on one GPU, a pre-LayerNorm ViT encoder block with fused
+ * multi-head attention (the attention map is never written to memory), scores
+ * every token by its representation shift around the MLP, keeps the highest
+ * scoring tokens (plus a protected prefix such as the class token) and compacts
+ * the survivors for the next block.
+ *
+ * Conventions shared by every call
+ *   - Every data pointer is a DEVICE pointer owned by the caller, unless a
+ *     comment says "host".  The library never allocates, frees or keeps device
+ *     memory; scratch space comes in through the `workspace` argument.
+ *   - Tensors are dense row-major.  B images, N tokens per image entering the
+ *     call, D channels, H heads of dh = D/H = 64 channels, Dm MLP width.
+ *     Linear weights are [in, out] ("[Q,K,V] = xW, W in R^{C x 3C}", Sec. 3.1).
+ *   - dtype selects storage AND arithmetic of activations and weights:
+ *     RS_F32 = fp32 storage, fp32 multiply-accumulate; RS_BF16 = bf16 storage,
+ *     bf16 matrix-core products accumulated in fp32.  Scores are always fp32,
+ *     indices int32.
+ *   - All work is enqueued on the caller's stream (`hip_stream` is a
+ *     hipStream_t, NULL = the default stream).  No call synchronises with the
+ *     host or copies to the host; outputs are valid once the stream reaches
+ *     that point.  Output shapes depend only on host-known integers.
+ *   - Every call returns an rs_status.  Argument errors are found before any
+ *     kernel is launched and leave the device untouched; rs_last_error() gives
+ *     a message for the calling thread's most recent failure.
+ *   - Same inputs give bit-identical outputs (no floating-point atomics).
+ *   - Alignment: every tensor pointer must be 16-byte aligned.
+ */
+#ifndef RS_H
+#define RS_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define RS_API __attribute__((visibility("default")))
+
+typedef enum {
+    RS_OK = 0,
+    RS_ERR_INVALID_ARG = 1,        /* NULL pointer, non-positive size, misaligned pointer ... */
+    RS_ERR_UNSUPPORTED = 2,        /* valid request outside what the kernels cover            */
+    RS_ERR_WORKSPACE_TOO_SMALL = 3,
+    RS_ERR_DEVICE = 4              /* a HIP call or kernel launch failed                      */
+} rs_status;
+
+typedef enum { RS_F32 = 0, RS_BF16 = 1 } rs_dtype;
+
+/* Distance D of the representation shift ("Distance metrics", Sec. 3.3).
+ * L2 is the paper's default. */
+typedef enum { RS_DIST_L2 = 0, RS_DIST_L1 = 1, RS_DIST_COS = 2 } rs_dist;
+
+/* Which transformation F the shift is measured around ("Operation choice",
+ * Sec. 3.3).  Case (ii), the MLP, is the paper's default and the only one
+ * rs_block_fwd computes; the others are reachable through rs_shift_topk. */
+typedef enum { RS_SHIFT_MLP = 0 } rs_shift_op;
+
+/* Weights of one encoder block, Eqs. (5),(6) of Sec. 3.3.  Element type follows
+ * cfg->dtype.  Any bias pointer may be NULL (= zero); LayerNorm gamma NULL = 1,
+ * beta NULL = 0.  W_qkv columns are ordered [Q | K | V], each H heads of dh. */
+typedef struct {
+    const void *ln1_g, *ln1_b;     /* [D]                 */
+    const void *w_qkv, *b_qkv;     /* [D, 3D], [3D]       */
+    const void *w_proj, *b_proj;   /* [D, D], [D]         */
+    const void *ln2_g, *ln2_b;     /* [D]                 */
+    const void *w_fc1, *b_fc1;     /* [D, Dm], [Dm]       */
+    const void *w_fc2, *b_fc2;     /* [Dm, D], [D]        */
+    /* Optional: buffer of rs_packed_weights_size() bytes filled by rs_pack_weights()
+     * from the four matrices above.  NULL = the library re-packs into the workspace
+     * on every rs_block_fwd call (RS_BF16 only; RS_F32 needs no packing). */
+    const void *packed;
+} rs_block_weights;
+
+typedef struct {
+    int32_t B, N, D, H, Dm;        /* D/H must be 64, D % 64 == 0, Dm % 64 == 0            */
+    int32_t n_prefix;              /* tokens [0, n_prefix) are always kept (1 = class token) */
+    int32_t n_keep;                /* non-prefix tokens kept; K = n_prefix + n_keep;        */
+                                   /* n_keep == N - n_prefix keeps every token              */
+    float ln_eps;                  /* LayerNorm epsilon (> 0)                               */
+    float attn_scale;              /* softmax scale; <= 0 selects 1/sqrt(dh)                */
+    rs_dtype dtype;
+    rs_dist dist;
+    rs_shift_op op;
+} rs_block_cfg;
+
+/* Thread-local message of the calling thread's most recent failing call
+ * (static storage, never NULL). */
+RS_API const char *rs_last_error(void);
+
+/* Library version as major*10000 + minor*100 + patch. */
+RS_API int32_t rs_version(void);
+
+/*
+ * Fused multi-head self-attention, Eq. (1) of Sec. 3.1:
+ *     O = Softmax(Q K^T * scale) V     per image and head,
+ * computed tile by tile with a running row maximum and row sum so that the
+ * N x N attention map never leaves the chip.
+ *   q, k, v : element (b, n, h, d) at  b*stride_b + n*stride_n + h*stride_h + d
+ *             (strides in ELEMENTS, shared by q, k and v; d is contiguous);
+ *             strides must be multiples of 8 elements (16 bytes in bf16).
+ *   o       : same addressing with the o_stride_* values; must not alias q, k, v.
+ *   dh      : must be 64.   scale: the caller's (1/sqrt(dh) for ViT heads; the
+ *             paper prints 1/sqrt(C)).   Needs no workspace.
+ */
+RS_API rs_status rs_attention_fwd(const void *q, const void *k, const void *v, void *o,
+                           int32_t B, int32_t H, int32_t N, int32_t dh,
+                           int64_t stride_b, int64_t stride_n, int64_t stride_h,
+                           int64_t o_stride_b, int64_t o_stride_n, int64_t o_stride_h,
+                           float scale, rs_dtype dtype, void *hip_stream);
+
+/*
+ * Representation shift score, selection and compaction (Eq. (4) of Sec. 3.2;
+ * pruning of the lowest-score tokens, Secs. 3.1 and 3.2):
+ *     scores[b, i] = D(f_out[b, i, :], f_in[b, i, :])
+ *     per image, among tokens i >= n_prefix, the n_keep highest scores survive
+ *     (equal scores: the lower index wins); kept_idx[b, :] lists the prefix and
+ *     the survivors in ascending index order (K = n_prefix + n_keep entries);
+ *     gathered[b, j, :] = src[b, kept_idx[b, j], :].
+ *   f_out, f_in : [B, N, D]  F(x) and x.            src : [B, N, D] or NULL (= f_in).
+ *   scores      : float [B, N], required.           kept_idx : int32 [B, K], required.
+ *   gathered    : [B, K, D] or NULL (no gather); must not alias src.
+ *   D % 8 == 0.  NaN scores order above +inf.  workspace: rs_shift_topk_workspace_size bytes.
+ */
+RS_API size_t rs_shift_topk_workspace_size(int32_t B, int32_t N, int32_t D, rs_dtype dtype);
+RS_API rs_status rs_shift_topk(const void *f_out, const void *f_in, const void *src,
+                        int32_t B, int32_t N, int32_t D, int32_t n_prefix, int32_t n_keep,
+                        rs_dist dist, rs_dtype dtype,
+                        float *scores, int32_t *kept_idx, void *gathered,
+                        void *workspace, size_t workspace_bytes, void *hip_stream);
+
+/*
+ * One-off re-layout of a block's four weight matrices for the matrix-core
+ * GEMMs (weights are static at inference; the method is training-free).
+ * `packed_out` must hold rs_packed_weights_size(cfg) bytes and is then passed
+ * as rs_block_weights.packed.  Only cfg->D, Dm, dtype are read.
+ */
+RS_API size_t rs_packed_weights_size(const rs_block_cfg *cfg);
+RS_API rs_status rs_pack_weights(const rs_block_cfg *cfg, const rs_block_weights *w,
+                          void *packed_out, void *hip_stream);
+
+/*
+ * One pre-LN encoder block followed by representation-shift pruning
+ * (Eqs. (5),(6) and case (ii) of "Operation choice", Sec. 3.3):
+ *     x1   = SA(LN(x)) + x             SA = fused attention + output projection
+ *     mlp  = W2 GELU(W1 LN(x1) + b1) + b2        (exact-erf GELU)
+ *     xhat = mlp + x1
+ *     scores[b, i] = || mlp[b, i, :] - x1[b, i, :] ||_2      (cfg->dist)
+ *     kept_idx, y  = selection and gather of xhat as in rs_shift_topk.
+ *   x        : [B, N, D] in.            y : [B, K, D] out, must not alias x.
+ *   kept_idx : int32 [B, K] out.        scores : float [B, N] out, or NULL.
+ *   workspace: rs_block_workspace_size(cfg) bytes, 256-byte aligned.
+ * Restrictions: D/H == 64, D % 64 == 0, Dm % 64 == 0; else RS_ERR_UNSUPPORTED.
+ */
+RS_API size_t rs_block_workspace_size(const rs_block_cfg *cfg);
+RS_API rs_status rs_block_fwd(const rs_block_cfg *cfg, const rs_block_weights *w,
+                       const void *x, void *y, int32_t *kept_idx, float *scores,
+                       void *workspace, size_t workspace_bytes, void *hip_stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* RS_H */

@@ -1,0 +1,132 @@
+// Shared device/host helpers of the representation-shift HIP library (gfx950 only).
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "rs.h"
+
+namespace rs {
+
+constexpr int kWave = 64;  // CDNA wavefront width
+
+typedef uint16_t bf16raw;  // bf16 storage: upper half of an fp32
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+
+// ---- bf16 <-> fp32 -------------------------------------------------------
+__device__ __forceinline__ float bf2f(bf16raw b) { return __uint_as_float(((uint32_t)b) << 16); }
+
+// round-to-nearest-even; NaN stays NaN
+__device__ __forceinline__ bf16raw f2bf(float f) {
+    uint32_t u = __float_as_uint(f);
+    if ((u & 0x7fffffffu) > 0x7f800000u) return (bf16raw)0x7fc0;
+    u += 0x7fffu + ((u >> 16) & 1u);
+    return (bf16raw)(u >> 16);
+}
+
+__device__ __forceinline__ uint32_t pack2bf(float lo, float hi) {
+    return (uint32_t)f2bf(lo) | ((uint32_t)f2bf(hi) << 16);
+}
+
+// Storage-type traits: load/store 8 consecutive elements as fp32.
+template <typename T> struct Elem;
+template <> struct Elem<float> {
+    static constexpr rs_dtype dtype = RS_F32;
+    __device__ static __forceinline__ void load8(const float* p, float (&v)[8]) {
+        float4 a = *reinterpret_cast<const float4*>(p);
+        float4 b = *reinterpret_cast<const float4*>(p + 4);
+        v[0] = a.x; v[1] = a.y; v[2] = a.z; v[3] = a.w;
+        v[4] = b.x; v[5] = b.y; v[6] = b.z; v[7] = b.w;
+    }
+    __device__ static __forceinline__ void store8(float* p, const float (&v)[8]) {
+        *reinterpret_cast<float4*>(p) = make_float4(v[0], v[1], v[2], v[3]);
+        *reinterpret_cast<float4*>(p + 4) = make_float4(v[4], v[5], v[6], v[7]);
+    }
+    __device__ static __forceinline__ float ld(const float* p) { return *p; }
+    __device__ static __forceinline__ void st(float* p, float v) { *p = v; }
+};
+template <> struct Elem<bf16raw> {
+    static constexpr rs_dtype dtype = RS_BF16;
+    __device__ static __forceinline__ void load8(const bf16raw* p, float (&v)[8]) {
+        uint4 a = *reinterpret_cast<const uint4*>(p);
+        uint32_t w[4] = {a.x, a.y, a.z, a.w};
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            v[2 * i] = __uint_as_float(w[i] << 16);
+            v[2 * i + 1] = __uint_as_float(w[i] & 0xffff0000u);
+        }
+    }
+    __device__ static __forceinline__ void store8(bf16raw* p, const float (&v)[8]) {
+        uint4 a;
+        a.x = pack2bf(v[0], v[1]); a.y = pack2bf(v[2], v[3]);
+        a.z = pack2bf(v[4], v[5]); a.w = pack2bf(v[6], v[7]);
+        *reinterpret_cast<uint4*>(p) = a;
+    }
+    __device__ static __forceinline__ float ld(const bf16raw* p) { return bf2f(*p); }
+    __device__ static __forceinline__ void st(bf16raw* p, float v) { *p = f2bf(v); }
+};
+
+// ---- wave reductions (fixed butterfly order: deterministic) ---------------
+__device__ __forceinline__ float wave_sum(float v) {
+#pragma unroll
+    for (int off = 32; off >= 1; off >>= 1) v += __shfl_xor(v, off, kWave);
+    return v;
+}
+
+// exact GELU: x * Phi(x)
+__device__ __forceinline__ float gelu_erf(float x) {
+    return 0.5f * x * (1.0f + erff(x * 0.70710678118654752440f));
+}
+
+// ---- host-side error plumbing ---------------------------------------------
+void set_error(const char* fmt, ...);
+rs_status device_error(const char* what, hipError_t e);
+
+inline size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
+inline size_t elem_size(rs_dtype t) { return t == RS_F32 ? 4 : 2; }
+
+// ---- kernel launchers (one per .hip file) -----------------------------------
+// LayerNorm over the last axis of x[M, D]; gamma/beta may be null.
+hipError_t launch_layernorm(rs_dtype dt, const void* x, const void* gamma, const void* beta,
+                            void* out, int64_t M, int D, float eps, hipStream_t s);
+
+enum GemmEpilogue {
+    EPI_BIAS = 0,            // out = acc + bias
+    EPI_BIAS_GELU = 1,       // out = gelu(acc + bias)
+    EPI_BIAS_RES = 2,        // out = acc + bias + res
+    EPI_BIAS_RES_SHIFT = 3   // out = acc + bias + res; partial sums of D(acc + bias, res) per row
+};
+
+// Number of per-row partial slots the SHIFT epilogue writes for an output width N.
+int gemm_shift_slots(rs_dtype dt, int N);
+constexpr int kShiftLanes = 3;  // floats per slot (L2/L1 use the first, cosine all three)
+
+// out[M, N] = epilogue(a[M, K] @ W).  bf16: `w` is the packed [N, K] matrix; fp32: `w` is the
+// caller's [K, N] matrix.  partials: float [M, slots, kShiftLanes] for EPI_BIAS_RES_SHIFT.
+hipError_t launch_gemm(rs_dtype dt, GemmEpilogue epi, rs_dist dist, const void* a, const void* w,
+                       const void* bias, const void* res, void* out, float* partials,
+                       int64_t M, int N, int K, hipStream_t s);
+
+// bf16 [K, N] row-major -> [N, K] row-major.
+hipError_t launch_pack_transpose(const void* w, void* wt, int K, int N, hipStream_t s);
+
+hipError_t launch_attention(rs_dtype dt, const void* q, const void* k, const void* v, void* o,
+                            int B, int H, int N, int64_t sb, int64_t sn, int64_t sh,
+                            int64_t osb, int64_t osn, int64_t osh, float scale, hipStream_t s);
+
+// scores[M] = D(f_out[M, D], f_in[M, D])
+hipError_t launch_shift_scores(rs_dtype dt, rs_dist dist, const void* f_out, const void* f_in,
+                               float* scores, int64_t M, int D, hipStream_t s);
+// scores[M] from the GEMM epilogue's partial slots
+hipError_t launch_finalize_scores(rs_dist dist, const float* partials, int slots, float* scores,
+                                  int64_t M, hipStream_t s);
+// per image: the n_keep highest scores among tokens >= n_prefix, ascending kept_idx[B, K]
+hipError_t launch_select(const float* scores, int32_t* kept_idx, int B, int N, int n_prefix,
+                         int n_keep, hipStream_t s);
+// out[b, j, :] = src[b, kept_idx[b, j], :]
+hipError_t launch_gather(rs_dtype dt, const void* src, const int32_t* kept_idx, void* out, int B,
+                         int N, int K, int D, hipStream_t s);
+
+}  // namespace rs

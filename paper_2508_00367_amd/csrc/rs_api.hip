@@ -1,0 +1,287 @@
+// C ABI of the representation-shift library: argument validation, workspace carving
+// and the launch sequence of the block (Eqs. (5),(6), Sec. 3.3) on the caller's stream.
+// Every argument check happens before the first HIP call, so the error paths run
+// (and are tested) without a GPU.
+#include <stdarg.h>
+#include <stdio.h>
+#include <string.h>
+
+#include "common.hpp"
+
+namespace rs {
+
+static thread_local char g_err[512] = "";
+
+void set_error(const char* fmt, ...) {
+    va_list ap;
+    va_start(ap, fmt);
+    vsnprintf(g_err, sizeof(g_err), fmt, ap);
+    va_end(ap);
+}
+
+rs_status device_error(const char* what, hipError_t e) {
+    set_error("%s: %s", what, hipGetErrorString(e));
+    return RS_ERR_DEVICE;
+}
+
+static bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+#define RS_REQUIRE(cond, status, ...)  \
+    do {                               \
+        if (!(cond)) {                 \
+            rs::set_error(__VA_ARGS__); \
+            return (status);           \
+        }                              \
+    } while (0)
+
+#define RS_LAUNCH(expr)                                          \
+    do {                                                         \
+        hipError_t e_ = (expr);                                  \
+        if (e_ != hipSuccess) return rs::device_error(#expr, e_); \
+    } while (0)
+
+// ---- workspace layout of rs_block_fwd ---------------------------------------
+struct BlockLayout {
+    size_t packed, u, qkv, att, x1, hid, partials, scores, total;
+    int slots;
+};
+
+static size_t packed_bytes(const rs_block_cfg* c) {
+    if (c->dtype != RS_BF16) return 0;
+    const size_t D = c->D, Dm = c->Dm;
+    return align_up((3 * D * D + D * D + 2 * D * Dm) * 2, 256);
+}
+
+static BlockLayout block_layout(const rs_block_cfg* c) {
+    BlockLayout L;
+    const size_t e = elem_size(c->dtype);
+    const size_t M = (size_t)c->B * (size_t)c->N, D = c->D, Dm = c->Dm;
+    L.slots = gemm_shift_slots(c->dtype, c->D);
+    size_t off = 0;
+    auto take = [&](size_t bytes) { size_t o = off; off += align_up(bytes, 256); return o; };
+    L.packed = take(packed_bytes(c));
+    L.u = take(M * D * e);
+    L.qkv = take(M * 3 * D * e);
+    L.att = take(M * D * e);
+    L.x1 = take(M * D * e);
+    L.hid = take(M * Dm * e);
+    L.partials = take(M * (size_t)L.slots * kShiftLanes * sizeof(float));
+    L.scores = take(M * sizeof(float));
+    L.total = off;
+    return L;
+}
+
+static rs_status check_cfg(const rs_block_cfg* c) {
+    RS_REQUIRE(c != nullptr, RS_ERR_INVALID_ARG, "cfg is NULL");
+    RS_REQUIRE(c->dtype == RS_F32 || c->dtype == RS_BF16, RS_ERR_INVALID_ARG, "unknown dtype %d", (int)c->dtype);
+    RS_REQUIRE(c->dist == RS_DIST_L2 || c->dist == RS_DIST_L1 || c->dist == RS_DIST_COS, RS_ERR_INVALID_ARG,
+               "unknown distance %d", (int)c->dist);
+    RS_REQUIRE(c->op == RS_SHIFT_MLP, RS_ERR_INVALID_ARG, "unknown shift operation %d", (int)c->op);
+    RS_REQUIRE(c->B >= 0 && c->N >= 0, RS_ERR_INVALID_ARG, "negative B or N");
+    RS_REQUIRE(c->D > 0 && c->H > 0 && c->Dm > 0, RS_ERR_INVALID_ARG, "D, H, Dm must be positive");
+    RS_REQUIRE(c->D % c->H == 0, RS_ERR_INVALID_ARG, "D %d not divisible by H %d", c->D, c->H);
+    RS_REQUIRE(c->D / c->H == 64, RS_ERR_UNSUPPORTED, "head width D/H = %d, only 64 is built", c->D / c->H);
+    RS_REQUIRE(c->Dm % 64 == 0, RS_ERR_UNSUPPORTED, "Dm %d is not a multiple of 64", c->Dm);
+    RS_REQUIRE(c->D <= 4096, RS_ERR_UNSUPPORTED, "D %d > 4096", c->D);
+    RS_REQUIRE((int64_t)c->B * c->N < (int64_t)1 << 31, RS_ERR_UNSUPPORTED, "B*N does not fit 31 bits");
+    RS_REQUIRE(c->n_prefix >= 0 && c->n_keep >= 0, RS_ERR_INVALID_ARG, "negative n_prefix or n_keep");
+    RS_REQUIRE((int64_t)c->n_prefix + c->n_keep <= c->N, RS_ERR_INVALID_ARG,
+               "n_prefix %d + n_keep %d exceeds N %d", c->n_prefix, c->n_keep, c->N);
+    RS_REQUIRE(c->ln_eps > 0.f, RS_ERR_INVALID_ARG, "ln_eps must be positive");
+    return RS_OK;
+}
+
+}  // namespace rs
+
+using namespace rs;
+
+extern "C" {
+
+const char* rs_last_error(void) { return g_err; }
+
+int32_t rs_version(void) { return 100; }
+
+rs_status rs_attention_fwd(const void* q, const void* k, const void* v, void* o, int32_t B, int32_t H,
+                           int32_t N, int32_t dh, int64_t stride_b, int64_t stride_n, int64_t stride_h,
+                           int64_t o_stride_b, int64_t o_stride_n, int64_t o_stride_h, float scale,
+                           rs_dtype dtype, void* hip_stream) {
+    RS_REQUIRE(dtype == RS_F32 || dtype == RS_BF16, RS_ERR_INVALID_ARG, "unknown dtype %d", (int)dtype);
+    RS_REQUIRE(B >= 0 && H >= 0 && N >= 0, RS_ERR_INVALID_ARG, "negative B, H or N");
+    RS_REQUIRE(dh > 0, RS_ERR_INVALID_ARG, "dh must be positive");
+    RS_REQUIRE(dh == 64, RS_ERR_UNSUPPORTED, "head width %d, only 64 is built", dh);
+    RS_REQUIRE(B <= 65535 && H <= 65535, RS_ERR_UNSUPPORTED, "B and H are limited to 65535");
+    RS_REQUIRE(scale > 0.f && scale < INFINITY, RS_ERR_INVALID_ARG, "scale must be positive and finite");
+    if (B == 0 || H == 0 || N == 0) return RS_OK;
+    RS_REQUIRE(q && k && v && o, RS_ERR_INVALID_ARG, "q, k, v and o must not be NULL");
+    RS_REQUIRE(aligned16(q) && aligned16(k) && aligned16(v) && aligned16(o), RS_ERR_INVALID_ARG,
+               "q, k, v and o must be 16-byte aligned");
+    RS_REQUIRE(o != q && o != k && o != v, RS_ERR_INVALID_ARG, "o must not alias q, k or v");
+    const int64_t st[6] = {stride_b, stride_n, stride_h, o_stride_b, o_stride_n, o_stride_h};
+    for (int i = 0; i < 6; ++i)
+        RS_REQUIRE(st[i] >= 0 && st[i] % 8 == 0, RS_ERR_INVALID_ARG,
+                   "strides must be non-negative multiples of 8 elements");
+    RS_REQUIRE(stride_n >= dh && o_stride_n >= dh, RS_ERR_INVALID_ARG, "token stride smaller than dh");
+    RS_LAUNCH(launch_attention(dtype, q, k, v, o, B, H, N, stride_b, stride_n, stride_h, o_stride_b,
+                               o_stride_n, o_stride_h, scale, (hipStream_t)hip_stream));
+    return RS_OK;
+}
+
+size_t rs_shift_topk_workspace_size(int32_t B, int32_t N, int32_t D, rs_dtype dtype) {
+    (void)B; (void)N; (void)D; (void)dtype;
+    return 0;
+}
+
+rs_status rs_shift_topk(const void* f_out, const void* f_in, const void* src, int32_t B, int32_t N,
+                        int32_t D, int32_t n_prefix, int32_t n_keep, rs_dist dist, rs_dtype dtype,
+                        float* scores, int32_t* kept_idx, void* gathered, void* workspace,
+                        size_t workspace_bytes, void* hip_stream) {
+    (void)workspace;
+    RS_REQUIRE(dtype == RS_F32 || dtype == RS_BF16, RS_ERR_INVALID_ARG, "unknown dtype %d", (int)dtype);
+    RS_REQUIRE(dist == RS_DIST_L2 || dist == RS_DIST_L1 || dist == RS_DIST_COS, RS_ERR_INVALID_ARG,
+               "unknown distance %d", (int)dist);
+    RS_REQUIRE(B >= 0 && N >= 0, RS_ERR_INVALID_ARG, "negative B or N");
+    RS_REQUIRE(D > 0 && D % 8 == 0, RS_ERR_INVALID_ARG, "D must be a positive multiple of 8");
+    RS_REQUIRE(n_prefix >= 0 && n_keep >= 0 && (int64_t)n_prefix + n_keep <= N, RS_ERR_INVALID_ARG,
+               "need 0 <= n_prefix, 0 <= n_keep, n_prefix + n_keep <= N");
+    RS_REQUIRE((int64_t)B * N < (int64_t)1 << 31, RS_ERR_UNSUPPORTED, "B*N does not fit 31 bits");
+    RS_REQUIRE(workspace_bytes >= rs_shift_topk_workspace_size(B, N, D, dtype), RS_ERR_WORKSPACE_TOO_SMALL,
+               "workspace too small");
+    if (B == 0 || N == 0) return RS_OK;
+    RS_REQUIRE(f_out && f_in && scores, RS_ERR_INVALID_ARG, "f_out, f_in and scores must not be NULL");
+    RS_REQUIRE(kept_idx || n_prefix + n_keep == 0, RS_ERR_INVALID_ARG, "kept_idx must not be NULL");
+    const void* s = src ? src : f_in;
+    RS_REQUIRE(aligned16(f_out) && aligned16(f_in) && aligned16(s) && aligned16(gathered), RS_ERR_INVALID_ARG,
+               "tensors must be 16-byte aligned");
+    RS_REQUIRE(gathered == nullptr || gathered != s, RS_ERR_INVALID_ARG, "gathered must not alias src");
+    hipStream_t st = (hipStream_t)hip_stream;
+    const int K = n_prefix + n_keep;
+    RS_LAUNCH(launch_shift_scores(dtype, dist, f_out, f_in, scores, (int64_t)B * N, D, st));
+    RS_LAUNCH(launch_select(scores, kept_idx, B, N, n_prefix, n_keep, st));
+    if (gathered) RS_LAUNCH(launch_gather(dtype, s, kept_idx, gathered, B, N, K, D, st));
+    return RS_OK;
+}
+
+size_t rs_packed_weights_size(const rs_block_cfg* cfg) {
+    if (!cfg || cfg->D <= 0 || cfg->Dm <= 0) return 0;
+    return packed_bytes(cfg);
+}
+
+static rs_status pack_into(const rs_block_cfg* c, const rs_block_weights* w, void* dst, hipStream_t st) {
+    const size_t D = c->D, Dm = c->Dm;
+    char* p = (char*)dst;
+    RS_LAUNCH(launch_pack_transpose(w->w_qkv, p, c->D, 3 * c->D, st));
+    p += 3 * D * D * 2;
+    RS_LAUNCH(launch_pack_transpose(w->w_proj, p, c->D, c->D, st));
+    p += D * D * 2;
+    RS_LAUNCH(launch_pack_transpose(w->w_fc1, p, c->D, c->Dm, st));
+    p += D * Dm * 2;
+    RS_LAUNCH(launch_pack_transpose(w->w_fc2, p, c->Dm, c->D, st));
+    return RS_OK;
+}
+
+static rs_status check_weights(const rs_block_weights* w) {
+    RS_REQUIRE(w != nullptr, RS_ERR_INVALID_ARG, "weights is NULL");
+    RS_REQUIRE(w->w_qkv && w->w_proj && w->w_fc1 && w->w_fc2, RS_ERR_INVALID_ARG,
+               "w_qkv, w_proj, w_fc1 and w_fc2 must not be NULL");
+    const void* all[] = {w->ln1_g, w->ln1_b, w->w_qkv, w->b_qkv, w->w_proj, w->b_proj, w->ln2_g,
+                         w->ln2_b, w->w_fc1, w->b_fc1, w->w_fc2, w->b_fc2, w->packed};
+    for (const void* p : all) RS_REQUIRE(aligned16(p), RS_ERR_INVALID_ARG, "weight pointers must be 16-byte aligned");
+    return RS_OK;
+}
+
+rs_status rs_pack_weights(const rs_block_cfg* cfg, const rs_block_weights* w, void* packed_out,
+                          void* hip_stream) {
+    RS_REQUIRE(cfg != nullptr, RS_ERR_INVALID_ARG, "cfg is NULL");
+    RS_REQUIRE(cfg->D > 0 && cfg->Dm > 0 && cfg->D % 64 == 0 && cfg->Dm % 64 == 0, RS_ERR_INVALID_ARG,
+               "D and Dm must be positive multiples of 64");
+    RS_REQUIRE(cfg->dtype == RS_F32 || cfg->dtype == RS_BF16, RS_ERR_INVALID_ARG, "unknown dtype");
+    rs_status s = check_weights(w);
+    if (s != RS_OK) return s;
+    if (cfg->dtype == RS_F32) return RS_OK;  // the fp32 path reads the caller's layout
+    RS_REQUIRE(packed_out != nullptr && aligned16(packed_out), RS_ERR_INVALID_ARG,
+               "packed_out must be a 16-byte aligned buffer");
+    return pack_into(cfg, w, packed_out, (hipStream_t)hip_stream);
+}
+
+size_t rs_block_workspace_size(const rs_block_cfg* cfg) {
+    if (check_cfg(cfg) != RS_OK) return 0;
+    return block_layout(cfg).total;
+}
+
+rs_status rs_block_fwd(const rs_block_cfg* cfg, const rs_block_weights* w, const void* x, void* y,
+                       int32_t* kept_idx, float* scores, void* workspace, size_t workspace_bytes,
+                       void* hip_stream) {
+    rs_status st = check_cfg(cfg);
+    if (st != RS_OK) return st;
+    st = check_weights(w);
+    if (st != RS_OK) return st;
+    const rs_block_cfg& c = *cfg;
+    if (c.B == 0 || c.N == 0) return RS_OK;  // nothing to do, nothing touched
+    const BlockLayout L = block_layout(cfg);
+    RS_REQUIRE(workspace_bytes >= L.total, RS_ERR_WORKSPACE_TOO_SMALL,
+               "workspace has %zu bytes, rs_block_workspace_size needs %zu", workspace_bytes, L.total);
+    const int K = c.n_prefix + c.n_keep;
+    RS_REQUIRE(x != nullptr, RS_ERR_INVALID_ARG, "x is NULL");
+    RS_REQUIRE(K == 0 || (y != nullptr && kept_idx != nullptr), RS_ERR_INVALID_ARG, "y and kept_idx must not be NULL");
+    RS_REQUIRE(workspace != nullptr, RS_ERR_INVALID_ARG, "workspace is NULL");
+    RS_REQUIRE((reinterpret_cast<uintptr_t>(workspace) & 255u) == 0, RS_ERR_INVALID_ARG,
+               "workspace must be 256-byte aligned");
+    RS_REQUIRE(aligned16(x) && aligned16(y), RS_ERR_INVALID_ARG, "x and y must be 16-byte aligned");
+    RS_REQUIRE(x != y, RS_ERR_INVALID_ARG, "y must not alias x");
+
+    hipStream_t s = (hipStream_t)hip_stream;
+    char* ws = (char*)workspace;
+    const rs_dtype dt = c.dtype;
+    const int64_t M = (int64_t)c.B * c.N;
+    const int D = c.D, Dm = c.Dm;
+    void* u = ws + L.u;
+    void* qkv = ws + L.qkv;
+    void* att = ws + L.att;
+    void* x1 = ws + L.x1;
+    void* hid = ws + L.hid;
+    float* partials = (float*)(ws + L.partials);
+    const bool prune = c.n_keep < c.N - c.n_prefix;
+    const bool want_scores = prune || scores != nullptr;
+    float* sc = scores ? scores : (float*)(ws + L.scores);
+
+    // weights as the GEMMs read them
+    const void *wq = w->w_qkv, *wp = w->w_proj, *w1 = w->w_fc1, *w2 = w->w_fc2;
+    if (dt == RS_BF16) {
+        const char* pk = (const char*)w->packed;
+        if (!pk) {
+            st = pack_into(cfg, w, ws + L.packed, s);
+            if (st != RS_OK) return st;
+            pk = ws + L.packed;
+        }
+        const size_t Ds = D, Dms = Dm;
+        wq = pk;
+        wp = pk + 3 * Ds * Ds * 2;
+        w1 = pk + 4 * Ds * Ds * 2;
+        w2 = pk + (4 * Ds * Ds + Ds * Dms) * 2;
+    }
+    const float scale = c.attn_scale > 0.f ? c.attn_scale : 0.125f;  // 1/sqrt(64)
+
+    // x1 = SA(LN(x)) + x                                                     Eq. (5)
+    RS_LAUNCH(launch_layernorm(dt, x, w->ln1_g, w->ln1_b, u, M, D, c.ln_eps, s));
+    RS_LAUNCH(launch_gemm(dt, EPI_BIAS, RS_DIST_L2, u, wq, w->b_qkv, nullptr, qkv, nullptr, M, 3 * D, D, s));
+    {
+        const size_t e = elem_size(dt);
+        const char* qp = (const char*)qkv;
+        RS_LAUNCH(launch_attention(dt, qp, qp + (size_t)D * e, qp + 2 * (size_t)D * e, att, c.B, c.H, c.N,
+                                   (int64_t)c.N * 3 * D, 3 * D, 64, (int64_t)c.N * D, D, 64, scale, s));
+    }
+    RS_LAUNCH(launch_gemm(dt, EPI_BIAS_RES, RS_DIST_L2, att, wp, w->b_proj, x, x1, nullptr, M, D, D, s));
+    // xhat = MLP(LN(x1)) + x1, with the shift partial sums of D(MLP(LN(x1)), x1)   Eq. (6), Eq. (4)
+    RS_LAUNCH(launch_layernorm(dt, x1, w->ln2_g, w->ln2_b, u, M, D, c.ln_eps, s));
+    RS_LAUNCH(launch_gemm(dt, EPI_BIAS_GELU, RS_DIST_L2, u, w1, w->b_fc1, nullptr, hid, nullptr, M, Dm, D, s));
+    void* xhat = prune ? att : y;  // without pruning the block output goes straight to y
+    RS_LAUNCH(launch_gemm(dt, want_scores ? EPI_BIAS_RES_SHIFT : EPI_BIAS_RES, c.dist, hid, w2, w->b_fc2, x1,
+                          xhat, partials, M, D, Dm, s));
+    if (want_scores) RS_LAUNCH(launch_finalize_scores(c.dist, partials, L.slots, sc, M, s));
+    // keep the n_keep highest-shift tokens (plus the prefix) and compact them
+    RS_LAUNCH(launch_select(sc, kept_idx, c.B, c.N, c.n_prefix, c.n_keep, s));
+    if (prune) RS_LAUNCH(launch_gather(dt, xhat, kept_idx, y, c.B, c.N, K, D, s));
+    return RS_OK;
+}
+
+}  // extern "C"

@@ -1,0 +1,160 @@
+"""Host-side checks of the C ABI that need no GPU: the library loads, exports every symbol
+the header declares, and rejects bad arguments before touching a device."""
+import ctypes
+import os
+import re
+
+import paper_2508_00367_amd as rs
+from paper_2508_00367_amd import binding
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def _declared():
+    text = open(os.path.join(ROOT, "include", "rs.h")).read()
+    return sorted(set(re.findall(r"RS_API[^;(]*?\b(rs_\w+)\s*\(", text)))
+
+
+def test_header_symbols_exported():
+    names = _declared()
+    assert len(names) >= 9
+    L = rs.lib()
+    for n in names:
+        assert hasattr(L, n), n
+    assert set(names) == set(binding.EXPORTS)
+    assert rs.rs_version() >= 100
+
+
+def test_struct_layouts_match_header():
+    # 13 pointers; 7 int32 + 2 float + 3 enums
+    assert ctypes.sizeof(binding.RsBlockWeights) == 13 * 8
+    assert ctypes.sizeof(binding.RsBlockCfg) == 12 * 4
+
+
+def _cfg(**kw):
+    base = dict(B=2, N=10, D=128, H=2, Dm=256, n_prefix=1, n_keep=4, dtype=rs.RS_BF16)
+    base.update(kw)
+    return rs.make_cfg(**base)
+
+
+FAKE = 0x1000  # aligned, never dereferenced: every check below fails before any launch
+
+
+def _weights(**kw):
+    w = binding.RsBlockWeights()
+    for name, _ in binding.RsBlockWeights._fields_:
+        setattr(w, name, FAKE)
+    for k, v in kw.items():
+        setattr(w, k, v)
+    return w
+
+
+def test_block_rejects_bad_config():
+    w = _weights()
+    for kw, want in [(dict(H=3), rs.RS_ERR_INVALID_ARG),           # D not divisible by H
+                     (dict(D=256, H=2), rs.RS_ERR_UNSUPPORTED),    # head width 128
+                     (dict(Dm=100), rs.RS_ERR_UNSUPPORTED),
+                     (dict(n_keep=10), rs.RS_ERR_INVALID_ARG),     # prefix + keep > N
+                     (dict(n_prefix=-1), rs.RS_ERR_INVALID_ARG),
+                     (dict(ln_eps=0.0), rs.RS_ERR_INVALID_ARG),
+                     (dict(dtype=7), rs.RS_ERR_INVALID_ARG),
+                     (dict(dist=9), rs.RS_ERR_INVALID_ARG),
+                     (dict(B=-1), rs.RS_ERR_INVALID_ARG)]:
+        cfg = _cfg(**kw)
+        st = rs.lib().rs_block_fwd(ctypes.byref(cfg), ctypes.byref(w), FAKE, FAKE * 2, FAKE * 3, None,
+                                   FAKE * 16, 1 << 40, None)
+        assert st == want, (kw, rs.rs_last_error())
+        assert rs.rs_last_error() != ""
+        assert rs.rs_block_workspace_size(cfg) == 0
+
+
+def test_block_rejects_bad_pointers_and_workspace():
+    cfg = _cfg()
+    need = rs.rs_block_workspace_size(cfg)
+    assert need > 0
+    L = rs.lib()
+
+    def call(w, x, y, kept, ws, ws_bytes):
+        return L.rs_block_fwd(ctypes.byref(cfg), ctypes.byref(w), x, y, kept, None, ws, ws_bytes, None)
+
+    w = _weights()
+    assert call(w, FAKE, 2 * FAKE, 3 * FAKE, 16 * FAKE, need - 1) == rs.RS_ERR_WORKSPACE_TOO_SMALL
+    assert "workspace" in rs.rs_last_error()
+    assert call(w, None, 2 * FAKE, 3 * FAKE, 16 * FAKE, need) == rs.RS_ERR_INVALID_ARG
+    assert call(w, FAKE, None, 3 * FAKE, 16 * FAKE, need) == rs.RS_ERR_INVALID_ARG
+    assert call(w, FAKE, 2 * FAKE, None, 16 * FAKE, need) == rs.RS_ERR_INVALID_ARG
+    assert call(w, FAKE, FAKE, 3 * FAKE, 16 * FAKE, need) == rs.RS_ERR_INVALID_ARG       # y aliases x
+    assert call(w, FAKE + 4, 2 * FAKE, 3 * FAKE, 16 * FAKE, need) == rs.RS_ERR_INVALID_ARG  # misaligned
+    assert call(w, FAKE, 2 * FAKE, 3 * FAKE, None, need) == rs.RS_ERR_INVALID_ARG
+    assert call(w, FAKE, 2 * FAKE, 3 * FAKE, 16 * FAKE + 16, need) == rs.RS_ERR_INVALID_ARG  # ws alignment
+    assert call(_weights(w_fc1=None), FAKE, 2 * FAKE, 3 * FAKE, 16 * FAKE, need) == rs.RS_ERR_INVALID_ARG
+    assert L.rs_block_fwd(None, ctypes.byref(w), FAKE, FAKE, FAKE, None, FAKE, need, None) == rs.RS_ERR_INVALID_ARG
+    assert L.rs_block_fwd(ctypes.byref(cfg), None, FAKE, 2 * FAKE, FAKE, None, FAKE, need, None) == rs.RS_ERR_INVALID_ARG
+    # empty batch is a successful no-op that never reaches the device
+    cfg0 = _cfg(B=0)
+    assert L.rs_block_fwd(ctypes.byref(cfg0), ctypes.byref(w), None, None, None, None, None, 0, None) == rs.RS_OK
+
+
+def test_attention_rejects_bad_arguments():
+    L = rs.lib()
+
+    def call(q=FAKE, k=2 * FAKE, v=3 * FAKE, o=4 * FAKE, B=1, H=1, N=4, dh=64, sn=64, scale=0.125, dt=rs.RS_BF16):
+        return L.rs_attention_fwd(q, k, v, o, B, H, N, dh, N * sn, sn, 64, N * sn, sn, 64, scale, dt, None)
+
+    assert call(dh=128) == rs.RS_ERR_UNSUPPORTED
+    assert call(dh=0) == rs.RS_ERR_INVALID_ARG
+    assert call(q=None) == rs.RS_ERR_INVALID_ARG
+    assert call(o=FAKE) == rs.RS_ERR_INVALID_ARG          # aliases q
+    assert call(q=FAKE + 2) == rs.RS_ERR_INVALID_ARG
+    assert call(sn=60) == rs.RS_ERR_INVALID_ARG
+    assert call(scale=0.0) == rs.RS_ERR_INVALID_ARG
+    assert call(dt=5) == rs.RS_ERR_INVALID_ARG
+    assert call(B=-2) == rs.RS_ERR_INVALID_ARG
+    assert call(N=0) == rs.RS_OK and call(B=0, q=None) == rs.RS_OK
+    assert "stride" in rs.rs_last_error() or rs.rs_last_error() != ""
+
+
+def test_shift_topk_rejects_bad_arguments():
+    L = rs.lib()
+
+    def call(fo=FAKE, fi=2 * FAKE, src=None, B=2, N=8, D=64, P=1, K=3, dist=0, dt=rs.RS_BF16,
+             sc=3 * FAKE, kept=4 * FAKE, g=5 * FAKE):
+        return L.rs_shift_topk(fo, fi, src, B, N, D, P, K, dist, dt, sc, kept, g, None, 0, None)
+
+    assert call(D=60) == rs.RS_ERR_INVALID_ARG
+    assert call(P=5, K=4) == rs.RS_ERR_INVALID_ARG
+    assert call(K=-1) == rs.RS_ERR_INVALID_ARG
+    assert call(fo=None) == rs.RS_ERR_INVALID_ARG
+    assert call(sc=None) == rs.RS_ERR_INVALID_ARG
+    assert call(kept=None) == rs.RS_ERR_INVALID_ARG
+    assert call(g=2 * FAKE) == rs.RS_ERR_INVALID_ARG       # gathered aliases src (= f_in)
+    assert call(dist=4) == rs.RS_ERR_INVALID_ARG
+    assert call(B=0, fo=None) == rs.RS_OK
+
+
+def test_pack_weights_validation():
+    cfg = _cfg()
+    assert rs.rs_packed_weights_size(cfg) == (3 * 128 * 128 + 128 * 128 + 2 * 128 * 256) * 2
+    L = rs.lib()
+    w = _weights()
+    assert L.rs_pack_weights(ctypes.byref(cfg), ctypes.byref(w), None, None) == rs.RS_ERR_INVALID_ARG
+    assert L.rs_pack_weights(ctypes.byref(cfg), None, FAKE, None) == rs.RS_ERR_INVALID_ARG
+    cfg32 = _cfg(dtype=rs.RS_F32)
+    assert rs.rs_packed_weights_size(cfg32) == 0
+    assert L.rs_pack_weights(ctypes.byref(cfg32), ctypes.byref(w), None, None) == rs.RS_OK
+
+
+def test_schedule_matches_workload_statement():
+    import synth_inputs as si
+    kc = rs.keep_counts(197, 1, 12, si.WORKLOADS["vit_b16"]["prune"])
+    assert [n for n, _ in kc] == [197, 197, 197, 197, 178, 161, 145, 131, 118, 107, 97, 88]
+    assert kc[3] == (197, 177) and kc[11] == (88, 87)
+    kc = rs.keep_counts(197, 1, 1, si.WORKLOADS["vit_block_fp32"]["prune"])
+    assert kc == [(197, 138)]
+    lin, att = rs.forward_flops(197, 1, 768, 3072, 12, si.WORKLOADS["vit_b16"]["prune"])
+    assert abs(lin / 1e9 - 25.664) < 1e-3 and abs(att / 1e9 - 0.902) < 1e-3
+    # the product's schedule and the checker's agree (two independent implementations)
+    from oracle import schedule as osch
+    for name, wl in si.WORKLOADS.items():
+        ours = [n for n, _ in rs.keep_counts(wl["N"], 1, wl["blocks"], wl["prune"])]
+        assert ours == osch.tokens_per_block(wl["N"], 1, wl["blocks"], wl["prune"]), name

@@ -1,0 +1,272 @@
+"""GPU parity: the HIP path (through the C ABI) against the fp64 CPU checker, element by
+element, on the same seeded inputs.  Tolerances: tensor-normalised max error 1e-4 (fp32),
+2e-2 (bf16); indices bit-exact, with the tie-band rule where scores differ by rounding."""
+import math
+import sys
+
+import numpy as np
+import pytest
+import torch
+
+import oracle
+import paper_2508_00367_amd as rs
+import synth_inputs as si
+from rs_testlib import TOL, check_kept_admissible, host_round, norm_err, to_dev, to_host
+
+pytestmark = pytest.mark.gpu
+
+
+def _say(*a):
+    print(*a, flush=True)
+    sys.stdout.flush()
+
+
+# ----------------------------------------------------------------------------
+# fused attention
+# ----------------------------------------------------------------------------
+ATT_SHAPES = [(1, 1, 1), (1, 2, 1), (2, 17, 3), (1, 64, 2), (1, 65, 1), (2, 197, 3), (1, 198, 2),
+              (1, 300, 2), (1, 1569, 1)]
+
+
+@pytest.mark.parametrize("dtype", ["bf16", "f32"])
+@pytest.mark.parametrize("B,N,H", ATT_SHAPES)
+def test_attention_packed_qkv(dtype, B, N, H):
+    """q, k, v as strided views of one [B, N, 3, H, 64] buffer (the block's layout)."""
+    _say("attention", dtype, B, N, H)
+    qkv = host_round(si.generic(0, 1, (B, N, 3, H, 64)), dtype)
+    scale = 0.125
+    ref = oracle.attention(qkv[:, :, 0], qkv[:, :, 1], qkv[:, :, 2], scale)
+    d = to_dev(qkv, dtype)
+    o = torch.full((B, N, H, 64), float("nan"), device="cuda", dtype=d.dtype)
+    rs.rs_attention_fwd(d[:, :, 0], d[:, :, 1], d[:, :, 2], o, scale)
+    torch.cuda.synchronize()
+    err = norm_err(to_host(o), ref)
+    _say("  err", err)
+    assert err < TOL[dtype]
+
+
+@pytest.mark.parametrize("dtype", ["bf16", "f32"])
+def test_attention_large_logits_and_separate_tensors(dtype):
+    B, N, H = 1, 130, 2
+    q = host_round(si.generic(1, 2, (B, N, H, 64), std=6.0), dtype)
+    k = host_round(si.generic(1, 3, (B, N, H, 64), std=6.0), dtype)
+    v = host_round(si.generic(1, 4, (B, N, H, 64)), dtype)
+    scale = 1.0 / math.sqrt(64.0)
+    ref = oracle.attention(q, k, v, scale)
+    o = torch.empty((B, N, H, 64), device="cuda", dtype=to_dev(q, dtype).dtype)
+    rs.rs_attention_fwd(to_dev(q, dtype), to_dev(k, dtype), to_dev(v, dtype), o, scale)
+    torch.cuda.synchronize()
+    got = to_host(o)
+    assert np.isfinite(got).all()
+    assert norm_err(got, ref) < TOL[dtype]
+
+
+def test_attention_closed_forms_on_gpu():
+    # identical keys -> mean of V; V = 1 -> 1
+    B, N, H = 1, 100, 1
+    q = host_round(si.generic(2, 5, (B, N, H, 64)), "bf16")
+    k = np.broadcast_to(host_round(si.generic(2, 6, (B, 1, H, 64)), "bf16"), q.shape).copy()
+    v = host_round(si.generic(2, 7, (B, N, H, 64)), "bf16")
+    o = torch.empty((B, N, H, 64), device="cuda", dtype=torch.bfloat16)
+    rs.rs_attention_fwd(to_dev(q, "bf16"), to_dev(k, "bf16"), to_dev(v, "bf16"), o, 0.125)
+    torch.cuda.synchronize()
+    assert norm_err(to_host(o), np.broadcast_to(v.astype(np.float64).mean(1, keepdims=True), v.shape)) < 1e-2
+    ones = torch.ones((B, N, H, 64), device="cuda", dtype=torch.bfloat16)
+    rs.rs_attention_fwd(to_dev(q, "bf16"), to_dev(k, "bf16"), ones, o, 0.125)
+    torch.cuda.synchronize()
+    assert np.abs(to_host(o) - 1.0).max() < 1e-2
+
+
+# ----------------------------------------------------------------------------
+# shift score + selection + gather
+# ----------------------------------------------------------------------------
+def _run_shift_topk(f_out, f_in, src, P, K, dist, dtype):
+    B, N, D = f_in.shape
+    d_out, d_in = to_dev(f_out, dtype), to_dev(f_in, dtype)
+    d_src = None if src is None else to_dev(src, dtype)
+    scores = torch.full((B, N), float("nan"), device="cuda", dtype=torch.float32)
+    kept = torch.full((B, P + K), -1, device="cuda", dtype=torch.int32)
+    gathered = torch.full((B, P + K, D), float("nan"), device="cuda", dtype=d_in.dtype)
+    rs.rs_shift_topk(d_out, d_in, d_src, P, K, scores, kept, gathered, dist=dist)
+    torch.cuda.synchronize()
+    return to_host(scores), kept.cpu().numpy(), to_host(gathered)
+
+
+SHIFT_CASES = [  # B, N, D, n_prefix, n_keep
+    (3, 17, 64, 1, 7), (2, 197, 192, 1, 138), (4, 197, 768, 1, 177), (1, 4097, 1024, 1, 2868),
+    (2, 1, 64, 1, 0), (2, 5, 72, 0, 5), (2, 300, 384, 2, 1), (1, 1000, 8, 0, 0), (5, 263, 2056, 3, 100)]
+
+
+@pytest.mark.parametrize("dtype", ["bf16", "f32"])
+@pytest.mark.parametrize("dist", [rs.RS_DIST_L2, rs.RS_DIST_L1, rs.RS_DIST_COS])
+@pytest.mark.parametrize("B,N,D,P,K", SHIFT_CASES)
+def test_shift_topk(dtype, dist, B, N, D, P, K):
+    _say("shift_topk", dtype, dist, B, N, D, P, K)
+    f_in = host_round(si.tokens(0, B, N, D, spread=0.5), dtype)
+    f_out = host_round(f_in + si.generic(0, 8, (B, N, D), std=0.3) * np.exp(si.generic(0, 9, (B, N, 1), std=0.7)), dtype)
+    src = host_round(si.generic(0, 10, (B, N, D)), dtype)
+    s_ref, kept_ref, g_ref = oracle.shift_topk(f_out, f_in, src, P, K, dist)
+    s, kept, g = _run_shift_topk(f_out, f_in, src, P, K, dist, dtype)
+    assert norm_err(s, s_ref) < 1e-5  # inputs identical on both sides, fp32 accumulation
+    # selection is exact on the GPU's own scores (integer work: bit-exact) ...
+    np.testing.assert_array_equal(kept, oracle.topk(s, P, K))
+    # ... and agrees with the checker's selection outside the rounding band
+    check_kept_admissible(kept, s, s_ref, P, K)
+    # gather is a copy of the selected rows
+    np.testing.assert_array_equal(g, oracle.gather(src, kept))
+
+
+@pytest.mark.parametrize("dtype", ["bf16", "f32"])
+def test_shift_topk_exact_ties(dtype):
+    """Small-integer data: scores are exact in fp32 and heavily tied, so kept_idx must
+    equal the checker's bit for bit (lower index wins a tie)."""
+    B, N, D, P, K = 4, 197, 64, 1, 100
+    rng = np.random.default_rng(7)
+    f_in = rng.integers(-3, 4, size=(B, N, D)).astype(np.float32)
+    delta = np.zeros((B, N, D), np.float32)
+    delta[:, :, :4] = rng.integers(0, 3, size=(B, N, 4))
+    f_out = f_in + delta
+    for dist in (rs.RS_DIST_L2, rs.RS_DIST_L1):
+        s_ref, kept_ref, g_ref = oracle.shift_topk(f_out, f_in, None, P, K, dist)
+        s, kept, g = _run_shift_topk(f_out, f_in, None, P, K, dist, dtype)
+        np.testing.assert_allclose(s, s_ref, rtol=1e-6)
+        np.testing.assert_array_equal(kept, kept_ref)
+        np.testing.assert_array_equal(g, g_ref)
+    # all-equal scores: lowest indices
+    s, kept, g = _run_shift_topk(f_in + 1.0, f_in, None, 1, 10, rs.RS_DIST_L2, dtype)
+    np.testing.assert_array_equal(kept, np.tile(np.arange(11), (B, 1)))
+    # identity sub-layer: zero shift
+    s, kept, g = _run_shift_topk(f_in, f_in, None, 1, 10, rs.RS_DIST_L2, dtype)
+    assert (s == 0).all()
+
+
+# ----------------------------------------------------------------------------
+# whole block
+# ----------------------------------------------------------------------------
+def _block_inputs(seed, B, N, D, Dm, dtype, block=0, std=0.02, spread=0.0, affine_ln=False):
+    x = host_round(si.tokens(seed, B, N, D, spread), dtype)
+    w = {k: host_round(v, dtype) for k, v in si.block_weights(seed, block, D, Dm, std).items()}
+    if affine_ln:
+        for i, k in enumerate(("ln1_g", "ln1_b", "ln2_g", "ln2_b")):
+            base = 1.0 if k.endswith("_g") else 0.0
+            w[k] = host_round(base + si.generic(seed, 20 + i, (D,), std=0.2), dtype)
+    return x, w
+
+
+def _run_block(x, w, H, P, K, dtype, dist=rs.RS_DIST_L2, want_scores=True, pack=False, ln_eps=1e-6):
+    B, N, D = x.shape
+    Dm = w["w_fc1"].shape[1]
+    dw = {k: to_dev(v, dtype) for k, v in w.items()}
+    dx = to_dev(x, dtype)
+    cfg = rs.make_cfg(B, N, D, H, Dm, P, K, dx.dtype, ln_eps=ln_eps, dist=dist)
+    packed = None
+    if pack and dtype == "bf16":
+        packed = torch.empty(rs.rs_packed_weights_size(cfg), dtype=torch.uint8, device="cuda")
+        rs.rs_pack_weights(cfg, rs.make_weights(dw), packed)
+    ws = torch.empty(rs.rs_block_workspace_size(cfg), dtype=torch.uint8, device="cuda")
+    y = torch.full((B, P + K, D), float("nan"), device="cuda", dtype=dx.dtype)
+    kept = torch.full((B, P + K), -1, device="cuda", dtype=torch.int32)
+    scores = torch.full((B, N), float("nan"), device="cuda", dtype=torch.float32) if want_scores else None
+    rs.rs_block_fwd(cfg, rs.make_weights(dw, packed), dx, y, kept, scores, ws)
+    torch.cuda.synchronize()
+    return y, kept, scores
+
+
+def _check_block(x, w, H, P, K, dtype, dist=rs.RS_DIST_L2, **kw):
+    y, kept, scores = _run_block(x, w, H, P, K, dtype, dist=dist, **kw)
+    ref = oracle.block(x, w, H, ln_eps=kw.get("ln_eps", 1e-6), dist=dist)
+    s, kept_h = to_host(scores), kept.cpu().numpy()
+    e_s = norm_err(s, ref["scores"])
+    exact = check_kept_admissible(kept_h, s, ref["scores"], P, K)
+    # teacher forcing: compare the compacted rows on the GPU's own kept set
+    e_y = norm_err(to_host(y), oracle.gather(ref["xhat"], kept_h))
+    _say("  score err %.3e  y err %.3e  kept exact on %.0f%% of images" % (e_s, e_y, 100 * exact))
+    assert e_s < TOL[dtype] and e_y < TOL[dtype]
+    np.testing.assert_array_equal(kept_h, oracle.topk(s, P, K))  # selection exact on the GPU's scores
+    return exact
+
+
+def test_block_fp32_config1():
+    """Single ViT block, fp32: batch 4, 197 tokens, D 192, 3 heads, MLP 768, drop 30% of the
+    non-class tokens (196 -> 138)."""
+    wl = si.WORKLOADS["vit_block_fp32"]
+    (n_in, n_keep), = rs.keep_counts(wl["N"], 1, 1, wl["prune"])
+    assert n_keep == 138
+    x, w = _block_inputs(0, wl["B"], wl["N"], wl["D"], wl["Dm"], "f32")
+    _say("block fp32 config 1")
+    exact = _check_block(x, w, wl["H"], 1, n_keep, "f32")
+    assert exact == 1.0  # fp32 scores are close enough that the kept sets agree exactly here
+
+
+@pytest.mark.parametrize("dtype", ["bf16", "f32"])
+@pytest.mark.parametrize("B,N,D,H,Dm,P,K", [(2, 197, 384, 6, 1536, 1, 180), (1, 50, 128, 2, 192, 0, 20),
+                                             (3, 300, 192, 3, 768, 2, 100), (1, 129, 64, 1, 64, 1, 1)])
+def test_block_shapes(dtype, B, N, D, H, Dm, P, K):
+    _say("block", dtype, B, N, D, H, Dm, P, K)
+    x, w = _block_inputs(1, B, N, D, Dm, dtype, std=0.05, spread=0.3, affine_ln=True)
+    _check_block(x, w, H, P, K, dtype, ln_eps=1e-5)
+
+
+@pytest.mark.parametrize("dist", [rs.RS_DIST_L1, rs.RS_DIST_COS])
+def test_block_other_distances(dist):
+    x, w = _block_inputs(2, 2, 100, 128, 256, "bf16", std=0.1, spread=0.3)
+    _say("block dist", dist)
+    _check_block(x, w, 2, 1, 40, "bf16", dist=dist)
+    _check_block(x.astype(np.float32), w, 2, 1, 40, "f32", dist=dist)
+
+
+@pytest.mark.parametrize("dtype", ["bf16", "f32"])
+def test_block_without_pruning_and_null_biases(dtype):
+    B, N, D, H, Dm = 2, 70, 128, 2, 256
+    x, w = _block_inputs(3, B, N, D, Dm, dtype, std=0.05)
+    for k in ("b_qkv", "b_proj", "b_fc1", "b_fc2", "ln1_b", "ln2_b", "ln1_g"):
+        w[k] = None
+    ref = oracle.block(x, w, H)
+    for want_scores in (False, True):
+        y, kept, scores = _run_block(x, w, H, 1, N - 1, dtype, want_scores=want_scores)
+        assert norm_err(to_host(y), ref["xhat"]) < TOL[dtype]
+        np.testing.assert_array_equal(kept.cpu().numpy(), np.tile(np.arange(N), (B, 1)))
+        if want_scores:
+            assert norm_err(to_host(scores), ref["scores"]) < TOL[dtype]
+    # prefix only: everything but the class token is dropped
+    y, kept, scores = _run_block(x, w, H, 1, 0, dtype)
+    np.testing.assert_array_equal(kept.cpu().numpy(), np.zeros((B, 1), np.int32))
+    assert norm_err(to_host(y), ref["xhat"][:, :1]) < TOL[dtype]
+
+
+def test_block_packed_weights_and_determinism():
+    x, w = _block_inputs(4, 2, 197, 384, 1536, "bf16")
+    a = _run_block(x, w, 6, 1, 150, "bf16", pack=False)
+    b = _run_block(x, w, 6, 1, 150, "bf16", pack=True)
+    c = _run_block(x, w, 6, 1, 150, "bf16", pack=True)
+    for t0, t1, t2 in zip(a, b, c):
+        assert torch.equal(t0, t1) and torch.equal(t1, t2)
+
+
+def test_multi_block_teacher_forced():
+    """Four blocks of a ViT-S-like stack with 16 tokens dropped after each: the checker follows
+    the GPU's kept set block by block (kept sets may legitimately differ inside the rounding band)."""
+    B, N, D, H, Dm, dtype = 2, 197, 384, 6, 1536, "bf16"
+    x = host_round(si.tokens(5, B, N, D), dtype)
+    dx = to_dev(x, dtype)
+    for blk in range(4):
+        w = {k: host_round(v, dtype) for k, v in si.block_weights(5, blk, D, Dm).items()}
+        n = dx.shape[1]
+        K = n - 1 - 16
+        dw = {k: to_dev(v, dtype) for k, v in w.items()}
+        cfg = rs.make_cfg(B, n, D, H, Dm, 1, K, dx.dtype)
+        ws = torch.empty(rs.rs_block_workspace_size(cfg), dtype=torch.uint8, device="cuda")
+        y = torch.empty((B, 1 + K, D), device="cuda", dtype=dx.dtype)
+        kept = torch.empty((B, 1 + K), device="cuda", dtype=torch.int32)
+        scores = torch.empty((B, n), device="cuda", dtype=torch.float32)
+        rs.rs_block_fwd(cfg, rs.make_weights(dw), dx, y, kept, scores, ws)
+        torch.cuda.synchronize()
+        # checker continues from the GPU's block input (teacher forcing), so each block is
+        # compared like with like
+        ref = oracle.block(to_host(dx), w, H)
+        s, kept_h = to_host(scores), kept.cpu().numpy()
+        assert norm_err(s, ref["scores"]) < TOL[dtype]
+        exact = check_kept_admissible(kept_h, s, ref["scores"], 1, K)
+        assert norm_err(to_host(y), oracle.gather(ref["xhat"], kept_h)) < TOL[dtype]
+        _say("  block %d: kept exact on %.0f%% of images" % (blk + 1, 100 * exact))
+        dx = y
