@@ -95,6 +95,19 @@ RS_API const char *rs_last_error(void);
 RS_API int32_t rs_version(void);
 
 /*
+ * Measurement aid (not part of the method): while enabled, every kernel the library
+ * launches is bracketed by two HIP events on the caller's stream.  rs_profile_read waits
+ * for the recorded events (host synchronisation), adds the elapsed milliseconds and the
+ * launch counts per kernel class into ms_out[RS_PROFILE_CLASSES] and
+ * launches_out[RS_PROFILE_CLASSES] (host arrays), and forgets the records.
+ * Classes, by index: see rs_profile_class_name (host string, static storage).
+ */
+#define RS_PROFILE_CLASSES 10
+RS_API rs_status rs_profile_enable(int32_t enable);
+RS_API rs_status rs_profile_read(double *ms_out, int64_t *launches_out);
+RS_API const char *rs_profile_class_name(int32_t cls);
+
+/*
  * Fused multi-head self-attention, Eq. (1) of Sec. 3.1:
  *     O = Softmax(Q K^T * scale) V     per image and head,
  * computed tile by tile with a running row maximum and row sum so that the

@@ -19,7 +19,10 @@ RS_F32, RS_BF16 = 0, 1
 RS_DIST_L2, RS_DIST_L1, RS_DIST_COS = 0, 1, 2
 RS_SHIFT_MLP = 0
 
-EXPORTS = ("rs_last_error", "rs_version", "rs_attention_fwd", "rs_shift_topk_workspace_size",
+RS_PROFILE_CLASSES = 10
+
+EXPORTS = ("rs_last_error", "rs_version", "rs_profile_enable", "rs_profile_read",
+           "rs_profile_class_name", "rs_attention_fwd", "rs_shift_topk_workspace_size",
            "rs_shift_topk", "rs_packed_weights_size", "rs_pack_weights", "rs_block_workspace_size",
            "rs_block_fwd")
 
@@ -59,6 +62,12 @@ def lib():
         L = ctypes.CDLL(LIB_PATH)
         L.rs_last_error.restype = ctypes.c_char_p
         L.rs_version.restype = _i32
+        L.rs_profile_enable.argtypes = [_i32]
+        L.rs_profile_enable.restype = ctypes.c_int
+        L.rs_profile_read.argtypes = [ctypes.POINTER(ctypes.c_double), ctypes.POINTER(_i64)]
+        L.rs_profile_read.restype = ctypes.c_int
+        L.rs_profile_class_name.argtypes = [_i32]
+        L.rs_profile_class_name.restype = ctypes.c_char_p
         L.rs_attention_fwd.argtypes = [_vp, _vp, _vp, _vp, _i32, _i32, _i32, _i32] + [_i64] * 6 + \
             [ctypes.c_float, ctypes.c_int, _vp]
         L.rs_attention_fwd.restype = ctypes.c_int
@@ -128,6 +137,18 @@ def make_weights(w: dict, packed=None) -> RsBlockWeights:
 # ---- the calls of include/rs.h ------------------------------------------------
 def rs_version() -> int:
     return int(lib().rs_version())
+
+
+def rs_profile_enable(enable: bool) -> None:
+    _check(lib().rs_profile_enable(1 if enable else 0))
+
+
+def rs_profile_read() -> dict:
+    """{class name: (milliseconds, launches)} since the last read; waits for the events."""
+    ms = (ctypes.c_double * RS_PROFILE_CLASSES)()
+    n = (_i64 * RS_PROFILE_CLASSES)()
+    _check(lib().rs_profile_read(ms, n))
+    return {lib().rs_profile_class_name(i).decode(): (ms[i], n[i]) for i in range(RS_PROFILE_CLASSES)}
 
 
 def rs_attention_fwd(q, k, v, o, scale, stream=None) -> None:

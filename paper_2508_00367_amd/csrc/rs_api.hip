@@ -6,6 +6,9 @@
 #include <stdio.h>
 #include <string.h>
 
+#include <mutex>
+#include <vector>
+
 #include "common.hpp"
 
 namespace rs {
@@ -38,6 +41,55 @@ static bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 
     do {                                                         \
         hipError_t e_ = (expr);                                  \
         if (e_ != hipSuccess) return rs::device_error(#expr, e_); \
+    } while (0)
+
+// ---- optional per-kernel timing with HIP events on the caller's stream ---------
+enum KernelClass { K_PACK = 0, K_LN, K_GEMM_QKV, K_ATTN, K_GEMM_PROJ, K_GEMM_FC1, K_GEMM_FC2, K_SCORE,
+                   K_SELECT, K_GATHER, K_COUNT };
+static_assert(K_COUNT == RS_PROFILE_CLASSES, "header and library disagree on the class count");
+static const char* const kClassNames[K_COUNT] = {"pack_weights", "layernorm", "gemm_qkv", "attention",
+                                                 "gemm_proj", "gemm_fc1", "gemm_fc2", "shift_score",
+                                                 "select", "gather"};
+struct ProfRec { int cls; hipEvent_t start, stop; };
+static struct {
+    std::mutex mu;
+    bool on = false;
+    std::vector<ProfRec> recs;
+    std::vector<hipEvent_t> pool;
+} g_prof;
+
+static hipEvent_t prof_event() {
+    if (!g_prof.pool.empty()) {
+        hipEvent_t e = g_prof.pool.back();
+        g_prof.pool.pop_back();
+        return e;
+    }
+    hipEvent_t e = nullptr;
+    if (hipEventCreate(&e) != hipSuccess) return nullptr;
+    return e;
+}
+
+// Runs `launch` and, when profiling is on, brackets it with two events on `s`.
+template <typename F>
+static hipError_t timed(int cls, hipStream_t s, F launch) {
+    if (!g_prof.on) return launch();
+    std::lock_guard<std::mutex> lk(g_prof.mu);
+    hipEvent_t a = prof_event(), b = prof_event();
+    if (!a || !b) return hipErrorOutOfMemory;
+    hipError_t e = hipEventRecord(a, s);
+    if (e != hipSuccess) return e;
+    e = launch();
+    if (e != hipSuccess) return e;
+    e = hipEventRecord(b, s);
+    if (e != hipSuccess) return e;
+    g_prof.recs.push_back({cls, a, b});
+    return hipSuccess;
+}
+
+#define RS_LAUNCH_K(cls, stream, expr)                                         \
+    do {                                                                       \
+        hipError_t e_ = rs::timed((cls), (stream), [&]() { return (expr); });  \
+        if (e_ != hipSuccess) return rs::device_error(#expr, e_);              \
     } while (0)
 
 // ---- workspace layout of rs_block_fwd ---------------------------------------
@@ -101,6 +153,35 @@ const char* rs_last_error(void) { return g_err; }
 
 int32_t rs_version(void) { return 100; }
 
+rs_status rs_profile_enable(int32_t enable) {
+    std::lock_guard<std::mutex> lk(g_prof.mu);
+    g_prof.on = enable != 0;
+    return RS_OK;
+}
+
+const char* rs_profile_class_name(int32_t cls) {
+    return (cls >= 0 && cls < K_COUNT) ? kClassNames[cls] : "";
+}
+
+rs_status rs_profile_read(double* ms_out, int64_t* launches_out) {
+    RS_REQUIRE(ms_out && launches_out, RS_ERR_INVALID_ARG, "ms_out and launches_out must not be NULL");
+    std::lock_guard<std::mutex> lk(g_prof.mu);
+    for (int i = 0; i < K_COUNT; ++i) { ms_out[i] = 0.0; launches_out[i] = 0; }
+    rs_status st = RS_OK;
+    for (const ProfRec& r : g_prof.recs) {
+        float ms = 0.f;
+        hipError_t e = hipEventSynchronize(r.stop);
+        if (e == hipSuccess) e = hipEventElapsedTime(&ms, r.start, r.stop);
+        if (e != hipSuccess) st = device_error("profile event", e);
+        ms_out[r.cls] += ms;
+        launches_out[r.cls] += 1;
+        g_prof.pool.push_back(r.start);
+        g_prof.pool.push_back(r.stop);
+    }
+    g_prof.recs.clear();
+    return st;
+}
+
 rs_status rs_attention_fwd(const void* q, const void* k, const void* v, void* o, int32_t B, int32_t H,
                            int32_t N, int32_t dh, int64_t stride_b, int64_t stride_n, int64_t stride_h,
                            int64_t o_stride_b, int64_t o_stride_n, int64_t o_stride_h, float scale,
@@ -121,7 +202,7 @@ rs_status rs_attention_fwd(const void* q, const void* k, const void* v, void* o,
         RS_REQUIRE(st[i] >= 0 && st[i] % 8 == 0, RS_ERR_INVALID_ARG,
                    "strides must be non-negative multiples of 8 elements");
     RS_REQUIRE(stride_n >= dh && o_stride_n >= dh, RS_ERR_INVALID_ARG, "token stride smaller than dh");
-    RS_LAUNCH(launch_attention(dtype, q, k, v, o, B, H, N, stride_b, stride_n, stride_h, o_stride_b,
+    RS_LAUNCH_K(K_ATTN, (hipStream_t)hip_stream, launch_attention(dtype, q, k, v, o, B, H, N, stride_b, stride_n, stride_h, o_stride_b,
                                o_stride_n, o_stride_h, scale, (hipStream_t)hip_stream));
     return RS_OK;
 }
@@ -155,9 +236,9 @@ rs_status rs_shift_topk(const void* f_out, const void* f_in, const void* src, in
     RS_REQUIRE(gathered == nullptr || gathered != s, RS_ERR_INVALID_ARG, "gathered must not alias src");
     hipStream_t st = (hipStream_t)hip_stream;
     const int K = n_prefix + n_keep;
-    RS_LAUNCH(launch_shift_scores(dtype, dist, f_out, f_in, scores, (int64_t)B * N, D, st));
-    RS_LAUNCH(launch_select(scores, kept_idx, B, N, n_prefix, n_keep, st));
-    if (gathered) RS_LAUNCH(launch_gather(dtype, s, kept_idx, gathered, B, N, K, D, st));
+    RS_LAUNCH_K(K_SCORE, st, launch_shift_scores(dtype, dist, f_out, f_in, scores, (int64_t)B * N, D, st));
+    RS_LAUNCH_K(K_SELECT, st, launch_select(scores, kept_idx, B, N, n_prefix, n_keep, st));
+    if (gathered) RS_LAUNCH_K(K_GATHER, st, launch_gather(dtype, s, kept_idx, gathered, B, N, K, D, st));
     return RS_OK;
 }
 
@@ -169,13 +250,13 @@ size_t rs_packed_weights_size(const rs_block_cfg* cfg) {
 static rs_status pack_into(const rs_block_cfg* c, const rs_block_weights* w, void* dst, hipStream_t st) {
     const size_t D = c->D, Dm = c->Dm;
     char* p = (char*)dst;
-    RS_LAUNCH(launch_pack_transpose(w->w_qkv, p, c->D, 3 * c->D, st));
+    RS_LAUNCH_K(K_PACK, st, launch_pack_transpose(w->w_qkv, p, c->D, 3 * c->D, st));
     p += 3 * D * D * 2;
-    RS_LAUNCH(launch_pack_transpose(w->w_proj, p, c->D, c->D, st));
+    RS_LAUNCH_K(K_PACK, st, launch_pack_transpose(w->w_proj, p, c->D, c->D, st));
     p += D * D * 2;
-    RS_LAUNCH(launch_pack_transpose(w->w_fc1, p, c->D, c->Dm, st));
+    RS_LAUNCH_K(K_PACK, st, launch_pack_transpose(w->w_fc1, p, c->D, c->Dm, st));
     p += D * Dm * 2;
-    RS_LAUNCH(launch_pack_transpose(w->w_fc2, p, c->Dm, c->D, st));
+    RS_LAUNCH_K(K_PACK, st, launch_pack_transpose(w->w_fc2, p, c->Dm, c->D, st));
     return RS_OK;
 }
 
@@ -262,25 +343,25 @@ rs_status rs_block_fwd(const rs_block_cfg* cfg, const rs_block_weights* w, const
     const float scale = c.attn_scale > 0.f ? c.attn_scale : 0.125f;  // 1/sqrt(64)
 
     // x1 = SA(LN(x)) + x                                                     Eq. (5)
-    RS_LAUNCH(launch_layernorm(dt, x, w->ln1_g, w->ln1_b, u, M, D, c.ln_eps, s));
-    RS_LAUNCH(launch_gemm(dt, EPI_BIAS, RS_DIST_L2, u, wq, w->b_qkv, nullptr, qkv, nullptr, M, 3 * D, D, s));
+    RS_LAUNCH_K(K_LN, s, launch_layernorm(dt, x, w->ln1_g, w->ln1_b, u, M, D, c.ln_eps, s));
+    RS_LAUNCH_K(K_GEMM_QKV, s, launch_gemm(dt, EPI_BIAS, RS_DIST_L2, u, wq, w->b_qkv, nullptr, qkv, nullptr, M, 3 * D, D, s));
     {
         const size_t e = elem_size(dt);
         const char* qp = (const char*)qkv;
-        RS_LAUNCH(launch_attention(dt, qp, qp + (size_t)D * e, qp + 2 * (size_t)D * e, att, c.B, c.H, c.N,
+        RS_LAUNCH_K(K_ATTN, s, launch_attention(dt, qp, qp + (size_t)D * e, qp + 2 * (size_t)D * e, att, c.B, c.H, c.N,
                                    (int64_t)c.N * 3 * D, 3 * D, 64, (int64_t)c.N * D, D, 64, scale, s));
     }
-    RS_LAUNCH(launch_gemm(dt, EPI_BIAS_RES, RS_DIST_L2, att, wp, w->b_proj, x, x1, nullptr, M, D, D, s));
+    RS_LAUNCH_K(K_GEMM_PROJ, s, launch_gemm(dt, EPI_BIAS_RES, RS_DIST_L2, att, wp, w->b_proj, x, x1, nullptr, M, D, D, s));
     // xhat = MLP(LN(x1)) + x1, with the shift partial sums of D(MLP(LN(x1)), x1)   Eq. (6), Eq. (4)
-    RS_LAUNCH(launch_layernorm(dt, x1, w->ln2_g, w->ln2_b, u, M, D, c.ln_eps, s));
-    RS_LAUNCH(launch_gemm(dt, EPI_BIAS_GELU, RS_DIST_L2, u, w1, w->b_fc1, nullptr, hid, nullptr, M, Dm, D, s));
+    RS_LAUNCH_K(K_LN, s, launch_layernorm(dt, x1, w->ln2_g, w->ln2_b, u, M, D, c.ln_eps, s));
+    RS_LAUNCH_K(K_GEMM_FC1, s, launch_gemm(dt, EPI_BIAS_GELU, RS_DIST_L2, u, w1, w->b_fc1, nullptr, hid, nullptr, M, Dm, D, s));
     void* xhat = prune ? att : y;  // without pruning the block output goes straight to y
-    RS_LAUNCH(launch_gemm(dt, want_scores ? EPI_BIAS_RES_SHIFT : EPI_BIAS_RES, c.dist, hid, w2, w->b_fc2, x1,
+    RS_LAUNCH_K(K_GEMM_FC2, s, launch_gemm(dt, want_scores ? EPI_BIAS_RES_SHIFT : EPI_BIAS_RES, c.dist, hid, w2, w->b_fc2, x1,
                           xhat, partials, M, D, Dm, s));
-    if (want_scores) RS_LAUNCH(launch_finalize_scores(c.dist, partials, L.slots, sc, M, s));
+    if (want_scores) RS_LAUNCH_K(K_SCORE, s, launch_finalize_scores(c.dist, partials, L.slots, sc, M, s));
     // keep the n_keep highest-shift tokens (plus the prefix) and compact them
-    RS_LAUNCH(launch_select(sc, kept_idx, c.B, c.N, c.n_prefix, c.n_keep, s));
-    if (prune) RS_LAUNCH(launch_gather(dt, xhat, kept_idx, y, c.B, c.N, K, D, s));
+    RS_LAUNCH_K(K_SELECT, s, launch_select(sc, kept_idx, c.B, c.N, c.n_prefix, c.n_keep, s));
+    if (prune) RS_LAUNCH_K(K_GATHER, s, launch_gather(dt, xhat, kept_idx, y, c.B, c.N, K, D, s));
     return RS_OK;
 }
 
