@@ -25,20 +25,57 @@ constexpr int BK = 64;
 
 __device__ __forceinline__ int swz(int row, int chunk) { return row * 128 + ((chunk ^ (row & 7)) << 4); }
 
-template <int BM, int BN, int WGM, int WGN, int EPI, int DIST>
-__global__ __launch_bounds__(WGM* WGN * 64) void gemm_bf16_kernel(
+// Exact-erf GELU x * Phi(x) with erf from the 5-term rational/exponential form of
+// Abramowitz & Stegun 7.1.26 (|error| < 1.5e-7 on erf): 2 transcendental + ~12 plain ops,
+// a fraction of libm's erff, which matters because the fc1 epilogue runs it M * Dm times.
+__device__ __forceinline__ float gelu_fast(float x) {
+    const float z = fabsf(x) * 0.70710678118654752440f;
+    const float t = __builtin_amdgcn_rcpf(fmaf(0.3275911f, z, 1.0f));
+    float p = fmaf(1.061405429f, t, -1.453152027f);
+    p = fmaf(p, t, 1.421413741f);
+    p = fmaf(p, t, -0.284496736f);
+    p = fmaf(p, t, 0.254829592f);
+    const float y = p * t * __builtin_amdgcn_exp2f(-(z * z) * 1.44269504088896340736f);  // 1 - erf(z)
+    const float phi = x >= 0.f ? fmaf(-0.5f, y, 1.0f) : 0.5f * y;
+    return x * phi;
+}
+
+template <int TN, int TM>
+struct Frags {
+    bf16x8 w[TN], a[TM];
+};
+
+typedef __attribute__((address_space(3))) void* lds_ptr;
+
+// One wave-wide 16-byte-per-lane copy from a buffer resource straight into LDS
+// (buffer_load_dwordx4 ... lds): lane l lands at lds_base + 16 * l; reads past the
+// resource's size return zeros.  `voff` is the lane's byte offset, `soff` a uniform one.
+__device__ __forceinline__ void dma16(__amdgpu_buffer_rsrc_t rsrc, unsigned char* lds_base, int voff, int soff) {
+    __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrc, (lds_ptr)lds_base, 16, voff, soff, 0, 0);
+}
+
+__device__ __forceinline__ __amdgpu_buffer_rsrc_t make_rsrc(const void* base, int64_t bytes) {
+    const int64_t lim = 0xffffffffll;
+    return __builtin_amdgcn_make_buffer_rsrc(const_cast<void*>(base), 0, (int)(bytes < lim ? bytes : lim), 0x00020000);
+}
+
+// 256 threads = 2 x 2 waves; workgroup tile BM x BN (multiples of 64), wave tile BM/2 x BN/2.
+// Two LDS stages of (BM + BN) rows x 128 B; the next K tile streams from global memory
+// directly into the idle stage (no register staging) while the matrix cores work on the
+// current one.  Operand fragments are double buffered in registers and their LDS reads are
+// interleaved with the MFMAs of the previous K step.
+template <int BM, int BN, int EPI, int DIST>
+__global__ __launch_bounds__(256, 1) void gemm_bf16_kernel(
     const bf16raw* __restrict__ a, const bf16raw* __restrict__ wt, const bf16raw* __restrict__ bias,
     const bf16raw* __restrict__ res, bf16raw* __restrict__ out, float* __restrict__ partials,
     int M, int N, int K, int tiles_m, int tiles_n, int slots) {
-    constexpr int NT = WGM * WGN * 64;
-    constexpr int WM = BM / WGM, WN = BN / WGN;  // wave tile
-    constexpr int TM = WM / 32, TN = WN / 32;    // MFMA tiles per wave
-    constexpr int A_LOADS = BM * 8 / NT, W_LOADS = BN * 8 / NT;
-    static_assert(BM * 8 % NT == 0 && BN * 8 % NT == 0, "tile/threads mismatch");
-
-    extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
-    // stage s: activations at s*STAGE, weights after them
+    constexpr int WM = BM / 2, WN = BN / 2;     // wave tile
+    constexpr int TM = WM / 32, TN = WN / 32;   // MFMA tiles per wave
+    constexpr int A_LOADS = BM / 32, W_LOADS = BN / 32;  // 1 KiB wave copies per stage and wave
     constexpr int STAGE = (BM + BN) * 128;
+
+    __shared__ __attribute__((aligned(1024))) unsigned char stage0[STAGE];
+    __shared__ __attribute__((aligned(1024))) unsigned char stage1[STAGE];
 
     // XCD-aware tile order: consecutive workgroup ids go round-robin to the 8 XCDs, so give
     // each XCD a contiguous range of tiles; inside a range the n index runs fastest, so the
@@ -53,26 +90,18 @@ __global__ __launch_bounds__(WGM* WGN * 64) void gemm_bf16_kernel(
     const int tile_m = bid / tiles_n, tile_n = bid % tiles_n;
     const int m0 = tile_m * BM, n0 = tile_n * BN;
 
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const int wm = wave % WGM, wn = wave / WGM;
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);  // wave-uniform: LDS copy targets go to M0
+    const int wm = wave & 1, wn = wave >> 1;
     const int l32 = lane & 31, g = lane >> 5;
 
-    // global -> LDS assignment: thread handles chunk (tid & 7) of rows (tid >> 3) + i * (NT/8)
-    const int ld_chunk = tid & 7, ld_row = tid >> 3;
-    const bf16raw* a_src[A_LOADS];
-    const bf16raw* w_src[W_LOADS];
-#pragma unroll
-    for (int i = 0; i < A_LOADS; ++i) {
-        int r = m0 + ld_row + i * (NT / 8);
-        r = r < M ? r : M - 1;  // clamp: rows past the end are computed but never stored
-        a_src[i] = a + (int64_t)r * K + ld_chunk * 8;
-    }
-#pragma unroll
-    for (int i = 0; i < W_LOADS; ++i) {
-        int r = n0 + ld_row + i * (NT / 8);
-        r = r < N ? r : N - 1;
-        w_src[i] = wt + (int64_t)r * K + ld_chunk * 8;
-    }
+    // global -> LDS: wave copy i of a wave fills LDS rows 32*i + 8*wave .. +7 (1 KiB, lane l at
+    // byte 16*l = row l/8, slot l%8); slot p of row r must hold global chunk p ^ (r & 7).
+    const __amdgpu_buffer_rsrc_t rs_a = make_rsrc(a + (int64_t)m0 * K, (int64_t)(M - m0) * K * 2);
+    const __amdgpu_buffer_rsrc_t rs_w = make_rsrc(wt + (int64_t)n0 * K, (int64_t)(N - n0) * K * 2);
+    const int ld_r = lane >> 3;
+    const int voff = ((wave * 8 + ld_r) * K + (((lane & 7) ^ ld_r) << 3)) * 2;
+    const int pass_bytes = 32 * K * 2;
 
     f32x16 acc[TN][TM];
 #pragma unroll
@@ -82,55 +111,95 @@ __global__ __launch_bounds__(WGM* WGN * 64) void gemm_bf16_kernel(
 #pragma unroll
             for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
 
-    uint4 a_reg[A_LOADS], w_reg[W_LOADS];
     const int KT = K / BK;
+    const int a_row0 = wm * WM + l32, w_row0 = wn * WN + l32;
+    const int sw7 = l32 & 7;  // (row & 7) of every operand row of this lane
 
-    auto load_global = [&](int kt) {
-#pragma unroll
-        for (int i = 0; i < A_LOADS; ++i) a_reg[i] = *reinterpret_cast<const uint4*>(a_src[i] + kt * BK);
-#pragma unroll
-        for (int i = 0; i < W_LOADS; ++i) w_reg[i] = *reinterpret_cast<const uint4*>(w_src[i] + kt * BK);
-    };
-    auto store_lds = [&](int stage) {
-        unsigned char* sa = smem + stage * STAGE;
-        unsigned char* sw = sa + BM * 128;
-#pragma unroll
-        for (int i = 0; i < A_LOADS; ++i)
-            *reinterpret_cast<uint4*>(sa + swz(ld_row + i * (NT / 8), ld_chunk)) = a_reg[i];
-#pragma unroll
-        for (int i = 0; i < W_LOADS; ++i)
-            *reinterpret_cast<uint4*>(sw + swz(ld_row + i * (NT / 8), ld_chunk)) = w_reg[i];
-    };
-
-    load_global(0);
-    store_lds(0);
-    __syncthreads();
-
-    for (int kt = 0; kt < KT; ++kt) {
-        if (kt + 1 < KT) load_global(kt + 1);
-        const unsigned char* sa = smem + (kt & 1) * STAGE;
-        const unsigned char* sw = sa + BM * 128;
-#pragma unroll
-        for (int kk = 0; kk < BK / 16; ++kk) {
-            bf16x8 wf[TN], af[TM];
-#pragma unroll
-            for (int i = 0; i < TN; ++i)
-                wf[i] = *reinterpret_cast<const bf16x8*>(sw + swz(wn * WN + i * 32 + l32, kk * 2 + g));
-#pragma unroll
-            for (int j = 0; j < TM; ++j)
-                af[j] = *reinterpret_cast<const bf16x8*>(sa + swz(wm * WM + j * 32 + l32, kk * 2 + g));
-#pragma unroll
-            for (int i = 0; i < TN; ++i)
-#pragma unroll
-                for (int j = 0; j < TM; ++j)
-                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf[i], af[j], acc[i][j], 0, 0, 0);
-        }
-        if (kt + 1 < KT) store_lds((kt + 1) & 1);
-        __syncthreads();
+#define RS_GEMM_DMA(stage_, kt_)                                                                          \
+    {                                                                                                     \
+        const int kb_ = (kt_) * (BK * 2);                                                                 \
+        _Pragma("unroll") for (int i = 0; i < A_LOADS; ++i)                                               \
+            dma16(rs_a, (stage_) + (i * 32 + wave * 8) * 128, voff, i * pass_bytes + kb_);                \
+        _Pragma("unroll") for (int i = 0; i < W_LOADS; ++i)                                               \
+            dma16(rs_w, (stage_) + (BM + i * 32 + wave * 8) * 128, voff, i * pass_bytes + kb_);           \
+    }
+#define RS_GEMM_LOAD_FRAGS(f_, stage_, kk_)                                                               \
+    {                                                                                                     \
+        const int co_ = ((((kk_) * 2 + g) ^ sw7) << 4);                                                   \
+        _Pragma("unroll") for (int i = 0; i < TN; ++i)                                                    \
+            (f_).w[i] = *reinterpret_cast<const bf16x8*>((stage_) + (BM + w_row0 + i * 32) * 128 + co_);  \
+        _Pragma("unroll") for (int j = 0; j < TM; ++j)                                                    \
+            (f_).a[j] = *reinterpret_cast<const bf16x8*>((stage_) + (a_row0 + j * 32) * 128 + co_);       \
+    }
+#define RS_GEMM_MFMA(f_)                                                                                  \
+    {                                                                                                     \
+        _Pragma("unroll") for (int i = 0; i < TN; ++i)                                                    \
+            _Pragma("unroll") for (int j = 0; j < TM; ++j)                                                \
+                acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16((f_).w[i], (f_).a[j], acc[i][j], 0, 0, 0); \
+    }
+// Scheduling recipe for one K step (one scheduling region): every LDS fragment read of the
+// next step is followed by `vm_` global->LDS copies and its share of this step's MFMAs.
+#define RS_GEMM_INTERLEAVE(vm_)                                                                           \
+    {                                                                                                     \
+        _Pragma("unroll") for (int s_ = 0; s_ < TN + TM; ++s_) {                                          \
+            __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);                                            \
+            if (vm_) __builtin_amdgcn_sched_group_barrier(0x020, (A_LOADS + W_LOADS) / (TN + TM), 0);     \
+            __builtin_amdgcn_sched_group_barrier(0x008, (TN * TM) / (TN + TM), 0);                        \
+        }                                                                                                 \
+        __builtin_amdgcn_sched_barrier(0);                                                                \
+    }
+// One K tile from `cur_`; DMA_ (may be empty) starts the copies of a later tile into the idle stage.
+#define RS_GEMM_COMPUTE(cur_, DMA_, has_dma_)                                                             \
+    {                                                                                                     \
+        Frags<TN, TM> f0, f1;                                                                             \
+        RS_GEMM_LOAD_FRAGS(f0, cur_, 0)                                                                   \
+        __builtin_amdgcn_sched_barrier(0);                                                                \
+        DMA_                                                                                              \
+        RS_GEMM_LOAD_FRAGS(f1, cur_, 1)                                                                   \
+        RS_GEMM_MFMA(f0)                                                                                  \
+        RS_GEMM_INTERLEAVE(has_dma_)                                                                      \
+        RS_GEMM_LOAD_FRAGS(f0, cur_, 2)                                                                   \
+        RS_GEMM_MFMA(f1)                                                                                  \
+        RS_GEMM_INTERLEAVE(0)                                                                             \
+        RS_GEMM_LOAD_FRAGS(f1, cur_, 3)                                                                   \
+        RS_GEMM_MFMA(f0)                                                                                  \
+        RS_GEMM_INTERLEAVE(0)                                                                             \
+        RS_GEMM_MFMA(f1)                                                                                  \
+    }
+// all of this wave's copies have landed, then every wave's
+#define RS_GEMM_SYNC()                       \
+    {                                        \
+        __builtin_amdgcn_s_waitcnt(0x0F70);  \
+        __syncthreads();                     \
     }
 
-    // ---- epilogue: lane owns token row m = .. + l32; register r = 4*q + i of tile (tn, tm)
-    //      is output feature n = .. + 8*q + 4*g + i.
+    RS_GEMM_DMA(stage0, 0)
+    RS_GEMM_SYNC()
+    int kt = 0;
+    for (; kt + 2 < KT; kt += 2) {  // tiles kt+1 and kt+2 both exist
+        RS_GEMM_COMPUTE(stage0, RS_GEMM_DMA(stage1, kt + 1), 1)
+        RS_GEMM_SYNC()
+        RS_GEMM_COMPUTE(stage1, RS_GEMM_DMA(stage0, kt + 2), 1)
+        RS_GEMM_SYNC()
+    }
+    if (kt + 2 == KT) {  // two tiles left
+        RS_GEMM_COMPUTE(stage0, RS_GEMM_DMA(stage1, kt + 1), 1)
+        RS_GEMM_SYNC()
+        RS_GEMM_COMPUTE(stage1, , 0)
+    } else {             // one tile left
+        RS_GEMM_COMPUTE(stage0, , 0)
+    }
+#undef RS_GEMM_DMA
+#undef RS_GEMM_LOAD_FRAGS
+#undef RS_GEMM_MFMA
+#undef RS_GEMM_INTERLEAVE
+#undef RS_GEMM_COMPUTE
+#undef RS_GEMM_SYNC
+
+    // ---- epilogue.  Lane (l32, g) owns token row m = .. + l32; register 4*q + e of tile (i, j)
+    //      is output feature n = .. + 32*i + 8*q + 4*g + e.  After the elementwise work the two
+    //      half-waves swap quads (v_permlane32_swap) so that every lane stores 8 consecutive
+    //      features (16 bytes): g = 0 takes the even q of a pair, g = 1 the odd one.
 #pragma unroll
     for (int j = 0; j < TM; ++j) {
         const int m = m0 + wm * WM + j * 32 + l32;
@@ -138,13 +207,15 @@ __global__ __launch_bounds__(WGM* WGN * 64) void gemm_bf16_kernel(
         float p0 = 0.f, p1 = 0.f, p2 = 0.f;  // shift partial sums of this row over the wave's columns
 #pragma unroll
         for (int i = 0; i < TN; ++i) {
+            const int nb = n0 + wn * WN + i * 32;
+            uint32_t d0[4], d1[4];
 #pragma unroll
             for (int q = 0; q < 4; ++q) {
-                const int n = n0 + wn * WN + i * 32 + q * 8 + g * 4;
-                if (n < N) {  // N % 4 == 0: a quad is either fully inside or fully outside
-                    float v[4];
+                const int n = nb + q * 8 + g * 4;
+                float v[4];
 #pragma unroll
-                    for (int e = 0; e < 4; ++e) v[e] = acc[i][j][q * 4 + e];
+                for (int e = 0; e < 4; ++e) v[e] = acc[i][j][q * 4 + e];
+                if (n < N) {  // N % 8 == 0: an 8-wide group is fully inside or fully outside
                     if (bias) {
                         uint2 b = *reinterpret_cast<const uint2*>(bias + n);
                         v[0] += __uint_as_float(b.x << 16); v[1] += __uint_as_float(b.x & 0xffff0000u);
@@ -152,7 +223,7 @@ __global__ __launch_bounds__(WGM* WGN * 64) void gemm_bf16_kernel(
                     }
                     if (EPI == EPI_BIAS_GELU) {
 #pragma unroll
-                        for (int e = 0; e < 4; ++e) v[e] = gelu_erf(v[e]);
+                        for (int e = 0; e < 4; ++e) v[e] = gelu_fast(v[e]);
                     }
                     if (EPI == EPI_BIAS_RES || EPI == EPI_BIAS_RES_SHIFT) {
                         float r[4] = {0.f, 0.f, 0.f, 0.f};
@@ -172,12 +243,20 @@ __global__ __launch_bounds__(WGM* WGN * 64) void gemm_bf16_kernel(
 #pragma unroll
                         for (int e = 0; e < 4; ++e) v[e] += r[e];
                     }
-                    if (m_ok) {
-                        uint2 o;
-                        o.x = pack2bf(v[0], v[1]);
-                        o.y = pack2bf(v[2], v[3]);
-                        *reinterpret_cast<uint2*>(out + (int64_t)m * N + n) = o;
-                    }
+                }
+                d0[q] = pack2bf(v[0], v[1]);
+                d1[q] = pack2bf(v[2], v[3]);
+            }
+#pragma unroll
+            for (int t = 0; t < 2; ++t) {
+                // swap: lanes g=0 give their odd quad and receive the partner's even quad
+                auto s0 = __builtin_amdgcn_permlane32_swap(d0[2 * t], d0[2 * t + 1], false, false);
+                auto s1 = __builtin_amdgcn_permlane32_swap(d1[2 * t], d1[2 * t + 1], false, false);
+                const int n = nb + (2 * t + g) * 8;
+                if (m_ok && n < N) {
+                    uint4 o;
+                    o.x = s0[0]; o.y = s1[0]; o.z = s0[1]; o.w = s1[1];
+                    *reinterpret_cast<uint4*>(out + (int64_t)m * N + n) = o;
                 }
             }
         }
@@ -200,8 +279,8 @@ __global__ __launch_bounds__(WGM* WGN * 64) void gemm_bf16_kernel(
 
 // Tile configuration of the bf16 GEMM.
 struct GemmCfg {
-    static constexpr int BM = 128, BN = 128, WGM = 2, WGN = 2;
-    static constexpr int WN = BN / WGN;
+    static constexpr int BM = 256, BN = 256;
+    static constexpr int WN = BN / 2;
 };
 
 template <int EPI, int DIST>
@@ -210,15 +289,7 @@ static hipError_t launch_bf16(const void* a, const void* wt, const void* bias, c
     using C = GemmCfg;
     const int tiles_m = (int)((M + C::BM - 1) / C::BM), tiles_n = (N + C::BN - 1) / C::BN;
     const int slots = (tiles_n * C::BN) / C::WN;
-    const size_t lds = 2 * (C::BM + C::BN) * 128;
-    auto kern = gemm_bf16_kernel<C::BM, C::BN, C::WGM, C::WGN, EPI, DIST>;
-    static bool attr_done = false;  // raise the dynamic LDS limit once per instantiation
-    if (!attr_done) {
-        hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-        if (e != hipSuccess) return e;
-        attr_done = true;
-    }
-    hipLaunchKernelGGL(kern, dim3(tiles_m * tiles_n), dim3(C::WGM * C::WGN * 64), lds, s,
+    hipLaunchKernelGGL((gemm_bf16_kernel<C::BM, C::BN, EPI, DIST>), dim3(tiles_m * tiles_n), dim3(256), 0, s,
                        (const bf16raw*)a, (const bf16raw*)wt, (const bf16raw*)bias, (const bf16raw*)res,
                        (bf16raw*)out, partials, (int)M, N, K, tiles_m, tiles_n, slots);
     return hipGetLastError();
