@@ -102,7 +102,7 @@ RS_API int32_t rs_version(void);
  * launches_out[RS_PROFILE_CLASSES] (host arrays), and forgets the records.
  * Classes, by index: see rs_profile_class_name (host string, static storage).
  */
-#define RS_PROFILE_CLASSES 10
+#define RS_PROFILE_CLASSES 11
 RS_API rs_status rs_profile_enable(int32_t enable);
 RS_API rs_status rs_profile_read(double *ms_out, int64_t *launches_out);
 RS_API const char *rs_profile_class_name(int32_t cls);
@@ -154,6 +154,25 @@ RS_API rs_status rs_shift_topk(const void *f_out, const void *f_in, const void *
 RS_API size_t rs_packed_weights_size(const rs_block_cfg *cfg);
 RS_API rs_status rs_pack_weights(const rs_block_cfg *cfg, const rs_block_weights *w,
                           void *packed_out, void *hip_stream);
+
+/*
+ * One linear layer of the block with its fused elementwise tail (the four contractions of
+ * Eqs. (5),(6): QKV, output projection, fc1, fc2; the O(N C^2) term of Sec. 3.1):
+ *     out = epilogue(a @ W + bias)
+ *   RS_EPI_BIAS       out = a W + bias
+ *   RS_EPI_BIAS_GELU  out = GELU(a W + bias)          (exact-erf GELU)
+ *   RS_EPI_BIAS_RES   out = a W + bias + res
+ *   a : [M, K].   out, res : [M, N]; out must not alias a.   bias : [N] or NULL.
+ *   w : RS_F32: the [K, N] matrix as is.  RS_BF16: the [N, K] re-layout written by
+ *       rs_pack_linear (wt must hold N*K elements).
+ *   K % 64 == 0, N % 64 == 0.
+ */
+typedef enum { RS_EPI_BIAS = 0, RS_EPI_BIAS_GELU = 1, RS_EPI_BIAS_RES = 2 } rs_epilogue;
+RS_API rs_status rs_pack_linear(const void *w, void *wt, int32_t K, int32_t N, rs_dtype dtype,
+                                void *hip_stream);
+RS_API rs_status rs_linear_fwd(const void *a, const void *w, const void *bias, const void *res,
+                               void *out, int64_t M, int32_t N, int32_t K, rs_epilogue epi,
+                               rs_dtype dtype, void *hip_stream);
 
 /*
  * One pre-LN encoder block followed by representation-shift pruning

@@ -19,11 +19,12 @@ RS_F32, RS_BF16 = 0, 1
 RS_DIST_L2, RS_DIST_L1, RS_DIST_COS = 0, 1, 2
 RS_SHIFT_MLP = 0
 
-RS_PROFILE_CLASSES = 10
+RS_PROFILE_CLASSES = 11
+RS_EPI_BIAS, RS_EPI_BIAS_GELU, RS_EPI_BIAS_RES = 0, 1, 2
 
 EXPORTS = ("rs_last_error", "rs_version", "rs_profile_enable", "rs_profile_read",
            "rs_profile_class_name", "rs_attention_fwd", "rs_shift_topk_workspace_size",
-           "rs_shift_topk", "rs_packed_weights_size", "rs_pack_weights", "rs_block_workspace_size",
+           "rs_shift_topk", "rs_pack_linear", "rs_linear_fwd", "rs_packed_weights_size", "rs_pack_weights", "rs_block_workspace_size",
            "rs_block_fwd")
 
 _vp = ctypes.c_void_p
@@ -76,6 +77,10 @@ def lib():
         L.rs_shift_topk.argtypes = [_vp, _vp, _vp, _i32, _i32, _i32, _i32, _i32, ctypes.c_int,
                                     ctypes.c_int, _vp, _vp, _vp, _vp, ctypes.c_size_t, _vp]
         L.rs_shift_topk.restype = ctypes.c_int
+        L.rs_pack_linear.argtypes = [_vp, _vp, _i32, _i32, ctypes.c_int, _vp]
+        L.rs_pack_linear.restype = ctypes.c_int
+        L.rs_linear_fwd.argtypes = [_vp, _vp, _vp, _vp, _vp, _i64, _i32, _i32, ctypes.c_int, ctypes.c_int, _vp]
+        L.rs_linear_fwd.restype = ctypes.c_int
         L.rs_packed_weights_size.argtypes = [ctypes.POINTER(RsBlockCfg)]
         L.rs_packed_weights_size.restype = ctypes.c_size_t
         L.rs_pack_weights.argtypes = [ctypes.POINTER(RsBlockCfg), ctypes.POINTER(RsBlockWeights), _vp, _vp]
@@ -173,6 +178,20 @@ def rs_shift_topk(f_out, f_in, src, n_prefix, n_keep, scores, kept_idx, gathered
     _check(lib().rs_shift_topk(_ptr(f_out), _ptr(f_in), _ptr(src), B, N, D, n_prefix, n_keep, dist,
                                dtype_code(f_in.dtype), _ptr(scores), _ptr(kept_idx), _ptr(gathered),
                                _ptr(workspace), ws_bytes, _stream(stream)))
+
+
+def rs_pack_linear(w, wt, stream=None) -> None:
+    """w [K, N] -> wt [N, K] (bf16; a no-op for fp32, whose GEMM reads w directly)."""
+    K, N = w.shape
+    _check(lib().rs_pack_linear(_ptr(w), _ptr(wt), K, N, dtype_code(w.dtype), _stream(stream)))
+
+
+def rs_linear_fwd(a, w, bias, res, out, epi=RS_EPI_BIAS, stream=None) -> None:
+    """out [M, N] = epilogue(a [M, K] @ W + bias); w is the packed [N, K] tensor for bf16, [K, N] for fp32."""
+    M, K = a.shape
+    N = out.shape[1]
+    _check(lib().rs_linear_fwd(_ptr(a), _ptr(w), _ptr(bias), _ptr(res), _ptr(out), M, N, K, epi,
+                               dtype_code(a.dtype), _stream(stream)))
 
 
 def rs_packed_weights_size(cfg: RsBlockCfg) -> int:

@@ -176,17 +176,15 @@ __global__ __launch_bounds__(256, 1) void gemm_bf16_kernel(
     RS_GEMM_DMA(stage0, 0)
     RS_GEMM_SYNC()
     int kt = 0;
-    for (; kt + 2 < KT; kt += 2) {  // tiles kt+1 and kt+2 both exist
+    for (; kt + 1 < KT; kt += 2) {  // pairs of tiles: kt from stage0, kt+1 from stage1
         RS_GEMM_COMPUTE(stage0, RS_GEMM_DMA(stage1, kt + 1), 1)
         RS_GEMM_SYNC()
-        RS_GEMM_COMPUTE(stage1, RS_GEMM_DMA(stage0, kt + 2), 1)
+        // past the last tile the copy is aimed beyond the resource: it fetches nothing
+        const int nxt = kt + 2 < KT ? kt + 2 : (0x7ff00000 / (BK * 2));
+        RS_GEMM_COMPUTE(stage1, RS_GEMM_DMA(stage0, nxt), 1)
         RS_GEMM_SYNC()
     }
-    if (kt + 2 == KT) {  // two tiles left
-        RS_GEMM_COMPUTE(stage0, RS_GEMM_DMA(stage1, kt + 1), 1)
-        RS_GEMM_SYNC()
-        RS_GEMM_COMPUTE(stage1, , 0)
-    } else {             // one tile left
+    if (KT & 1) {  // odd tile count: the last tile is already in stage0
         RS_GEMM_COMPUTE(stage0, , 0)
     }
 #undef RS_GEMM_DMA
@@ -196,82 +194,85 @@ __global__ __launch_bounds__(256, 1) void gemm_bf16_kernel(
 #undef RS_GEMM_COMPUTE
 #undef RS_GEMM_SYNC
 
-    // ---- epilogue.  Lane (l32, g) owns token row m = .. + l32; register 4*q + e of tile (i, j)
-    //      is output feature n = .. + 32*i + 8*q + 4*g + e.  After the elementwise work the two
-    //      half-waves swap quads (v_permlane32_swap) so that every lane stores 8 consecutive
-    //      features (16 bytes): g = 0 takes the even q of a pair, g = 1 the odd one.
+    // ---- epilogue, staged through LDS so that global traffic is row-contiguous.
+    // Accumulator layout: lane (l32, g) owns token row l32 of each 32-row group; register
+    // 4*q + e of tile (i, j) is feature 32*i + 8*q + 4*g + e.  Per 32-row group j the wave writes
+    // its 32 x WN fp32 block into a private LDS region (row pitch WN*4 + 16 bytes: conflict
+    // free), then re-reads it with 16 lanes per row, 8 consecutive features per lane; bias,
+    // GELU, residual, the shift partial sums and the bf16 rounding happen on that layout, and
+    // every global load/store instruction covers whole 16 * WN / 8-byte row segments.
+    __syncthreads();  // every wave is done with the K-loop stages: reuse them
+    {
+        constexpr int PITCH = WN * 4 + 16;         // bytes per staged row
+        constexpr int LPR = WN / 8;                // lanes per row on the way out (16 for WN = 128)
+        constexpr int RPS = 64 / LPR;              // rows per step
+        static_assert(32 * PITCH <= STAGE / 2, "epilogue staging does not fit");
+        unsigned char* ep = (wave < 2 ? stage0 : stage1) + (wave & 1) * (STAGE / 2);
+        const int oc = (lane % LPR) * 8;           // this lane's first feature inside the wave tile
+        const int orow = lane / LPR;
+        const int n = n0 + wn * WN + oc;
+        const bool n_ok = n < N;                   // N % 8 == 0
+        float bv[8];
 #pragma unroll
-    for (int j = 0; j < TM; ++j) {
-        const int m = m0 + wm * WM + j * 32 + l32;
-        const bool m_ok = m < M;
-        float p0 = 0.f, p1 = 0.f, p2 = 0.f;  // shift partial sums of this row over the wave's columns
+        for (int e = 0; e < 8; ++e) bv[e] = 0.f;
+        if (bias && n_ok) Elem<bf16raw>::load8(bias + n, bv);
 #pragma unroll
-        for (int i = 0; i < TN; ++i) {
-            const int nb = n0 + wn * WN + i * 32;
-            uint32_t d0[4], d1[4];
+        for (int j = 0; j < TM; ++j) {
 #pragma unroll
-            for (int q = 0; q < 4; ++q) {
-                const int n = nb + q * 8 + g * 4;
-                float v[4];
+            for (int i = 0; i < TN; ++i)
 #pragma unroll
-                for (int e = 0; e < 4; ++e) v[e] = acc[i][j][q * 4 + e];
-                if (n < N) {  // N % 8 == 0: an 8-wide group is fully inside or fully outside
-                    if (bias) {
-                        uint2 b = *reinterpret_cast<const uint2*>(bias + n);
-                        v[0] += __uint_as_float(b.x << 16); v[1] += __uint_as_float(b.x & 0xffff0000u);
-                        v[2] += __uint_as_float(b.y << 16); v[3] += __uint_as_float(b.y & 0xffff0000u);
-                    }
-                    if (EPI == EPI_BIAS_GELU) {
+                for (int q = 0; q < 4; ++q) {
+                    f32x4 v = {acc[i][j][4 * q], acc[i][j][4 * q + 1], acc[i][j][4 * q + 2], acc[i][j][4 * q + 3]};
+                    *reinterpret_cast<f32x4*>(ep + l32 * PITCH + (i * 32 + q * 8 + g * 4) * 4) = v;
+                }
 #pragma unroll
-                        for (int e = 0; e < 4; ++e) v[e] = gelu_fast(v[e]);
-                    }
-                    if (EPI == EPI_BIAS_RES || EPI == EPI_BIAS_RES_SHIFT) {
-                        float r[4] = {0.f, 0.f, 0.f, 0.f};
-                        if (m_ok) {
-                            uint2 rr = *reinterpret_cast<const uint2*>(res + (int64_t)m * N + n);
-                            r[0] = __uint_as_float(rr.x << 16); r[1] = __uint_as_float(rr.x & 0xffff0000u);
-                            r[2] = __uint_as_float(rr.y << 16); r[3] = __uint_as_float(rr.y & 0xffff0000u);
+            for (int st = 0; st < 32 / RPS; ++st) {
+                const int r = st * RPS + orow;
+                const int m = m0 + wm * WM + j * 32 + r;
+                const bool ok = m < M && n_ok;
+                float v[8];
+                {
+                    const f32x4 lo = *reinterpret_cast<const f32x4*>(ep + r * PITCH + oc * 4);
+                    const f32x4 hi = *reinterpret_cast<const f32x4*>(ep + r * PITCH + oc * 4 + 16);
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) { v[e] = lo[e] + bv[e]; v[4 + e] = hi[e] + bv[4 + e]; }
+                }
+                if (EPI == EPI_BIAS_GELU) {
+#pragma unroll
+                    for (int e = 0; e < 8; ++e) v[e] = gelu_fast(v[e]);
+                }
+                float p0 = 0.f, p1 = 0.f, p2 = 0.f;
+                if (EPI == EPI_BIAS_RES || EPI == EPI_BIAS_RES_SHIFT) {
+                    float rr[8];
+#pragma unroll
+                    for (int e = 0; e < 8; ++e) rr[e] = 0.f;
+                    if (ok) Elem<bf16raw>::load8(res + (int64_t)m * N + n, rr);
+                    if (EPI == EPI_BIAS_RES_SHIFT && ok) {
+#pragma unroll
+                        for (int e = 0; e < 8; ++e) {
+                            if (DIST == RS_DIST_L2) { float d = v[e] - rr[e]; p0 += d * d; }
+                            else if (DIST == RS_DIST_L1) { p0 += fabsf(v[e] - rr[e]); }
+                            else { p0 += v[e] * rr[e]; p1 += v[e] * v[e]; p2 += rr[e] * rr[e]; }
                         }
-                        if (EPI == EPI_BIAS_RES_SHIFT) {
+                    }
 #pragma unroll
-                            for (int e = 0; e < 4; ++e) {
-                                if (DIST == RS_DIST_L2) { float d = v[e] - r[e]; p0 += d * d; }
-                                else if (DIST == RS_DIST_L1) { p0 += fabsf(v[e] - r[e]); }
-                                else { p0 += v[e] * r[e]; p1 += v[e] * v[e]; p2 += r[e] * r[e]; }
-                            }
-                        }
+                    for (int e = 0; e < 8; ++e) v[e] += rr[e];
+                }
+                if (ok) Elem<bf16raw>::store8(out + (int64_t)m * N + n, v);
+                if (EPI == EPI_BIAS_RES_SHIFT) {
+                    // sum over the LPR lanes that share the row (fixed butterfly order)
 #pragma unroll
-                        for (int e = 0; e < 4; ++e) v[e] += r[e];
+                    for (int off = LPR / 2; off >= 1; off >>= 1) {
+                        p0 += __shfl_xor(p0, off, 64);
+                        if (DIST == RS_DIST_COS) { p1 += __shfl_xor(p1, off, 64); p2 += __shfl_xor(p2, off, 64); }
+                    }
+                    if ((lane % LPR) == 0 && m < M) {
+                        const int slot = (n0 + wn * WN) / WN;
+                        float* dst = partials + ((int64_t)m * slots + slot) * kShiftLanes;
+                        dst[0] = p0;
+                        if (DIST == RS_DIST_COS) { dst[1] = p1; dst[2] = p2; }
                     }
                 }
-                d0[q] = pack2bf(v[0], v[1]);
-                d1[q] = pack2bf(v[2], v[3]);
-            }
-#pragma unroll
-            for (int t = 0; t < 2; ++t) {
-                // swap: lanes g=0 give their odd quad and receive the partner's even quad
-                auto s0 = __builtin_amdgcn_permlane32_swap(d0[2 * t], d0[2 * t + 1], false, false);
-                auto s1 = __builtin_amdgcn_permlane32_swap(d1[2 * t], d1[2 * t + 1], false, false);
-                const int n = nb + (2 * t + g) * 8;
-                if (m_ok && n < N) {
-                    uint4 o;
-                    o.x = s0[0]; o.y = s1[0]; o.z = s0[1]; o.w = s1[1];
-                    *reinterpret_cast<uint4*>(out + (int64_t)m * N + n) = o;
-                }
-            }
-        }
-        if (EPI == EPI_BIAS_RES_SHIFT) {
-            // the two half-waves hold interleaved column quads of the same rows
-            p0 += __shfl_xor(p0, 32, 64);
-            if (DIST == RS_DIST_COS) {
-                p1 += __shfl_xor(p1, 32, 64);
-                p2 += __shfl_xor(p2, 32, 64);
-            }
-            if (g == 0 && m_ok) {
-                const int slot = (n0 + wn * WN) / WN;
-                float* dst = partials + ((int64_t)m * slots + slot) * kShiftLanes;
-                dst[0] = p0;
-                if (DIST == RS_DIST_COS) { dst[1] = p1; dst[2] = p2; }
             }
         }
     }

@@ -45,11 +45,11 @@ static bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 
 
 // ---- optional per-kernel timing with HIP events on the caller's stream ---------
 enum KernelClass { K_PACK = 0, K_LN, K_GEMM_QKV, K_ATTN, K_GEMM_PROJ, K_GEMM_FC1, K_GEMM_FC2, K_SCORE,
-                   K_SELECT, K_GATHER, K_COUNT };
+                   K_SELECT, K_GATHER, K_LINEAR, K_COUNT };
 static_assert(K_COUNT == RS_PROFILE_CLASSES, "header and library disagree on the class count");
 static const char* const kClassNames[K_COUNT] = {"pack_weights", "layernorm", "gemm_qkv", "attention",
                                                  "gemm_proj", "gemm_fc1", "gemm_fc2", "shift_score",
-                                                 "select", "gather"};
+                                                 "select", "gather", "linear"};
 struct ProfRec { int cls; hipEvent_t start, stop; };
 static struct {
     std::mutex mu;
@@ -282,6 +282,36 @@ rs_status rs_pack_weights(const rs_block_cfg* cfg, const rs_block_weights* w, vo
     RS_REQUIRE(packed_out != nullptr && aligned16(packed_out), RS_ERR_INVALID_ARG,
                "packed_out must be a 16-byte aligned buffer");
     return pack_into(cfg, w, packed_out, (hipStream_t)hip_stream);
+}
+
+rs_status rs_pack_linear(const void* w, void* wt, int32_t K, int32_t N, rs_dtype dtype, void* hip_stream) {
+    RS_REQUIRE(dtype == RS_F32 || dtype == RS_BF16, RS_ERR_INVALID_ARG, "unknown dtype %d", (int)dtype);
+    RS_REQUIRE(K > 0 && N > 0, RS_ERR_INVALID_ARG, "K and N must be positive");
+    if (dtype == RS_F32) return RS_OK;  // the fp32 path reads the caller's layout
+    RS_REQUIRE(w && wt && w != wt, RS_ERR_INVALID_ARG, "w and wt must be distinct non-NULL buffers");
+    hipStream_t st = (hipStream_t)hip_stream;
+    RS_LAUNCH_K(K_PACK, st, launch_pack_transpose(w, wt, K, N, st));
+    return RS_OK;
+}
+
+rs_status rs_linear_fwd(const void* a, const void* w, const void* bias, const void* res, void* out, int64_t M,
+                        int32_t N, int32_t K, rs_epilogue epi, rs_dtype dtype, void* hip_stream) {
+    RS_REQUIRE(dtype == RS_F32 || dtype == RS_BF16, RS_ERR_INVALID_ARG, "unknown dtype %d", (int)dtype);
+    RS_REQUIRE(epi == RS_EPI_BIAS || epi == RS_EPI_BIAS_GELU || epi == RS_EPI_BIAS_RES, RS_ERR_INVALID_ARG,
+               "unknown epilogue %d", (int)epi);
+    RS_REQUIRE(M >= 0 && M < ((int64_t)1 << 31), RS_ERR_INVALID_ARG, "M out of range");
+    RS_REQUIRE(N > 0 && K > 0, RS_ERR_INVALID_ARG, "N and K must be positive");
+    RS_REQUIRE(N % 64 == 0 && K % 64 == 0, RS_ERR_UNSUPPORTED, "N and K must be multiples of 64");
+    if (M == 0) return RS_OK;
+    RS_REQUIRE(a && w && out, RS_ERR_INVALID_ARG, "a, w and out must not be NULL");
+    RS_REQUIRE(epi != RS_EPI_BIAS_RES || res, RS_ERR_INVALID_ARG, "res must not be NULL for RS_EPI_BIAS_RES");
+    RS_REQUIRE(out != a, RS_ERR_INVALID_ARG, "out must not alias a");
+    RS_REQUIRE(aligned16(a) && aligned16(w) && aligned16(bias) && aligned16(res) && aligned16(out),
+               RS_ERR_INVALID_ARG, "tensors must be 16-byte aligned");
+    hipStream_t st = (hipStream_t)hip_stream;
+    const GemmEpilogue e = epi == RS_EPI_BIAS ? EPI_BIAS : epi == RS_EPI_BIAS_GELU ? EPI_BIAS_GELU : EPI_BIAS_RES;
+    RS_LAUNCH_K(K_LINEAR, st, launch_gemm(dtype, e, RS_DIST_L2, a, w, bias, res, out, nullptr, M, N, K, st));
+    return RS_OK;
 }
 
 size_t rs_block_workspace_size(const rs_block_cfg* cfg) {
