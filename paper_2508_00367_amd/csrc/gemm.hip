@@ -18,12 +18,15 @@ namespace rs {
 // bf16 MFMA GEMM:  out[m, n] = epi( sum_k a[m, k] * wt[n, k] )
 //   a  : [M, K] bf16 (token rows),  wt : [N, K] bf16 (packed weights),  K % 64 == 0.
 // Workgroup tile BM x BN, K step 64, WGM x WGN waves, LDS double buffered.
-// LDS rows are 64 bf16 = 8 chunks of 16 B; chunk c of row r sits at c ^ (r & 7) so that
-// the 32 rows a half-wave reads for one MFMA operand spread over all banks.
+// LDS rows are 64 bf16 = 8 slots of 16 B; chunk c of row r sits in slot c ^ ((r ^ (r >> 3)) & 7).
+// The LDS has 64 banks of 4 bytes and serves a 16-byte-per-lane read 16 lanes at a time, so the
+// 16 consecutive rows those lanes read for one MFMA operand must fall into 16 different
+// 16-byte bank groups: the row parity picks the 128-byte half, the XOR makes the slots of rows
+// r and r + 8 differ (measured: zero SQ_LDS_BANK_CONFLICT, against every second cycle with
+// the plain c ^ (r & 7)).
 // ---------------------------------------------------------------------------
 constexpr int BK = 64;
 
-__device__ __forceinline__ int swz(int row, int chunk) { return row * 128 + ((chunk ^ (row & 7)) << 4); }
 
 // Exact-erf GELU x * Phi(x) with erf from the 5-term rational/exponential form of
 // Abramowitz & Stegun 7.1.26 (|error| < 1.5e-7 on erf): 2 transcendental + ~12 plain ops,
@@ -73,6 +76,7 @@ __global__ __launch_bounds__(256, 1) void gemm_bf16_kernel(
     constexpr int TM = WM / 32, TN = WN / 32;   // MFMA tiles per wave
     constexpr int A_LOADS = BM / 32, W_LOADS = BN / 32;  // 1 KiB wave copies per stage and wave
     constexpr int STAGE = (BM + BN) * 128;
+    static_assert(BM % 128 == 0 && BN % 128 == 0, "wave tiles must be multiples of 64 rows");
 
     __shared__ __attribute__((aligned(1024))) unsigned char stage0[STAGE];
     __shared__ __attribute__((aligned(1024))) unsigned char stage1[STAGE];
@@ -100,7 +104,9 @@ __global__ __launch_bounds__(256, 1) void gemm_bf16_kernel(
     const __amdgpu_buffer_rsrc_t rs_a = make_rsrc(a + (int64_t)m0 * K, (int64_t)(M - m0) * K * 2);
     const __amdgpu_buffer_rsrc_t rs_w = make_rsrc(wt + (int64_t)n0 * K, (int64_t)(N - n0) * K * 2);
     const int ld_r = lane >> 3;
-    const int voff = ((wave * 8 + ld_r) * K + (((lane & 7) ^ ld_r) << 3)) * 2;
+    // slot -> chunk XOR of LDS row 32*i + 8*wave + ld_r is ld_r ^ ((4*i + wave) & 7): two cases by parity of i
+    const int voff_e = ((wave * 8 + ld_r) * K + (((lane & 7) ^ ld_r ^ wave) << 3)) * 2;
+    const int voff_o = ((wave * 8 + ld_r) * K + (((lane & 7) ^ ld_r ^ wave ^ 4) << 3)) * 2;
     const int pass_bytes = 32 * K * 2;
 
     f32x16 acc[TN][TM];
@@ -113,23 +119,24 @@ __global__ __launch_bounds__(256, 1) void gemm_bf16_kernel(
 
     const int KT = K / BK;
     const int a_row0 = wm * WM + l32, w_row0 = wn * WN + l32;
-    const int sw7 = l32 & 7;  // (row & 7) of every operand row of this lane
+    // slot XOR of operand row 32*t + l32 (tile index t): (l32 ^ (l32 >> 3) ^ 4*(t & 1)) & 7
+    const int sw_e = (l32 ^ (l32 >> 3)) & 7, sw_o = sw_e ^ 4;
 
 #define RS_GEMM_DMA(stage_, kt_)                                                                          \
     {                                                                                                     \
         const int kb_ = (kt_) * (BK * 2);                                                                 \
         _Pragma("unroll") for (int i = 0; i < A_LOADS; ++i)                                               \
-            dma16(rs_a, (stage_) + (i * 32 + wave * 8) * 128, voff, i * pass_bytes + kb_);                \
+            dma16(rs_a, (stage_) + (i * 32 + wave * 8) * 128, (i & 1) ? voff_o : voff_e, i * pass_bytes + kb_);                \
         _Pragma("unroll") for (int i = 0; i < W_LOADS; ++i)                                               \
-            dma16(rs_w, (stage_) + (BM + i * 32 + wave * 8) * 128, voff, i * pass_bytes + kb_);           \
+            dma16(rs_w, (stage_) + (BM + i * 32 + wave * 8) * 128, (i & 1) ? voff_o : voff_e, i * pass_bytes + kb_);           \
     }
 #define RS_GEMM_LOAD_FRAGS(f_, stage_, kk_)                                                               \
     {                                                                                                     \
-        const int co_ = ((((kk_) * 2 + g) ^ sw7) << 4);                                                   \
+        const int ce_ = ((((kk_) * 2 + g) ^ sw_e) << 4), co_ = ((((kk_) * 2 + g) ^ sw_o) << 4);           \
         _Pragma("unroll") for (int i = 0; i < TN; ++i)                                                    \
-            (f_).w[i] = *reinterpret_cast<const bf16x8*>((stage_) + (BM + w_row0 + i * 32) * 128 + co_);  \
+            (f_).w[i] = *reinterpret_cast<const bf16x8*>((stage_) + (BM + w_row0 + i * 32) * 128 + ((i & 1) ? co_ : ce_)); \
         _Pragma("unroll") for (int j = 0; j < TM; ++j)                                                    \
-            (f_).a[j] = *reinterpret_cast<const bf16x8*>((stage_) + (a_row0 + j * 32) * 128 + co_);       \
+            (f_).a[j] = *reinterpret_cast<const bf16x8*>((stage_) + (a_row0 + j * 32) * 128 + ((j & 1) ? co_ : ce_)); \
     }
 #define RS_GEMM_MFMA(f_)                                                                                  \
     {                                                                                                     \
