@@ -208,7 +208,7 @@ def main():
     if not a.no_cpu_baseline:
         import oracle
         per_img_gflop = total_flops / B / 1e9
-        ns = a.cpu_sample or max(1, min(B, int(round(16 * 26.6 / per_img_gflop)) or 1))
+        ns = a.cpu_sample or max(1, min(B, int(round(64 * 26.6 / per_img_gflop)) or 1))
         xs = si.round_to_bf16(si.tokens(0, B, N, D)[:ns]).astype(np.float64)
         wts = [{k: si.round_to_bf16(v) for k, v in si.block_weights(0, l, D, Dm).items()} for l in range(L)]
         t0 = time.perf_counter()
