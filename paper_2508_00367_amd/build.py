@@ -9,12 +9,13 @@ from concurrent.futures import ThreadPoolExecutor
 HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
-OBJ = os.path.join(HERE, "_build")
-LIB = os.path.join(HERE, "librs_hip.so")
+OBJ = os.environ.get("RS_OBJ_DIR", os.path.join(HERE, "_build"))
+LIB = os.environ.get("RS_LIB_OUT", os.path.join(HERE, "librs_hip.so"))   # override: experiments only
 SOURCES = ["rs_api.hip", "layernorm.hip", "gemm.hip", "attention.hip", "prune.hip"]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-fvisibility=hidden",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
-         "-I" + os.path.join(ROOT, "include"), "-I" + CSRC, "-Wall", "-Wno-unused-function"]
+         "-I" + os.path.join(ROOT, "include"), "-I" + CSRC, "-Wall", "-Wno-unused-function",
+         *os.environ.get("RS_EXTRA_HIPCC_FLAGS", "").split()]
 
 
 def _compile(src: str) -> str:

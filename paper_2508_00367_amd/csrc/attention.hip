@@ -198,6 +198,162 @@ __global__ __launch_bounds__(256) void attention_bf16_kernel(
 }
 
 // ---------------------------------------------------------------------------
+// Short sequences (N <= 256, every image-classification block): one workgroup of 8 waves per
+// (image, head).  K (N x 64) and V^T (64 x N) of the head are copied into LDS once, one
+// barrier, then wave w runs query rows 32w .. 32w+31 against all key tiles without further
+// synchronisation.  Against the tiled kernel this reads K and V once instead of once per
+// query tile and has no per-tile barrier or staging latency; two workgroups share a CU, so
+// one wave's exp/max/sum work runs under another's MFMAs.
+// LDS: K rows of 128 bytes, chunk c of row r in slot c ^ ((r ^ r>>3) & 7); V^T rows of 512
+// bytes (256 key positions), 16-byte chunk c of channel row d in slot c ^ ((d ^ d>>3) & 15):
+// both the 16-lane operand reads and the transposing 4-byte writes are bank-conflict free.
+// ---------------------------------------------------------------------------
+constexpr int SM_MAXN = 256;
+
+__device__ __forceinline__ int vt_off(int d, int chunk) { return d * 512 + ((chunk ^ ((d ^ (d >> 3)) & 15)) << 4); }
+
+__global__ __launch_bounds__(512) void attention_bf16_small_kernel(
+    const bf16raw* __restrict__ q, const bf16raw* __restrict__ k, const bf16raw* __restrict__ v,
+    bf16raw* __restrict__ o, int N, int64_t sb, int64_t sn, int64_t sh, int64_t osb, int64_t osn,
+    int64_t osh, float scale_log2e) {
+    __shared__ __attribute__((aligned(16))) unsigned char s_k[SM_MAXN * 128];
+    __shared__ __attribute__((aligned(16))) unsigned char s_vt[DH * 512];
+
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int l32 = lane & 31, g = lane >> 5;
+    const int b = blockIdx.y, h = blockIdx.x;
+    const int64_t base = (int64_t)b * sb + (int64_t)h * sh;
+    const bf16raw* kb = k + base;
+    const bf16raw* vb = v + base;
+    const int KT = (N + ATT_BN - 1) / ATT_BN;   // key tiles of 64
+    const int NP = KT * ATT_BN;                 // keys including the padding of the last tile
+
+    // ---- K -> LDS: 16-byte chunk (tid & 7) of key rows (tid >> 3) + 64 i
+    {
+        const int ld_chunk = tid & 7, ld_row = tid >> 3;
+        for (int r = ld_row; r < NP; r += 64) {
+            const int kr = r < N ? r : N - 1;  // padded keys are masked to -inf below
+            const uint4 t = *reinterpret_cast<const uint4*>(kb + (int64_t)kr * sn + ld_chunk * 8);
+            *reinterpret_cast<uint4*>(&s_k[att_swz(r, ld_chunk)]) = t;
+        }
+    }
+    // ---- V -> LDS transposed.  Thread: channel chunk (tid & 7), key positions 2a, 2a+1 with
+    //      a = (tid >> 3) + 64 i; position p = 16T + 8g' + 4u + i  <->  key 16T + 8u + 4g' + i
+    {
+        const int dc = tid & 7;
+        for (int a2 = tid >> 3; 2 * a2 < NP; a2 += 64) {
+            const int vpos = 2 * a2;
+            const int vkey = (vpos & ~15) | (((vpos >> 2) & 1) << 3) | (((vpos >> 3) & 1) << 2) | (vpos & 3);
+            uint4 r0 = make_uint4(0u, 0u, 0u, 0u), r1 = r0;  // keys past the end contribute exact zeros
+            if (vkey < N) r0 = *reinterpret_cast<const uint4*>(vb + (int64_t)vkey * sn + dc * 8);
+            if (vkey + 1 < N) r1 = *reinterpret_cast<const uint4*>(vb + (int64_t)(vkey + 1) * sn + dc * 8);
+            const uint32_t w0[4] = {r0.x, r0.y, r0.z, r0.w};
+            const uint32_t w1[4] = {r1.x, r1.y, r1.z, r1.w};
+#pragma unroll
+            for (int e = 0; e < 8; ++e) {
+                const uint32_t lo = (e & 1) ? (w0[e >> 1] >> 16) : (w0[e >> 1] & 0xffffu);
+                const uint32_t hi = (e & 1) ? (w1[e >> 1] & 0xffff0000u) : (w1[e >> 1] << 16);
+                const int d = dc * 8 + e;
+                *reinterpret_cast<uint32_t*>(&s_vt[vt_off(d, vpos >> 3) + (vpos & 7) * 2]) = lo | hi;
+            }
+        }
+    }
+    const int q0 = wave * 32;
+    // Q fragments (B operand): column = query row q0 + l32, k-slots = channels 16 kk + 8 g ..
+    bf16x8 qf[4];
+    {
+        int qr = q0 + l32;
+        qr = qr < N ? qr : N - 1;
+        const bf16raw* qp = q + base + (int64_t)qr * sn;
+#pragma unroll
+        for (int kk = 0; kk < 4; ++kk) qf[kk] = *reinterpret_cast<const bf16x8*>(qp + kk * 16 + g * 8);
+    }
+    __syncthreads();
+    if (q0 >= N) return;  // whole-wave exit after the only barrier
+
+    f32x16 oacc[2];
+#pragma unroll
+    for (int i = 0; i < 2; ++i)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) oacc[i][r] = 0.f;
+    float m_run = -INFINITY, l_run = 0.f;
+
+    for (int kt = 0; kt < KT; ++kt) {
+        f32x16 sacc[2];
+#pragma unroll
+        for (int kb2 = 0; kb2 < 2; ++kb2) {
+#pragma unroll
+            for (int r = 0; r < 16; ++r) sacc[kb2][r] = 0.f;
+#pragma unroll
+            for (int kk = 0; kk < 4; ++kk) {
+                bf16x8 kf = *reinterpret_cast<const bf16x8*>(&s_k[att_swz(kt * 64 + kb2 * 32 + l32, kk * 2 + g)]);
+                sacc[kb2] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[kk], sacc[kb2], 0, 0, 0);
+            }
+        }
+        if ((kt + 1) * ATT_BN > N) {
+#pragma unroll
+            for (int kb2 = 0; kb2 < 2; ++kb2)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) {
+                    const int key = kt * ATT_BN + kb2 * 32 + (r >> 2) * 8 + g * 4 + (r & 3);
+                    if (key >= N) sacc[kb2][r] = -INFINITY;
+                }
+        }
+        float mx = sacc[0][0];
+#pragma unroll
+        for (int kb2 = 0; kb2 < 2; ++kb2)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) mx = fmaxf(mx, sacc[kb2][r]);
+        mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
+        const float m_new = fmaxf(m_run, mx);
+        const float alpha = exp2f((m_run - m_new) * scale_log2e);
+        const float mb = m_new * scale_log2e;
+        m_run = m_new;
+        float psum = 0.f;
+#pragma unroll
+        for (int kb2 = 0; kb2 < 2; ++kb2)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                const float p = __builtin_amdgcn_exp2f(fmaf(sacc[kb2][r], scale_log2e, -mb));
+                sacc[kb2][r] = p;
+                psum += p;
+            }
+        l_run = l_run * alpha + psum;
+#pragma unroll
+        for (int i = 0; i < 2; ++i)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) oacc[i][r] *= alpha;
+#pragma unroll
+        for (int t = 0; t < 4; ++t) {
+            const int kb2 = t >> 1, r0 = (t & 1) * 8;
+            union { uint32_t u[4]; bf16x8 v; } pf;
+#pragma unroll
+            for (int e = 0; e < 4; ++e) pf.u[e] = pack2bf(sacc[kb2][r0 + 2 * e], sacc[kb2][r0 + 2 * e + 1]);
+#pragma unroll
+            for (int db = 0; db < 2; ++db) {
+                bf16x8 vf = *reinterpret_cast<const bf16x8*>(&s_vt[vt_off(db * 32 + l32, 2 * (kt * 4 + t) + g)]);
+                oacc[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, pf.v, oacc[db], 0, 0, 0);
+            }
+        }
+    }
+    const float l_tot = l_run + __shfl_xor(l_run, 32, 64);
+    const float inv = 1.0f / l_tot;
+    const int qr = q0 + l32;
+    if (qr < N) {
+        bf16raw* op = o + (int64_t)b * osb + (int64_t)qr * osn + (int64_t)h * osh;
+#pragma unroll
+        for (int db = 0; db < 2; ++db)
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                uint2 w;
+                w.x = pack2bf(oacc[db][4 * j] * inv, oacc[db][4 * j + 1] * inv);
+                w.y = pack2bf(oacc[db][4 * j + 2] * inv, oacc[db][4 * j + 3] * inv);
+                *reinterpret_cast<uint2*>(op + db * 32 + j * 8 + g * 4) = w;
+            }
+    }
+}
+
+// ---------------------------------------------------------------------------
 // fp32 path: workgroup = 64 query rows of one (image, head), one row per thread;
 // K/V tiles of 32 keys in LDS, broadcast reads.
 // ---------------------------------------------------------------------------
@@ -289,7 +445,11 @@ hipError_t launch_attention(rs_dtype dt, const void* q, const void* k, const voi
                             int64_t osn, int64_t osh, float scale, hipStream_t s) {
     if (B == 0 || H == 0 || N == 0) return hipSuccess;
     const float scale_log2e = scale * 1.44269504088896340736f;
-    if (dt == RS_BF16) {
+    if (dt == RS_BF16 && N <= SM_MAXN) {
+        hipLaunchKernelGGL(attention_bf16_small_kernel, dim3(H, B), dim3(512), 0, s, (const bf16raw*)q,
+                           (const bf16raw*)k, (const bf16raw*)v, (bf16raw*)o, N, sb, sn, sh, osb, osn, osh,
+                           scale_log2e);
+    } else if (dt == RS_BF16) {
         dim3 grid((N + ATT_BM - 1) / ATT_BM, H, B);
         hipLaunchKernelGGL(attention_bf16_kernel, grid, dim3(256), 0, s, (const bf16raw*)q,
                            (const bf16raw*)k, (const bf16raw*)v, (bf16raw*)o, N, sb, sn, sh, osb, osn,

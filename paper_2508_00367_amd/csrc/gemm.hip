@@ -10,6 +10,8 @@
 // (residual, shift partial sums) stays inside a lane, and stores are 8-byte vectors.
 //
 // fp32 path: plain FMA tiles (parity configuration, true fp32 products).
+#include <stdlib.h>
+
 #include "common.hpp"
 
 namespace rs {
@@ -25,8 +27,6 @@ namespace rs {
 // r and r + 8 differ (measured: zero SQ_LDS_BANK_CONFLICT, against every second cycle with
 // the plain c ^ (r & 7)).
 // ---------------------------------------------------------------------------
-constexpr int BK = 64;
-
 
 // Exact-erf GELU x * Phi(x) with erf from the 5-term rational/exponential form of
 // Abramowitz & Stegun 7.1.26 (|error| < 1.5e-7 on erf): 2 transcendental + ~12 plain ops,
@@ -62,28 +62,49 @@ __device__ __forceinline__ __amdgpu_buffer_rsrc_t make_rsrc(const void* base, in
     return __builtin_amdgcn_make_buffer_rsrc(const_cast<void*>(base), 0, (int)(bytes < lim ? bytes : lim), 0x00020000);
 }
 
-// 256 threads = 2 x 2 waves; workgroup tile BM x BN (multiples of 64), wave tile BM/2 x BN/2.
-// Two LDS stages of (BM + BN) rows x 128 B; the next K tile streams from global memory
-// directly into the idle stage (no register staging) while the matrix cores work on the
-// current one.  Operand fragments are double buffered in registers and their LDS reads are
-// interleaved with the MFMAs of the previous K step.
-template <int BM, int BN, int EPI, int DIST>
-__global__ __launch_bounds__(256, 1) void gemm_bf16_kernel(
+// s_waitcnt immediate for "at most n vector-memory operations outstanding" (gfx9 encoding,
+// other counters left at their maximum).
+constexpr int vmcnt_imm(int n) { return (n & 15) | ((n >> 4) << 14) | 0x0F70; }
+
+// 256 threads = 2 x 2 waves; workgroup tile BM x BN, wave tile BM/2 x BN/2, K slice BK (32 or 64).
+// A ring of NSTAGE LDS stages of (BM + BN) rows x 2*BK bytes: K slices stream from global
+// memory directly into LDS (buffer_load ... lds, no register staging), NSTAGE-1 slices ahead of
+// the one the matrix cores work on.  Loads return in order, so "slice t has landed" is
+// s_waitcnt vmcnt(<loads issued after it>); one workgroup barrier per slice.  The slice count is
+// padded to a multiple of NSTAGE with copies aimed past the end of the buffer resource (they
+// deliver zeros), which keeps the loop free of tail branches.  Operand fragments are double
+// buffered in registers and each LDS read is interleaved with its share of the previous K step's
+// MFMAs (sched_group_barrier).  WPE = waves per SIMD the register budget must allow (2 = two
+// workgroups per CU, so one's epilogue and barrier waits hide behind the other's MFMAs).
+template <int BM, int BN, int BK, int NSTAGE, int WPE, int EPI, int DIST>
+__global__ __launch_bounds__(256, WPE) void gemm_bf16_kernel(
     const bf16raw* __restrict__ a, const bf16raw* __restrict__ wt, const bf16raw* __restrict__ bias,
     const bf16raw* __restrict__ res, bf16raw* __restrict__ out, float* __restrict__ partials,
-    int M, int N, int K, int tiles_m, int tiles_n, int slots) {
+    int M, int N, int K, int tiles_m, int tiles_n, int slots, int gm) {
     constexpr int WM = BM / 2, WN = BN / 2;     // wave tile
     constexpr int TM = WM / 32, TN = WN / 32;   // MFMA tiles per wave
-    constexpr int A_LOADS = BM / 32, W_LOADS = BN / 32;  // 1 KiB wave copies per stage and wave
-    constexpr int STAGE = (BM + BN) * 128;
+    constexpr int RB = BK * 2;                  // bytes per LDS row
+    constexpr int SPR = BK / 8;                 // 16-byte slots per row (4 or 8)
+    constexpr int RPI = 64 / SPR;               // rows one wave copy (1 KiB) covers
+    constexpr int A_LOADS = BM / RPI / 4, W_LOADS = BN / RPI / 4;  // wave copies per slice and wave
+    constexpr int LPW = A_LOADS + W_LOADS;
+    constexpr int KK = BK / 16;                 // MFMA K steps per slice
+    constexpr int STAGE = (BM + BN) * RB;
     static_assert(BM % 128 == 0 && BN % 128 == 0, "wave tiles must be multiples of 64 rows");
+    static_assert(BK == 32 || BK == 64, "K slice of 32 or 64");
+    static_assert(NSTAGE >= 2 && NSTAGE <= 4, "2 to 4 stages");
+    static_assert((NSTAGE - 2) * LPW <= 63, "vmcnt range");
 
     __shared__ __attribute__((aligned(1024))) unsigned char stage0[STAGE];
     __shared__ __attribute__((aligned(1024))) unsigned char stage1[STAGE];
+    __shared__ __attribute__((aligned(1024))) unsigned char stage2[NSTAGE > 2 ? STAGE : 16];
+    __shared__ __attribute__((aligned(1024))) unsigned char stage3[NSTAGE > 3 ? STAGE : 16];
 
-    // XCD-aware tile order: consecutive workgroup ids go round-robin to the 8 XCDs, so give
-    // each XCD a contiguous range of tiles; inside a range the n index runs fastest, so the
-    // workgroups of one XCD share an activation row block in that XCD's L2.
+    // Tile order.  Consecutive workgroup ids go round-robin to the 8 XCDs, each with its own
+    // 4 MB L2, so XCD x takes a contiguous range of the tile sequence.  The sequence walks the tile
+    // grid in groups of `gm` row panels, n-major inside a group (m fastest): the ~32 tiles an XCD
+    // runs at a time then share gm activation panels, which stay in its L2 while the weight
+    // panels stream past, instead of re-reading the whole weight matrix for every row panel.
     const int nblk = tiles_m * tiles_n;
     int bid = blockIdx.x;
     {
@@ -91,7 +112,15 @@ __global__ __launch_bounds__(256, 1) void gemm_bf16_kernel(
         const int q = nblk >> 3, r = nblk & 7;  // XCD x owns q (+1 if x < r) tiles
         bid = x * q + (x < r ? x : r) + j;
     }
-    const int tile_m = bid / tiles_n, tile_n = bid % tiles_n;
+    int tile_m, tile_n;
+    {
+        const int per_group = gm * tiles_n;
+        const int grp = bid / per_group, rem = bid - grp * per_group;
+        const int first_m = grp * gm;
+        const int gsz = min(tiles_m - first_m, gm);
+        tile_n = rem / gsz;
+        tile_m = first_m + rem - tile_n * gsz;
+    }
     const int m0 = tile_m * BM, n0 = tile_n * BN;
 
     const int tid = threadIdx.x, lane = tid & 63;
@@ -99,15 +128,27 @@ __global__ __launch_bounds__(256, 1) void gemm_bf16_kernel(
     const int wm = wave & 1, wn = wave >> 1;
     const int l32 = lane & 31, g = lane >> 5;
 
-    // global -> LDS: wave copy i of a wave fills LDS rows 32*i + 8*wave .. +7 (1 KiB, lane l at
-    // byte 16*l = row l/8, slot l%8); slot p of row r must hold global chunk p ^ (r & 7).
+    // LDS layout.  Chunk c (16 bytes = 8 k values) of row r sits in slot c ^ f(r).  gfx950's LDS has
+    // 64 banks of 4 bytes and serves a 16-byte-per-lane read 16 lanes at a time, so the 16
+    // consecutive rows those lanes read for one MFMA operand must fall into 16 different 16-byte
+    // bank groups of a 256-byte line:
+    //   128-byte rows (BK 64): f(r) = (r ^ (r >> 3)) & 7   (row parity picks the half line, the XOR
+    //                          makes rows r and r + 8 differ; measured 0 SQ_LDS_BANK_CONFLICT,
+    //                          against every second cycle with the plain r & 7)
+    //    64-byte rows (BK 32): f(r) = (r >> 2) & 3         (r & 3 picks the quarter line)
+    // global -> LDS: wave copy i of wave w fills rows (4*i + w)*RPI .. +RPI-1 (lane l: row l / SPR,
+    // slot l % SPR), so the lane fetches chunk (l % SPR) ^ f(row).
     const __amdgpu_buffer_rsrc_t rs_a = make_rsrc(a + (int64_t)m0 * K, (int64_t)(M - m0) * K * 2);
     const __amdgpu_buffer_rsrc_t rs_w = make_rsrc(wt + (int64_t)n0 * K, (int64_t)(N - n0) * K * 2);
-    const int ld_r = lane >> 3;
-    // slot -> chunk XOR of LDS row 32*i + 8*wave + ld_r is ld_r ^ ((4*i + wave) & 7): two cases by parity of i
-    const int voff_e = ((wave * 8 + ld_r) * K + (((lane & 7) ^ ld_r ^ wave) << 3)) * 2;
-    const int voff_o = ((wave * 8 + ld_r) * K + (((lane & 7) ^ ld_r ^ wave ^ 4) << 3)) * 2;
-    const int pass_bytes = 32 * K * 2;
+    const int ld_r = lane / SPR, ld_p = lane % SPR;
+    int voff_e, voff_o;  // lane byte offset for even / odd copy index i
+    if (SPR == 8) {
+        voff_e = ((wave * RPI + ld_r) * K + ((ld_p ^ ld_r ^ wave) << 3)) * 2;
+        voff_o = ((wave * RPI + ld_r) * K + ((ld_p ^ ld_r ^ wave ^ 4) << 3)) * 2;
+    } else {
+        voff_e = voff_o = ((wave * RPI + ld_r) * K + ((ld_p ^ ((ld_r >> 2) & 3)) << 3)) * 2;
+    }
+    const int pass_bytes = 4 * RPI * K * 2;
 
     f32x16 acc[TN][TM];
 #pragma unroll
@@ -117,26 +158,29 @@ __global__ __launch_bounds__(256, 1) void gemm_bf16_kernel(
 #pragma unroll
             for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
 
-    const int KT = K / BK;
+    const int S = K / BK;                                   // real slices
+    const int S_pad = (S + NSTAGE - 1) / NSTAGE * NSTAGE;   // loop trip count (zero slices at the end)
     const int a_row0 = wm * WM + l32, w_row0 = wn * WN + l32;
-    // slot XOR of operand row 32*t + l32 (tile index t): (l32 ^ (l32 >> 3) ^ 4*(t & 1)) & 7
-    const int sw_e = (l32 ^ (l32 >> 3)) & 7, sw_o = sw_e ^ 4;
+    // slot XOR of operand row 32*t + l32 (t = MFMA tile index inside the wave tile)
+    const int sw_e = SPR == 8 ? ((l32 ^ (l32 >> 3)) & 7) : ((l32 >> 2) & 3);
+    const int sw_o = SPR == 8 ? (sw_e ^ 4) : sw_e;
 
-#define RS_GEMM_DMA(stage_, kt_)                                                                          \
+// copies of K slice t_ into stage_; slices past the end are aimed beyond the resource
+#define RS_GEMM_DMA(stage_, t_)                                                                           \
     {                                                                                                     \
-        const int kb_ = (kt_) * (BK * 2);                                                                 \
+        const int kb_ = (t_) < S ? (t_) * RB : 0x7ff00000;                                                \
         _Pragma("unroll") for (int i = 0; i < A_LOADS; ++i)                                               \
-            dma16(rs_a, (stage_) + (i * 32 + wave * 8) * 128, (i & 1) ? voff_o : voff_e, i * pass_bytes + kb_);                \
+            dma16(rs_a, (stage_) + (i * 4 + wave) * 1024, (i & 1) ? voff_o : voff_e, i * pass_bytes + kb_); \
         _Pragma("unroll") for (int i = 0; i < W_LOADS; ++i)                                               \
-            dma16(rs_w, (stage_) + (BM + i * 32 + wave * 8) * 128, (i & 1) ? voff_o : voff_e, i * pass_bytes + kb_);           \
+            dma16(rs_w, (stage_) + BM * RB + (i * 4 + wave) * 1024, (i & 1) ? voff_o : voff_e, i * pass_bytes + kb_); \
     }
 #define RS_GEMM_LOAD_FRAGS(f_, stage_, kk_)                                                               \
     {                                                                                                     \
         const int ce_ = ((((kk_) * 2 + g) ^ sw_e) << 4), co_ = ((((kk_) * 2 + g) ^ sw_o) << 4);           \
         _Pragma("unroll") for (int i = 0; i < TN; ++i)                                                    \
-            (f_).w[i] = *reinterpret_cast<const bf16x8*>((stage_) + (BM + w_row0 + i * 32) * 128 + ((i & 1) ? co_ : ce_)); \
+            (f_).w[i] = *reinterpret_cast<const bf16x8*>((stage_) + (BM + w_row0 + i * 32) * RB + ((i & 1) ? co_ : ce_)); \
         _Pragma("unroll") for (int j = 0; j < TM; ++j)                                                    \
-            (f_).a[j] = *reinterpret_cast<const bf16x8*>((stage_) + (a_row0 + j * 32) * 128 + ((j & 1) ? co_ : ce_)); \
+            (f_).a[j] = *reinterpret_cast<const bf16x8*>((stage_) + (a_row0 + j * 32) * RB + ((j & 1) ? co_ : ce_)); \
     }
 #define RS_GEMM_MFMA(f_)                                                                                  \
     {                                                                                                     \
@@ -145,61 +189,66 @@ __global__ __launch_bounds__(256, 1) void gemm_bf16_kernel(
                 acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16((f_).w[i], (f_).a[j], acc[i][j], 0, 0, 0); \
     }
 // Scheduling recipe for one K step (one scheduling region): every LDS fragment read of the
-// next step is followed by `vm_` global->LDS copies and its share of this step's MFMAs.
+// next step is followed by its share of global->LDS copies (vm_) and of this step's MFMAs.
 #define RS_GEMM_INTERLEAVE(vm_)                                                                           \
     {                                                                                                     \
         _Pragma("unroll") for (int s_ = 0; s_ < TN + TM; ++s_) {                                          \
             __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);                                            \
-            if (vm_) __builtin_amdgcn_sched_group_barrier(0x020, (A_LOADS + W_LOADS) / (TN + TM), 0);     \
+            if (vm_) __builtin_amdgcn_sched_group_barrier(0x020, (LPW + TN + TM - 1) / (TN + TM), 0);     \
             __builtin_amdgcn_sched_group_barrier(0x008, (TN * TM) / (TN + TM), 0);                        \
         }                                                                                                 \
         __builtin_amdgcn_sched_barrier(0);                                                                \
     }
-// One K tile from `cur_`; DMA_ (may be empty) starts the copies of a later tile into the idle stage.
-#define RS_GEMM_COMPUTE(cur_, DMA_, has_dma_)                                                             \
+// One K slice from cur_: wait until it has landed, barrier, start the copies of the slice
+// NSTAGE-1 ahead into the stage every wave has just left, then the MFMAs.
+#define RS_GEMM_SLICE(cur_, nxt_, t_)                                                                     \
     {                                                                                                     \
+        __builtin_amdgcn_s_waitcnt(vmcnt_imm((NSTAGE - 2) * LPW));                                        \
+        __syncthreads();                                                                                  \
         Frags<TN, TM> f0, f1;                                                                             \
         RS_GEMM_LOAD_FRAGS(f0, cur_, 0)                                                                   \
         __builtin_amdgcn_sched_barrier(0);                                                                \
-        DMA_                                                                                              \
+        RS_GEMM_DMA(nxt_, (t_) + NSTAGE - 1)                                                              \
         RS_GEMM_LOAD_FRAGS(f1, cur_, 1)                                                                   \
         RS_GEMM_MFMA(f0)                                                                                  \
-        RS_GEMM_INTERLEAVE(has_dma_)                                                                      \
-        RS_GEMM_LOAD_FRAGS(f0, cur_, 2)                                                                   \
+        RS_GEMM_INTERLEAVE(1)                                                                             \
+        if (KK == 4) {                                                                                    \
+            RS_GEMM_LOAD_FRAGS(f0, cur_, 2)                                                               \
+            RS_GEMM_MFMA(f1)                                                                              \
+            RS_GEMM_INTERLEAVE(0)                                                                         \
+            RS_GEMM_LOAD_FRAGS(f1, cur_, 3)                                                               \
+            RS_GEMM_MFMA(f0)                                                                              \
+            RS_GEMM_INTERLEAVE(0)                                                                         \
+        }                                                                                                 \
         RS_GEMM_MFMA(f1)                                                                                  \
-        RS_GEMM_INTERLEAVE(0)                                                                             \
-        RS_GEMM_LOAD_FRAGS(f1, cur_, 3)                                                                   \
-        RS_GEMM_MFMA(f0)                                                                                  \
-        RS_GEMM_INTERLEAVE(0)                                                                             \
-        RS_GEMM_MFMA(f1)                                                                                  \
-    }
-// all of this wave's copies have landed, then every wave's
-#define RS_GEMM_SYNC()                       \
-    {                                        \
-        __builtin_amdgcn_s_waitcnt(0x0F70);  \
-        __syncthreads();                     \
+        __builtin_amdgcn_sched_barrier(0);                                                                \
     }
 
+    // prologue: slices 0 .. NSTAGE-2
     RS_GEMM_DMA(stage0, 0)
-    RS_GEMM_SYNC()
-    int kt = 0;
-    for (; kt + 1 < KT; kt += 2) {  // pairs of tiles: kt from stage0, kt+1 from stage1
-        RS_GEMM_COMPUTE(stage0, RS_GEMM_DMA(stage1, kt + 1), 1)
-        RS_GEMM_SYNC()
-        // past the last tile the copy is aimed beyond the resource: it fetches nothing
-        const int nxt = kt + 2 < KT ? kt + 2 : (0x7ff00000 / (BK * 2));
-        RS_GEMM_COMPUTE(stage1, RS_GEMM_DMA(stage0, nxt), 1)
-        RS_GEMM_SYNC()
+    if (NSTAGE > 2) RS_GEMM_DMA(stage1, 1)
+    if (NSTAGE > 3) RS_GEMM_DMA(stage2, 2)
+    for (int t = 0; t < S_pad; t += NSTAGE) {
+        if (NSTAGE == 2) {
+            RS_GEMM_SLICE(stage0, stage1, t)
+            RS_GEMM_SLICE(stage1, stage0, t + 1)
+        } else if (NSTAGE == 3) {
+            RS_GEMM_SLICE(stage0, stage2, t)
+            RS_GEMM_SLICE(stage1, stage0, t + 1)
+            RS_GEMM_SLICE(stage2, stage1, t + 2)
+        } else {
+            RS_GEMM_SLICE(stage0, stage3, t)
+            RS_GEMM_SLICE(stage1, stage0, t + 1)
+            RS_GEMM_SLICE(stage2, stage1, t + 2)
+            RS_GEMM_SLICE(stage3, stage2, t + 3)
+        }
     }
-    if (KT & 1) {  // odd tile count: the last tile is already in stage0
-        RS_GEMM_COMPUTE(stage0, , 0)
-    }
+    __builtin_amdgcn_s_waitcnt(vmcnt_imm(0));  // the trailing (empty) copies too: the stages get reused
 #undef RS_GEMM_DMA
 #undef RS_GEMM_LOAD_FRAGS
 #undef RS_GEMM_MFMA
 #undef RS_GEMM_INTERLEAVE
-#undef RS_GEMM_COMPUTE
-#undef RS_GEMM_SYNC
+#undef RS_GEMM_SLICE
 
     // ---- epilogue, staged through LDS so that global traffic is row-contiguous.
     // Accumulator layout: lane (l32, g) owns token row l32 of each 32-row group; register
@@ -213,8 +262,9 @@ __global__ __launch_bounds__(256, 1) void gemm_bf16_kernel(
         constexpr int PITCH = WN * 4 + 16;         // bytes per staged row
         constexpr int LPR = WN / 8;                // lanes per row on the way out (16 for WN = 128)
         constexpr int RPS = 64 / LPR;              // rows per step
-        static_assert(32 * PITCH <= STAGE / 2, "epilogue staging does not fit");
-        unsigned char* ep = (wave < 2 ? stage0 : stage1) + (wave & 1) * (STAGE / 2);
+        static_assert(32 * PITCH <= (NSTAGE >= 4 ? STAGE : STAGE / 2), "epilogue staging does not fit");
+        unsigned char* ep = NSTAGE >= 4 ? (wave == 0 ? stage0 : wave == 1 ? stage1 : wave == 2 ? stage2 : stage3)
+                                        : (wave < 2 ? stage0 : stage1) + (wave & 1) * (STAGE / 2);
         const int oc = (lane % LPR) * 8;           // this lane's first feature inside the wave tile
         const int orow = lane / LPR;
         const int n = n0 + wn * WN + oc;
@@ -287,7 +337,11 @@ __global__ __launch_bounds__(256, 1) void gemm_bf16_kernel(
 
 // Tile configuration of the bf16 GEMM.
 struct GemmCfg {
-    static constexpr int BM = 256, BN = 256;
+#ifndef RS_GEMM_CFG
+#define RS_GEMM_CFG 256, 256, 64, 2, 1
+#endif
+    static constexpr int P[5] = {RS_GEMM_CFG};
+    static constexpr int BM = P[0], BN = P[1], BK = P[2], NSTAGE = P[3], WPE = P[4];
     static constexpr int WN = BN / 2;
 };
 
@@ -297,9 +351,12 @@ static hipError_t launch_bf16(const void* a, const void* wt, const void* bias, c
     using C = GemmCfg;
     const int tiles_m = (int)((M + C::BM - 1) / C::BM), tiles_n = (N + C::BN - 1) / C::BN;
     const int slots = (tiles_n * C::BN) / C::WN;
-    hipLaunchKernelGGL((gemm_bf16_kernel<C::BM, C::BN, EPI, DIST>), dim3(tiles_m * tiles_n), dim3(256), 0, s,
-                       (const bf16raw*)a, (const bf16raw*)wt, (const bf16raw*)bias, (const bf16raw*)res,
-                       (bf16raw*)out, partials, (int)M, N, K, tiles_m, tiles_n, slots);
+    static const int gm_env = getenv("RS_GEMM_GM") ? atoi(getenv("RS_GEMM_GM")) : 8;
+    const int gm = gm_env;
+    hipLaunchKernelGGL((gemm_bf16_kernel<C::BM, C::BN, C::BK, C::NSTAGE, C::WPE, EPI, DIST>),
+                       dim3(tiles_m * tiles_n), dim3(256), 0, s, (const bf16raw*)a, (const bf16raw*)wt,
+                       (const bf16raw*)bias, (const bf16raw*)res, (bf16raw*)out, partials, (int)M, N, K,
+                       tiles_m, tiles_n, slots, gm);
     return hipGetLastError();
 }
 
