@@ -156,10 +156,12 @@ __global__ __launch_bounds__(256) void attention_bf16_kernel(
                 psum += p;
             }
         l_run = l_run * alpha + psum;
+        if (__ballot(alpha != 1.0f)) {  // the running maximum moved for some row of this wave
 #pragma unroll
-        for (int i = 0; i < 2; ++i)
+            for (int i = 0; i < 2; ++i)
 #pragma unroll
-            for (int r = 0; r < 16; ++r) oacc[i][r] *= alpha;
+                for (int r = 0; r < 16; ++r) oacc[i][r] *= alpha;
+        }
 
         // ---- O^T += V^T P^T, 16 keys per MFMA
 #pragma unroll
@@ -319,10 +321,12 @@ __global__ __launch_bounds__(512) void attention_bf16_small_kernel(
                 psum += p;
             }
         l_run = l_run * alpha + psum;
+        if (__ballot(alpha != 1.0f)) {  // the running maximum moved for some row of this wave
 #pragma unroll
-        for (int i = 0; i < 2; ++i)
+            for (int i = 0; i < 2; ++i)
 #pragma unroll
-            for (int r = 0; r < 16; ++r) oacc[i][r] *= alpha;
+                for (int r = 0; r < 16; ++r) oacc[i][r] *= alpha;
+        }
 #pragma unroll
         for (int t = 0; t < 4; ++t) {
             const int kb2 = t >> 1, r0 = (t & 1) * 8;

@@ -18,16 +18,15 @@ typedef float f32x4 __attribute__((ext_vector_type(4)));
 // ---- bf16 <-> fp32 -------------------------------------------------------
 __device__ __forceinline__ float bf2f(bf16raw b) { return __uint_as_float(((uint32_t)b) << 16); }
 
-// round-to-nearest-even; NaN stays NaN
-__device__ __forceinline__ bf16raw f2bf(float f) {
-    uint32_t u = __float_as_uint(f);
-    if ((u & 0x7fffffffu) > 0x7f800000u) return (bf16raw)0x7fc0;
-    u += 0x7fffu + ((u >> 16) & 1u);
-    return (bf16raw)(u >> 16);
-}
+// round-to-nearest-even, NaN stays NaN: the hardware conversion (v_cvt_pk_bf16_f32)
+typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+__device__ __forceinline__ bf16raw f2bf(float f) { return __builtin_bit_cast(bf16raw, (__bf16)f); }
 
 __device__ __forceinline__ uint32_t pack2bf(float lo, float hi) {
-    return (uint32_t)f2bf(lo) | ((uint32_t)f2bf(hi) << 16);
+    bf16x2 v;
+    v[0] = (__bf16)lo;
+    v[1] = (__bf16)hi;
+    return __builtin_bit_cast(uint32_t, v);
 }
 
 // Storage-type traits: load/store 8 consecutive elements as fp32.
