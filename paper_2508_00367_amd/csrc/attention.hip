@@ -21,27 +21,108 @@
 
 namespace rs {
 
-constexpr int ATT_BM = 128;  // query rows per workgroup (4 waves x 32)
+constexpr int ATT_BM = 256;  // query rows per workgroup (8 waves x 32)
 constexpr int ATT_BN = 64;   // keys per tile
 constexpr int DH = 64;
 
-// 16-byte chunk `c` (0..7) of 128-byte LDS row `r`; the XOR spreads both the row-wise
-// operand reads and the transposed V writes over the banks.
+// 16-byte chunk `c` (0..7) of 128-byte LDS row `r`; the XOR spreads both the 16-lane operand
+// reads and the transposed V writes over the 64 banks (rows r and r + 8 must differ).
 __device__ __forceinline__ int att_swz(int r, int c) { return r * 128 + (((c ^ r ^ (r >> 3)) & 7) << 4); }
 
-__global__ __launch_bounds__(256) void attention_bf16_kernel(
+typedef __attribute__((address_space(3))) void* att_lds_ptr;
+
+// One query-row block of 32 rows against one resident tile of 64 keys: S^T = K Q^T, online
+// softmax in registers (one lane = one query row, half of the tile's keys), O^T += V^T P^T.
+// `sk`: K tile [64 keys][128 B] swizzled; `svt`: V^T tile [64 channels][64 key positions].
+template <bool MASK>
+__device__ __forceinline__ void att_tile(const unsigned char* sk, const unsigned char* svt,
+                                         const bf16x8 (&qf)[4], f32x16 (&oacc)[2], float& m_run,
+                                         float& l_run, int key0, int N, float scale_log2e, int l32, int g) {
+    f32x16 sacc[2];
+#pragma unroll
+    for (int kb2 = 0; kb2 < 2; ++kb2)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) sacc[kb2][r] = 0.f;
+#pragma unroll
+    for (int kk = 0; kk < 4; ++kk)
+#pragma unroll
+        for (int kb2 = 0; kb2 < 2; ++kb2) {  // two independent accumulator chains alternate
+            const bf16x8 kf = *reinterpret_cast<const bf16x8*>(sk + att_swz(kb2 * 32 + l32, kk * 2 + g));
+            sacc[kb2] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[kk], sacc[kb2], 0, 0, 0);
+        }
+    if (MASK) {  // keys past the end (last tile only)
+#pragma unroll
+        for (int kb2 = 0; kb2 < 2; ++kb2)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                const int key = key0 + kb2 * 32 + (r >> 2) * 8 + g * 4 + (r & 3);
+                if (key >= N) sacc[kb2][r] = -INFINITY;
+            }
+    }
+    float mx = fmaxf(sacc[0][0], sacc[1][0]);
+#pragma unroll
+    for (int r = 1; r < 16; ++r) mx = fmaxf(fmaxf(mx, sacc[0][r]), sacc[1][r]);
+    mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
+    const float m_new = fmaxf(m_run, mx);  // finite: every tile holds at least one real key
+    const float alpha = __builtin_amdgcn_exp2f((m_run - m_new) * scale_log2e);
+    const float mb = m_new * scale_log2e;
+    m_run = m_new;
+#pragma unroll
+    for (int r = 0; r < 16; ++r) {
+        sacc[0][r] = __builtin_amdgcn_exp2f(fmaf(sacc[0][r], scale_log2e, -mb));
+        sacc[1][r] = __builtin_amdgcn_exp2f(fmaf(sacc[1][r], scale_log2e, -mb));
+    }
+    if (__ballot(alpha != 1.0f)) {  // the running maximum moved for some row of this wave
+#pragma unroll
+        for (int i = 0; i < 2; ++i)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) oacc[i][r] *= alpha;
+    }
+    // P goes to bf16 once; the row sum is taken over the same rounded values (v_dot2 with ones)
+    float psum = 0.f;
+    const bf16x2 ones = __builtin_bit_cast(bf16x2, 0x3f803f80u);
+#pragma unroll
+    for (int t = 0; t < 4; ++t) {
+        const int kb2 = t >> 1, r0 = (t & 1) * 8;
+        union { uint32_t u[4]; bf16x8 v; } pf;
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            pf.u[e] = pack2bf(sacc[kb2][r0 + 2 * e], sacc[kb2][r0 + 2 * e + 1]);
+            psum = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, pf.u[e]), ones, psum, false);
+        }
+#pragma unroll
+        for (int db = 0; db < 2; ++db) {
+            const bf16x8 vf = *reinterpret_cast<const bf16x8*>(svt + att_swz(db * 32 + l32, 2 * t + g));
+            oacc[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, pf.v, oacc[db], 0, 0, 0);
+        }
+    }
+    l_run = l_run * alpha + psum;
+}
+
+// Long sequences: workgroup = 256 query rows (8 waves) of one (image, head).  K tiles stream
+// global -> LDS directly (buffer_load ... lds, rows past N read as zero through the buffer
+// resource); V tiles go through registers because they are transposed on the way in.  Two
+// stages each; the copies of tile t+1 are issued before the MFMAs of tile t, one barrier per tile.
+__global__ __launch_bounds__(512, 2) void attention_bf16_kernel(
     const bf16raw* __restrict__ q, const bf16raw* __restrict__ k, const bf16raw* __restrict__ v,
     bf16raw* __restrict__ o, int N, int64_t sb, int64_t sn, int64_t sh, int64_t osb, int64_t osn,
-    int64_t osh, float scale_log2e) {
-    __shared__ __attribute__((aligned(16))) unsigned char s_k[2][ATT_BN * 128];
-    __shared__ __attribute__((aligned(16))) unsigned char s_vt[2][DH * 128];
+    int64_t osh, float scale_log2e, int H, int BH, int q_tiles) {
+    __shared__ __attribute__((aligned(1024))) unsigned char sk0[ATT_BN * 128];
+    __shared__ __attribute__((aligned(1024))) unsigned char sk1[ATT_BN * 128];
+    __shared__ __attribute__((aligned(16))) unsigned char sv0[DH * 128];
+    __shared__ __attribute__((aligned(16))) unsigned char sv1[DH * 128];
 
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int l32 = lane & 31, g = lane >> 5;
-    const int b = blockIdx.z, h = blockIdx.y;
-    const int q0 = blockIdx.x * ATT_BM + wave * 32;
+    // Workgroup ids go round-robin to the 8 XCDs; all query tiles of one (image, head) are given
+    // to the same XCD so that its K/V tiles are fetched into that XCD's L2 once and hit afterwards.
+    const int xcd = blockIdx.x & 7, local = blockIdx.x >> 3;
+    const int head = xcd + 8 * (local / q_tiles);
+    if (head >= BH) return;  // whole workgroup, before any barrier
+    const int b = head / H, h = head - b * H;
+    const int q0 = (local % q_tiles) * ATT_BM + wave * 32;
     const int64_t base = (int64_t)b * sb + (int64_t)h * sh;
-    const bf16raw* kb = k + base;
     const bf16raw* vb = v + base;
 
     // Q fragments: B operand, column = query row q0 + l32, k-slots = 8 channels 16*kk + 8*g ..
@@ -54,46 +135,51 @@ __global__ __launch_bounds__(256) void attention_bf16_kernel(
         for (int kk = 0; kk < 4; ++kk) qf[kk] = *reinterpret_cast<const bf16x8*>(qp + kk * 16 + g * 8);
     }
 
-    // K tile loader: thread -> chunk (tid & 7) of key rows (tid >> 3) and (tid >> 3) + 32.
-    const int ld_chunk = tid & 7, ld_row = tid >> 3;
-    // V tile loader: thread -> channel chunk (tid & 7), key pair at positions 2a, 2a+1 (a = tid >> 3).
-    // position p = 16T + 8g' + 4u + i  <->  key 16T + 8u + 4g' + i
-    const int va = tid >> 3;
-    const int vpos = 2 * va;
-    const int vkey = (vpos & ~15) | (((vpos >> 2) & 1) << 3) | (((vpos >> 3) & 1) << 2) | (vpos & 3);
+    // K copies: wave w fills LDS rows 8w .. 8w+7 of the tile (lane l: row l/8, slot l%8 holds
+    // chunk (l%8) ^ f(row)); the resource ends with key N-1, so later rows arrive as zeros.
+    const int64_t k_bytes = ((int64_t)(N - 1) * sn + DH) * 2;
+    const __amdgpu_buffer_rsrc_t rs_k = __builtin_amdgcn_make_buffer_rsrc(
+        const_cast<bf16raw*>(k + base), 0, (int)(k_bytes < 0xffffffffll ? k_bytes : 0xffffffffll), 0x00020000);
+    const int k_lr = lane >> 3;
+    const int k_voff = (int)(((int64_t)(wave * 8 + k_lr) * sn + (((lane & 7) ^ k_lr ^ wave) << 3)) * 2);
+    const int k_tile_bytes = (int)(ATT_BN * sn * 2);
 
-    uint4 k_reg[2], v_reg[2];
-    auto load_global = [&](int kt) {
-        const int key0 = kt * ATT_BN;
-#pragma unroll
-        for (int i = 0; i < 2; ++i) {
-            int kr = key0 + ld_row + i * 32;
-            kr = kr < N ? kr : N - 1;  // masked to -inf below
-            k_reg[i] = *reinterpret_cast<const uint4*>(kb + (int64_t)kr * sn + ld_chunk * 8);
-        }
-#pragma unroll
-        for (int i = 0; i < 2; ++i) {
-            const int kr = key0 + vkey + i;
-            uint4 t = make_uint4(0u, 0u, 0u, 0u);  // keys past the end contribute exact zeros
-            if (kr < N) t = *reinterpret_cast<const uint4*>(vb + (int64_t)kr * sn + ld_chunk * 8);
-            v_reg[i] = t;
-        }
-    };
-    auto store_lds = [&](int stage) {
-#pragma unroll
-        for (int i = 0; i < 2; ++i)
-            *reinterpret_cast<uint4*>(&s_k[stage][att_swz(ld_row + i * 32, ld_chunk)]) = k_reg[i];
-        // transpose: channel d = 8*ld_chunk + e gets the pair (key, key+1) at positions vpos, vpos+1
-        const uint32_t w0[4] = {v_reg[0].x, v_reg[0].y, v_reg[0].z, v_reg[0].w};
-        const uint32_t w1[4] = {v_reg[1].x, v_reg[1].y, v_reg[1].z, v_reg[1].w};
-#pragma unroll
-        for (int e = 0; e < 8; ++e) {
-            const uint32_t lo = (e & 1) ? (w0[e >> 1] >> 16) : (w0[e >> 1] & 0xffffu);
-            const uint32_t hi = (e & 1) ? (w1[e >> 1] & 0xffff0000u) : (w1[e >> 1] << 16);
-            const int d = ld_chunk * 8 + e;
-            *reinterpret_cast<uint32_t*>(&s_vt[stage][att_swz(d, vpos >> 3) + (vpos & 7) * 2]) = lo | hi;
-        }
-    };
+    // V staging: thread -> 4 channels (tid & 15) of the key pair at positions 2a, 2a+1 (a = tid >> 4);
+    // position p = 16T + 8g' + 4u + i  <->  key 16T + 8u + 4g' + i
+    const int v_dc = tid & 15, v_pos = 2 * (tid >> 4);
+    const int v_key = (v_pos & ~15) | (((v_pos >> 2) & 1) << 3) | (((v_pos >> 3) & 1) << 2) | (v_pos & 3);
+    uint2 v_reg[2];
+
+#define ATT_LOAD_NEXT(SKn, kt_)                                                                          \
+    {                                                                                                    \
+        __builtin_amdgcn_raw_ptr_buffer_load_lds(rs_k, (att_lds_ptr)((SKn) + wave * 1024), 16, k_voff,    \
+                                                 (kt_) * k_tile_bytes, 0, 0);                            \
+        _Pragma("unroll") for (int i = 0; i < 2; ++i) {                                                  \
+            const int kr = (kt_) * ATT_BN + v_key + i;                                                   \
+            uint2 t = make_uint2(0u, 0u); /* keys past the end contribute exact zeros */                 \
+            if (kr < N) t = *reinterpret_cast<const uint2*>(vb + (int64_t)kr * sn + v_dc * 4);           \
+            v_reg[i] = t;                                                                                \
+        }                                                                                                \
+    }
+#define ATT_STORE_V(SVn)                                                                                 \
+    {                                                                                                    \
+        const uint32_t w0[2] = {v_reg[0].x, v_reg[0].y}, w1[2] = {v_reg[1].x, v_reg[1].y};               \
+        _Pragma("unroll") for (int e = 0; e < 4; ++e) {                                                  \
+            const uint32_t lo = (e & 1) ? (w0[e >> 1] >> 16) : (w0[e >> 1] & 0xffffu);                   \
+            const uint32_t hi = (e & 1) ? (w1[e >> 1] & 0xffff0000u) : (w1[e >> 1] << 16);               \
+            const int d = v_dc * 4 + e;                                                                  \
+            *reinterpret_cast<uint32_t*>((SVn) + att_swz(d, v_pos >> 3) + (v_pos & 7) * 2) = lo | hi;    \
+        }                                                                                                \
+    }
+// tile kt_ is resident in (SKc, SVc); tile kt_+1 is fetched into (SKn, SVn) meanwhile
+#define ATT_STEP(SKc, SVc, SKn, SVn, kt_, MASK_)                                                              \
+    {                                                                                                    \
+        ATT_LOAD_NEXT(SKn, (kt_) + 1)                                                                    \
+        att_tile<MASK_>(SKc, SVc, qf, oacc, m_run, l_run, (kt_) * ATT_BN, N, scale_log2e, l32, g);       \
+        ATT_STORE_V(SVn)                                                                                 \
+        __builtin_amdgcn_s_waitcnt(0x0F70); /* this wave's K copy has landed */                          \
+        __syncthreads();                                                                                 \
+    }
 
     f32x16 oacc[2];
 #pragma unroll
@@ -104,82 +190,23 @@ __global__ __launch_bounds__(256) void attention_bf16_kernel(
     float l_run = 0.f;        // this lane's share of the running row sum
 
     const int KT = (N + ATT_BN - 1) / ATT_BN;
-    load_global(0);
-    store_lds(0);
+    ATT_LOAD_NEXT(sk0, 0)
+    ATT_STORE_V(sv0)
+    __builtin_amdgcn_s_waitcnt(0x0F70);
     __syncthreads();
-
-    for (int kt = 0; kt < KT; ++kt) {
-        if (kt + 1 < KT) load_global(kt + 1);
-        const unsigned char* sk = s_k[kt & 1];
-        const unsigned char* sv = s_vt[kt & 1];
-
-        // ---- S^T = K Q^T for the 64 keys of this tile
-        f32x16 sacc[2];
-#pragma unroll
-        for (int kb2 = 0; kb2 < 2; ++kb2) {
-#pragma unroll
-            for (int r = 0; r < 16; ++r) sacc[kb2][r] = 0.f;
-#pragma unroll
-            for (int kk = 0; kk < 4; ++kk) {
-                bf16x8 kf = *reinterpret_cast<const bf16x8*>(sk + att_swz(kb2 * 32 + l32, kk * 2 + g));
-                sacc[kb2] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[kk], sacc[kb2], 0, 0, 0);
-            }
-        }
-        // ---- mask keys past the end (last tile only)
-        if ((kt + 1) * ATT_BN > N) {
-#pragma unroll
-            for (int kb2 = 0; kb2 < 2; ++kb2)
-#pragma unroll
-                for (int r = 0; r < 16; ++r) {
-                    const int key = kt * ATT_BN + kb2 * 32 + (r >> 2) * 8 + g * 4 + (r & 3);
-                    if (key >= N) sacc[kb2][r] = -INFINITY;
-                }
-        }
-        // ---- online softmax: row max over this lane's 32 keys, then across the half-waves
-        float mx = sacc[0][0];
-#pragma unroll
-        for (int kb2 = 0; kb2 < 2; ++kb2)
-#pragma unroll
-            for (int r = 0; r < 16; ++r) mx = fmaxf(mx, sacc[kb2][r]);
-        mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
-        const float m_new = fmaxf(m_run, mx);  // finite: every tile holds at least one real key
-        const float alpha = exp2f((m_run - m_new) * scale_log2e);
-        const float mb = m_new * scale_log2e;
-        m_run = m_new;
-        float psum = 0.f;
-#pragma unroll
-        for (int kb2 = 0; kb2 < 2; ++kb2)
-#pragma unroll
-            for (int r = 0; r < 16; ++r) {
-                const float p = exp2f(fmaf(sacc[kb2][r], scale_log2e, -mb));
-                sacc[kb2][r] = p;
-                psum += p;
-            }
-        l_run = l_run * alpha + psum;
-        if (__ballot(alpha != 1.0f)) {  // the running maximum moved for some row of this wave
-#pragma unroll
-            for (int i = 0; i < 2; ++i)
-#pragma unroll
-                for (int r = 0; r < 16; ++r) oacc[i][r] *= alpha;
-        }
-
-        // ---- O^T += V^T P^T, 16 keys per MFMA
-#pragma unroll
-        for (int t = 0; t < 4; ++t) {
-            const int kb2 = t >> 1, r0 = (t & 1) * 8;
-            union { uint32_t u[4]; bf16x8 v; } pf;
-#pragma unroll
-            for (int e = 0; e < 4; ++e) pf.u[e] = pack2bf(sacc[kb2][r0 + 2 * e], sacc[kb2][r0 + 2 * e + 1]);
-#pragma unroll
-            for (int db = 0; db < 2; ++db) {
-                bf16x8 vf = *reinterpret_cast<const bf16x8*>(sv + att_swz(db * 32 + l32, 2 * t + g));
-                oacc[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, pf.v, oacc[db], 0, 0, 0);
-            }
-        }
-
-        if (kt + 1 < KT) store_lds((kt + 1) & 1);
-        __syncthreads();
+    const int KF = N / ATT_BN;  // tiles without padding keys
+    int kt = 0;
+    for (; kt + 2 <= KF; kt += 2) {
+        ATT_STEP(sk0, sv0, sk1, sv1, kt, false)
+        ATT_STEP(sk1, sv1, sk0, sv0, kt + 1, false)
     }
+    if (kt < KT) {  // one or two tiles left, the last one possibly padded
+        ATT_STEP(sk0, sv0, sk1, sv1, kt, true)
+        if (kt + 1 < KT) ATT_STEP(sk1, sv1, sk0, sv0, kt + 1, true)
+    }
+#undef ATT_LOAD_NEXT
+#undef ATT_STORE_V
+#undef ATT_STEP
 
     // ---- normalise and store: lane holds O[q][db*32 + 8j + 4g + i] in oacc[db][4j + i]
     const float l_tot = l_run + __shfl_xor(l_run, 32, 64);
@@ -454,10 +481,11 @@ hipError_t launch_attention(rs_dtype dt, const void* q, const void* k, const voi
                            (const bf16raw*)k, (const bf16raw*)v, (bf16raw*)o, N, sb, sn, sh, osb, osn, osh,
                            scale_log2e);
     } else if (dt == RS_BF16) {
-        dim3 grid((N + ATT_BM - 1) / ATT_BM, H, B);
-        hipLaunchKernelGGL(attention_bf16_kernel, grid, dim3(256), 0, s, (const bf16raw*)q,
+        const int q_tiles = (N + ATT_BM - 1) / ATT_BM, BH = B * H;
+        dim3 grid(8 * ((BH + 7) / 8) * q_tiles);
+        hipLaunchKernelGGL(attention_bf16_kernel, grid, dim3(512), 0, s, (const bf16raw*)q,
                            (const bf16raw*)k, (const bf16raw*)v, (bf16raw*)o, N, sb, sn, sh, osb, osn,
-                           osh, scale_log2e);
+                           osh, scale_log2e, H, BH, q_tiles);
     } else {
         dim3 grid((N + 63) / 64, H, B);
         hipLaunchKernelGGL(attention_f32_kernel, grid, dim3(64), 0, s, (const float*)q,
