@@ -28,21 +28,6 @@ namespace rs {
 // the plain c ^ (r & 7)).
 // ---------------------------------------------------------------------------
 
-// Exact-erf GELU x * Phi(x) with erf from the 5-term rational/exponential form of
-// Abramowitz & Stegun 7.1.26 (|error| < 1.5e-7 on erf): 2 transcendental + ~12 plain ops,
-// a fraction of libm's erff, which matters because the fc1 epilogue runs it M * Dm times.
-__device__ __forceinline__ float gelu_fast(float x) {
-    const float z = fabsf(x) * 0.70710678118654752440f;
-    const float t = __builtin_amdgcn_rcpf(fmaf(0.3275911f, z, 1.0f));
-    float p = fmaf(1.061405429f, t, -1.453152027f);
-    p = fmaf(p, t, 1.421413741f);
-    p = fmaf(p, t, -0.284496736f);
-    p = fmaf(p, t, 0.254829592f);
-    const float y = p * t * __builtin_amdgcn_exp2f(-(z * z) * 1.44269504088896340736f);  // 1 - erf(z)
-    const float phi = x >= 0.f ? fmaf(-0.5f, y, 1.0f) : 0.5f * y;
-    return x * phi;
-}
-
 template <int TN, int TM>
 struct Frags {
     bf16x8 w[TN], a[TM];
@@ -273,6 +258,24 @@ __global__ __launch_bounds__(256, WPE) void gemm_bf16_kernel(
 #pragma unroll
         for (int e = 0; e < 8; ++e) bv[e] = 0.f;
         if (bias && n_ok) Elem<bf16raw>::load8(bias + n, bv);
+        // exact-erf GELU by table: 1024 intervals of 12/1024 on [-6, 6), (value, slope) pairs built
+        // here with erff and interpolated linearly (|error| < 1.4e-5, far below bf16 rounding);
+        // beyond +6 GELU(x) = x to 1e-8, below -6 it is 0.  One LDS gather + ~9 plain ops per
+        // element instead of ~22 for a direct erf evaluation: the fc1 epilogue runs M * Dm of them
+        // and plain ALU work does not overlap with the matrix cores on this chip.
+        constexpr int TAB_OFF = (32 * PITCH + 255) / 256 * 256;
+        static_assert(EPI != EPI_BIAS_GELU || TAB_OFF + 8192 <= (NSTAGE >= 4 ? STAGE : STAGE / 2),
+                      "GELU table does not fit beside the epilogue staging");
+        const float2* gelu_tab = reinterpret_cast<const float2*>(stage0 + TAB_OFF);
+        if (EPI == EPI_BIAS_GELU) {
+            float2* tab = reinterpret_cast<float2*>(stage0 + TAB_OFF);
+            for (int i = tid; i < 1024; i += 256) {
+                const float x0 = -6.0f + (float)i * 0.01171875f;
+                const float v0 = gelu_erf(x0), v1 = gelu_erf(x0 + 0.01171875f);
+                tab[i] = make_float2(v0, v1 - v0);
+            }
+            __syncthreads();
+        }
 #pragma unroll
         for (int j = 0; j < TM; ++j) {
 #pragma unroll
@@ -296,7 +299,14 @@ __global__ __launch_bounds__(256, WPE) void gemm_bf16_kernel(
                 }
                 if (EPI == EPI_BIAS_GELU) {
 #pragma unroll
-                    for (int e = 0; e < 8; ++e) v[e] = gelu_fast(v[e]);
+                    for (int e = 0; e < 8; ++e) {
+                        const float x = v[e];
+                        const float t = __builtin_amdgcn_fmed3f(fmaf(x, 85.33333333333333f, 512.0f), 0.0f, 1023.9999f);
+                        const int i = (int)t;
+                        const float2 en = gelu_tab[i];
+                        const float y = fmaf(t - (float)i, en.y, en.x);
+                        v[e] = x > 6.0f ? x : y;
+                    }
                 }
                 float p0 = 0.f, p1 = 0.f, p2 = 0.f;
                 if (EPI == EPI_BIAS_RES || EPI == EPI_BIAS_RES_SHIFT) {
