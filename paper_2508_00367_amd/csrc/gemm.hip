@@ -10,8 +10,6 @@
 // (residual, shift partial sums) stays inside a lane, and stores are 8-byte vectors.
 //
 // fp32 path: plain FMA tiles (parity configuration, true fp32 products).
-#include <stdlib.h>
-
 #include "common.hpp"
 
 namespace rs {
@@ -27,6 +25,22 @@ namespace rs {
 // r and r + 8 differ (measured: zero SQ_LDS_BANK_CONFLICT, against every second cycle with
 // the plain c ^ (r & 7)).
 // ---------------------------------------------------------------------------
+
+// Exact-erf GELU x * Phi(x) for the bf16 epilogue: Phi(x) = sigmoid(x (a + b x^2 + c x^4)) with
+// (a, b, c) fitted (minimax over [-9, 9]) to the erf form; max |error| of x * Phi(x) is 2.5e-5,
+// below half a bf16 ulp of every output larger than 6e-3.  7 plain + 2 transcendental ops per
+// element (libm erff: ~40) -- it matters: the fc1 epilogue runs M * Dm of them and plain ALU
+// work does not overlap with the matrix cores on this chip.  The polynomial argument is
+// clamped to [-10, 10] (it changes sign near |x| = 11); beyond that the sigmoid is 0 or 1 in
+// fp32 anyway.  Constants carry the factor -log2(e) for v_exp_f32.
+__device__ __forceinline__ float gelu_sp(float x) {
+    const float xc = __builtin_amdgcn_fmed3f(x, -10.0f, 10.0f);
+    const float x2 = xc * xc;
+    float p = fmaf(1.0142687e-3f, x2, -0.10677576f);
+    p = fmaf(p, x2, -2.3011212f);
+    const float e = __builtin_amdgcn_exp2f(p * xc);  // exp(-x (a + b x^2 + c x^4))
+    return x * __builtin_amdgcn_rcpf(1.0f + e);
+}
 
 template <int TN, int TM>
 struct Frags {
@@ -61,21 +75,24 @@ constexpr int vmcnt_imm(int n) { return (n & 15) | ((n >> 4) << 14) | 0x0F70; }
 // buffered in registers and each LDS read is interleaved with its share of the previous K step's
 // MFMAs (sched_group_barrier).  WPE = waves per SIMD the register budget must allow (2 = two
 // workgroups per CU, so one's epilogue and barrier waits hide behind the other's MFMAs).
-template <int BM, int BN, int BK, int NSTAGE, int WPE, int EPI, int DIST>
-__global__ __launch_bounds__(256, WPE) void gemm_bf16_kernel(
+template <int BM, int BN, int BK, int NSTAGE, int WGM, int WGN, int EPI, int DIST>
+__global__ __launch_bounds__(WGM* WGN * 64, WGM* WGN / 4) void gemm_bf16_kernel(
     const bf16raw* __restrict__ a, const bf16raw* __restrict__ wt, const bf16raw* __restrict__ bias,
     const bf16raw* __restrict__ res, bf16raw* __restrict__ out, float* __restrict__ partials,
     int M, int N, int K, int tiles_m, int tiles_n, int slots, int gm) {
-    constexpr int WM = BM / 2, WN = BN / 2;     // wave tile
+    constexpr int NW = WGM * WGN;               // waves: WGM along tokens x WGN along features
+    constexpr int WM = BM / WGM, WN = BN / WGN; // wave tile
     constexpr int TM = WM / 32, TN = WN / 32;   // MFMA tiles per wave
     constexpr int RB = BK * 2;                  // bytes per LDS row
     constexpr int SPR = BK / 8;                 // 16-byte slots per row (4 or 8)
     constexpr int RPI = 64 / SPR;               // rows one wave copy (1 KiB) covers
-    constexpr int A_LOADS = BM / RPI / 4, W_LOADS = BN / RPI / 4;  // wave copies per slice and wave
+    constexpr int A_LOADS = BM / RPI / NW, W_LOADS = BN / RPI / NW;  // wave copies per slice and wave
     constexpr int LPW = A_LOADS + W_LOADS;
     constexpr int KK = BK / 16;                 // MFMA K steps per slice
     constexpr int STAGE = (BM + BN) * RB;
-    static_assert(BM % 128 == 0 && BN % 128 == 0, "wave tiles must be multiples of 64 rows");
+    static_assert(WM % 64 == 0 && WN % 64 == 0, "wave tiles must be multiples of 64 rows");
+    static_assert(NW == 4 || NW == 8, "4 or 8 waves");
+    static_assert(BM % (RPI * NW) == 0 && BN % (RPI * NW) == 0, "tile rows must split evenly over the wave copies");
     static_assert(BK == 32 || BK == 64, "K slice of 32 or 64");
     static_assert(NSTAGE >= 2 && NSTAGE <= 4, "2 to 4 stages");
     static_assert((NSTAGE - 2) * LPW <= 63, "vmcnt range");
@@ -110,7 +127,7 @@ __global__ __launch_bounds__(256, WPE) void gemm_bf16_kernel(
 
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);  // wave-uniform: LDS copy targets go to M0
-    const int wm = wave & 1, wn = wave >> 1;
+    const int wm = wave % WGM, wn = wave / WGM;
     const int l32 = lane & 31, g = lane >> 5;
 
     // LDS layout.  Chunk c (16 bytes = 8 k values) of row r sits in slot c ^ f(r).  gfx950's LDS has
@@ -121,19 +138,19 @@ __global__ __launch_bounds__(256, WPE) void gemm_bf16_kernel(
     //                          makes rows r and r + 8 differ; measured 0 SQ_LDS_BANK_CONFLICT,
     //                          against every second cycle with the plain r & 7)
     //    64-byte rows (BK 32): f(r) = (r >> 2) & 3         (r & 3 picks the quarter line)
-    // global -> LDS: wave copy i of wave w fills rows (4*i + w)*RPI .. +RPI-1 (lane l: row l / SPR,
+    // global -> LDS: wave copy i of wave w fills rows (NW*i + w)*RPI .. +RPI-1 (lane l: row l / SPR,
     // slot l % SPR), so the lane fetches chunk (l % SPR) ^ f(row).
     const __amdgpu_buffer_rsrc_t rs_a = make_rsrc(a + (int64_t)m0 * K, (int64_t)(M - m0) * K * 2);
     const __amdgpu_buffer_rsrc_t rs_w = make_rsrc(wt + (int64_t)n0 * K, (int64_t)(N - n0) * K * 2);
     const int ld_r = lane / SPR, ld_p = lane % SPR;
     int voff_e, voff_o;  // lane byte offset for even / odd copy index i
-    if (SPR == 8) {
-        voff_e = ((wave * RPI + ld_r) * K + ((ld_p ^ ld_r ^ wave) << 3)) * 2;
-        voff_o = ((wave * RPI + ld_r) * K + ((ld_p ^ ld_r ^ wave ^ 4) << 3)) * 2;
+    if (SPR == 8) {  // row >> 3 = NW*i + w
+        voff_e = ((wave * RPI + ld_r) * K + ((ld_p ^ ld_r ^ (wave & 7)) << 3)) * 2;
+        voff_o = ((wave * RPI + ld_r) * K + ((ld_p ^ ld_r ^ ((wave + NW) & 7)) << 3)) * 2;
     } else {
         voff_e = voff_o = ((wave * RPI + ld_r) * K + ((ld_p ^ ((ld_r >> 2) & 3)) << 3)) * 2;
     }
-    const int pass_bytes = 4 * RPI * K * 2;
+    const int pass_bytes = NW * RPI * K * 2;
 
     f32x16 acc[TN][TM];
 #pragma unroll
@@ -155,9 +172,9 @@ __global__ __launch_bounds__(256, WPE) void gemm_bf16_kernel(
     {                                                                                                     \
         const int kb_ = (t_) < S ? (t_) * RB : 0x7ff00000;                                                \
         _Pragma("unroll") for (int i = 0; i < A_LOADS; ++i)                                               \
-            dma16(rs_a, (stage_) + (i * 4 + wave) * 1024, (i & 1) ? voff_o : voff_e, i * pass_bytes + kb_); \
+            dma16(rs_a, (stage_) + (i * NW + wave) * 1024, (i & 1) ? voff_o : voff_e, i * pass_bytes + kb_); \
         _Pragma("unroll") for (int i = 0; i < W_LOADS; ++i)                                               \
-            dma16(rs_w, (stage_) + BM * RB + (i * 4 + wave) * 1024, (i & 1) ? voff_o : voff_e, i * pass_bytes + kb_); \
+            dma16(rs_w, (stage_) + BM * RB + (i * NW + wave) * 1024, (i & 1) ? voff_o : voff_e, i * pass_bytes + kb_); \
     }
 #define RS_GEMM_LOAD_FRAGS(f_, stage_, kk_)                                                               \
     {                                                                                                     \
@@ -247,9 +264,8 @@ __global__ __launch_bounds__(256, WPE) void gemm_bf16_kernel(
         constexpr int PITCH = WN * 4 + 16;         // bytes per staged row
         constexpr int LPR = WN / 8;                // lanes per row on the way out (16 for WN = 128)
         constexpr int RPS = 64 / LPR;              // rows per step
-        static_assert(32 * PITCH <= (NSTAGE >= 4 ? STAGE : STAGE / 2), "epilogue staging does not fit");
-        unsigned char* ep = NSTAGE >= 4 ? (wave == 0 ? stage0 : wave == 1 ? stage1 : wave == 2 ? stage2 : stage3)
-                                        : (wave < 2 ? stage0 : stage1) + (wave & 1) * (STAGE / 2);
+        static_assert(32 * PITCH <= 2 * STAGE / NW, "epilogue staging does not fit");
+        unsigned char* ep = ((wave & 1) ? stage1 : stage0) + (wave >> 1) * (2 * STAGE / NW);
         const int oc = (lane % LPR) * 8;           // this lane's first feature inside the wave tile
         const int orow = lane / LPR;
         const int n = n0 + wn * WN + oc;
@@ -258,24 +274,6 @@ __global__ __launch_bounds__(256, WPE) void gemm_bf16_kernel(
 #pragma unroll
         for (int e = 0; e < 8; ++e) bv[e] = 0.f;
         if (bias && n_ok) Elem<bf16raw>::load8(bias + n, bv);
-        // exact-erf GELU by table: 1024 intervals of 12/1024 on [-6, 6), (value, slope) pairs built
-        // here with erff and interpolated linearly (|error| < 1.4e-5, far below bf16 rounding);
-        // beyond +6 GELU(x) = x to 1e-8, below -6 it is 0.  One LDS gather + ~9 plain ops per
-        // element instead of ~22 for a direct erf evaluation: the fc1 epilogue runs M * Dm of them
-        // and plain ALU work does not overlap with the matrix cores on this chip.
-        constexpr int TAB_OFF = (32 * PITCH + 255) / 256 * 256;
-        static_assert(EPI != EPI_BIAS_GELU || TAB_OFF + 8192 <= (NSTAGE >= 4 ? STAGE : STAGE / 2),
-                      "GELU table does not fit beside the epilogue staging");
-        const float2* gelu_tab = reinterpret_cast<const float2*>(stage0 + TAB_OFF);
-        if (EPI == EPI_BIAS_GELU) {
-            float2* tab = reinterpret_cast<float2*>(stage0 + TAB_OFF);
-            for (int i = tid; i < 1024; i += 256) {
-                const float x0 = -6.0f + (float)i * 0.01171875f;
-                const float v0 = gelu_erf(x0), v1 = gelu_erf(x0 + 0.01171875f);
-                tab[i] = make_float2(v0, v1 - v0);
-            }
-            __syncthreads();
-        }
 #pragma unroll
         for (int j = 0; j < TM; ++j) {
 #pragma unroll
@@ -299,14 +297,7 @@ __global__ __launch_bounds__(256, WPE) void gemm_bf16_kernel(
                 }
                 if (EPI == EPI_BIAS_GELU) {
 #pragma unroll
-                    for (int e = 0; e < 8; ++e) {
-                        const float x = v[e];
-                        const float t = __builtin_amdgcn_fmed3f(fmaf(x, 85.33333333333333f, 512.0f), 0.0f, 1023.9999f);
-                        const int i = (int)t;
-                        const float2 en = gelu_tab[i];
-                        const float y = fmaf(t - (float)i, en.y, en.x);
-                        v[e] = x > 6.0f ? x : y;
-                    }
+                    for (int e = 0; e < 8; ++e) v[e] = gelu_sp(v[e]);
                 }
                 float p0 = 0.f, p1 = 0.f, p2 = 0.f;
                 if (EPI == EPI_BIAS_RES || EPI == EPI_BIAS_RES_SHIFT) {
@@ -345,14 +336,14 @@ __global__ __launch_bounds__(256, WPE) void gemm_bf16_kernel(
     }
 }
 
-// Tile configuration of the bf16 GEMM.
+// Tile configuration of the bf16 GEMM: BM, BN, BK, NSTAGE, waves along tokens, waves along features.
 struct GemmCfg {
 #ifndef RS_GEMM_CFG
-#define RS_GEMM_CFG 256, 256, 64, 2, 1
+#define RS_GEMM_CFG 256, 256, 64, 2, 2, 4
 #endif
-    static constexpr int P[5] = {RS_GEMM_CFG};
-    static constexpr int BM = P[0], BN = P[1], BK = P[2], NSTAGE = P[3], WPE = P[4];
-    static constexpr int WN = BN / 2;
+    static constexpr int P[6] = {RS_GEMM_CFG};
+    static constexpr int BM = P[0], BN = P[1], BK = P[2], NSTAGE = P[3], WGM = P[4], WGN = P[5];
+    static constexpr int WN = BN / WGN;
 };
 
 template <int EPI, int DIST>
@@ -361,12 +352,11 @@ static hipError_t launch_bf16(const void* a, const void* wt, const void* bias, c
     using C = GemmCfg;
     const int tiles_m = (int)((M + C::BM - 1) / C::BM), tiles_n = (N + C::BN - 1) / C::BN;
     const int slots = (tiles_n * C::BN) / C::WN;
-    static const int gm_env = getenv("RS_GEMM_GM") ? atoi(getenv("RS_GEMM_GM")) : 8;
-    const int gm = gm_env;
-    hipLaunchKernelGGL((gemm_bf16_kernel<C::BM, C::BN, C::BK, C::NSTAGE, C::WPE, EPI, DIST>),
-                       dim3(tiles_m * tiles_n), dim3(256), 0, s, (const bf16raw*)a, (const bf16raw*)wt,
-                       (const bf16raw*)bias, (const bf16raw*)res, (bf16raw*)out, partials, (int)M, N, K,
-                       tiles_m, tiles_n, slots, gm);
+    const int gm = 8;  // row panels per tile group: their activations stay in an XCD's L2 during a sweep over n
+    hipLaunchKernelGGL((gemm_bf16_kernel<C::BM, C::BN, C::BK, C::NSTAGE, C::WGM, C::WGN, EPI, DIST>),
+                       dim3(tiles_m * tiles_n), dim3(C::WGM * C::WGN * 64), 0, s, (const bf16raw*)a,
+                       (const bf16raw*)wt, (const bf16raw*)bias, (const bf16raw*)res, (bf16raw*)out, partials,
+                       (int)M, N, K, tiles_m, tiles_n, slots, gm);
     return hipGetLastError();
 }
 
