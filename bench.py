@@ -39,7 +39,21 @@ def parse():
     ap.add_argument("--cpu-sample", type=int, default=0, help="images for the CPU baseline (0 = auto)")
     ap.add_argument("--stress", action="store_true",
                     help="also time rs_shift_topk alone on an HBM-resident shape (B=4096, N=197, D=768)")
+    ap.add_argument("--calib-copy-mb", type=int, default=0,
+                    help="after the run, copy this many MiB device-to-device three times: a kernel of known "
+                         "traffic to scale rocprofv3 FETCH_SIZE / WRITE_SIZE readings with")
     return ap.parse_args()
+
+
+# HBM bytes per launch (fetch + write) from the rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of this
+# script, scaled by what the same counters read for a 1 GiB device copy (fetch x2.000, write x1.000);
+# the runs and their per-kernel table are profiles/vit_b16_forward_hbm_traffic.md.  Counters cannot
+# be read from inside the process, so the figure is carried here; None where no run was made.
+MEASURED_HBM_BYTES_PER_LAUNCH = {
+    ("vit_b16", False, "gemm_fc2"): 556.3e6,   # the 8 of 12 launches that carry the shift epilogue
+    ("vit_b16", False, "gemm_fc1"): 576.5e6,
+    ("vit_b16", False, "gemm_qkv"): 449.3e6,
+}
 
 
 def main():
@@ -162,7 +176,8 @@ def main():
     avg_s, per_step = kern(dom)
     achieved = fl[dom] / per_step / avg_s / 1e12
     roofline = {"kernel": dom, "bound": "mfma", "achieved": round(achieved, 2), "peak": PEAK_BF16_TFLOPS,
-                "unit": "TFLOP/s", "frac": round(achieved / PEAK_BF16_TFLOPS, 4), "traffic": None,
+                "unit": "TFLOP/s", "frac": round(achieved / PEAK_BF16_TFLOPS, 4),
+                "traffic": MEASURED_HBM_BYTES_PER_LAUNCH.get((a.workload, a.unpruned, dom)),
                 "avg_launch_us": round(avg_s * 1e6, 2), "launches_per_step": per_step,
                 "whole_step_frac_of_mfma_peak": round(total_flops / (ms_per_step * 1e-3) / 1e12 / PEAK_BF16_TFLOPS, 4)}
 
@@ -203,6 +218,15 @@ def main():
         out["prune_stress"] = {"shape": [Bs, Ns, Ds, Ks], "ms": round(ts * 1e3, 4),
                                "GB/s": round(alg / ts / 1e9, 1), "frac_hbm": round(alg / ts / 1e9 / PEAK_HBM_GBS, 4)}
         del f_in, f_out, g
+
+    if a.calib_copy_mb:
+        src_c = torch.empty(a.calib_copy_mb << 20, dtype=torch.uint8, device=dev).fill_(1)
+        dst_c = torch.empty_like(src_c)
+        for _ in range(3):
+            dst_c.copy_(src_c)
+        torch.cuda.synchronize()
+        out["calib_copy_bytes"] = int(src_c.numel())
+        del src_c, dst_c
 
     # ---- CPU baseline: the fp64 checker on a bounded sample of the same workload ----
     if not a.no_cpu_baseline:
