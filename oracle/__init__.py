@@ -19,6 +19,9 @@ _SRC = os.path.join(_HERE, "rs_oracle.c")
 _LIB = os.path.join(_HERE, "librs_oracle.so")
 
 DIST_L2, DIST_L1, DIST_COS = 0, 1, 2
+# which pair (f_out, f_in) the shift is taken over ("Operation choice", Sec. 3.3, and the two other
+# readings of the MLP case): (MLP(LN(x1)), x1), (SA(LN(x)), x), (xhat, x), (xhat, x1), (MLP(v), v = LN(x1))
+OP_MLP, OP_ATTN, OP_BLOCK, OP_MLP_STREAM, OP_MLP_NORMED = 0, 1, 2, 3, 4
 
 
 def build(force: bool = False) -> str:
@@ -51,8 +54,8 @@ def lib():
         L.rs_oracle_shift_scores.argtypes = [_pd, _pd, _i64, _i64, ctypes.c_int, _pd]
         L.rs_oracle_topk.argtypes = [_pd, _i64, _i64, _i64, _i64, _pi]
         L.rs_oracle_gather.argtypes = [_pd, _pi, _i64, _i64, _i64, _i64, _pd]
-        L.rs_oracle_block.argtypes = ([_i64] * 5 + [ctypes.c_double, ctypes.c_double, ctypes.c_int]
-                                      + [_pd] * 13 + [_pd] * 4)
+        L.rs_oracle_block.argtypes = ([_i64] * 5 + [ctypes.c_double, ctypes.c_double, ctypes.c_int, ctypes.c_int]
+                                      + [_pd] * 13 + [_pd] * 5)
         L.rs_oracle_block.restype = ctypes.c_int
         _lib = L
     return _lib
@@ -145,10 +148,10 @@ def shift_topk(f_out, f_in, src, n_prefix, n_keep, dist=DIST_L2):
     return s, kept, gather(f_in if src is None else src, kept)
 
 
-def block(x, w, H, ln_eps=1e-6, attn_scale=None, dist=DIST_L2):
+def block(x, w, H, ln_eps=1e-6, attn_scale=None, dist=DIST_L2, op=OP_MLP):
     """One encoder block on x [B, N, D] with weight dict `w` (missing/None bias = 0).
 
-    Returns dict(x1, mlp, xhat [B,N,D], scores [B,N])."""
+    Returns dict(sa, x1, mlp, xhat [B,N,D], scores [B,N]); `op` picks the pair the shift is taken over."""
     x = _d(x)
     B, N, D = x.shape
     Dm = w["w_fc1"].shape[1]
@@ -158,18 +161,21 @@ def block(x, w, H, ln_eps=1e-6, attn_scale=None, dist=DIST_L2):
                                      "ln2_g", "ln2_b", "w_fc1", "b_fc1", "w_fc2", "b_fc2")}
     assert ws["w_qkv"].shape == (D, 3 * D) and ws["w_proj"].shape == (D, D)
     assert ws["w_fc1"].shape == (D, Dm) and ws["w_fc2"].shape == (Dm, D)
+    sa = np.empty_like(x)
     x1 = np.empty_like(x)
     mlp = np.empty_like(x)
     xhat = np.empty_like(x)
     s = np.empty((B, N), np.float64)
-    rc = lib().rs_oracle_block(B, N, D, H, Dm, float(ln_eps), float(attn_scale), int(dist),
+    rc = lib().rs_oracle_block(B, N, D, H, Dm, float(ln_eps), float(attn_scale), int(dist), int(op),
                                _p(x), *[_p(ws[k]) for k in
                                         ("ln1_g", "ln1_b", "w_qkv", "b_qkv", "w_proj", "b_proj",
                                          "ln2_g", "ln2_b", "w_fc1", "b_fc1", "w_fc2", "b_fc2")],
-                               _p(x1), _p(mlp), _p(xhat), _p(s))
+                               _p(sa), _p(x1), _p(mlp), _p(xhat), _p(s))
+    if rc == -2:
+        raise ValueError("unknown shift operation %r" % (op,))
     if rc != 0:
         raise MemoryError("rs_oracle_block")
-    return dict(x1=x1, mlp=mlp, xhat=xhat, scores=s)
+    return dict(sa=sa, x1=x1, mlp=mlp, xhat=xhat, scores=s)
 
 
 def block_pruned(x, w, H, n_prefix, n_keep, **kw):

@@ -206,16 +206,24 @@ void rs_oracle_gather(const double *src, const int32_t *kept_idx, int64_t B, int
 }
 
 /* One pre-LN encoder block, Eqs. (5),(6):
- *   x1   = SA(LN(x)) + x          SA = multi-head attention followed by the output projection
+ *   sa   = SA(LN(x))              SA = multi-head attention followed by the output projection
+ *   x1   = sa + x
  *   mlp  = W2 GELU(W1 LN(x1) + b1) + b2
  *   xhat = mlp + x1
- * and the shift around the MLP, case (ii) of "Operation choice" (Sec. 3.3):
- *   s_i = D(MLP(LN(x1))_i, x1_i)   -- branch output versus the residual-stream input.
+ * and the representation shift s_i = D(f_out_i, f_in_i) for the operation `op`
+ * ("Operation choice", Sec. 3.3):
+ *   op 0  case (ii), the MLP:       D(MLP(LN(x1)), x1)   -- branch output versus the
+ *                                                           residual-stream input (the default)
+ *   op 1  case (i), attention:      D(SA(LN(x)), x)
+ *   op 2  case (iii), whole block:  D(xhat, x)
+ * plus the two other readings of "the shift around the MLP" that the text leaves open:
+ *   op 3  residual stream before and after the MLP:  D(xhat, x1)
+ *   op 4  the MLP's own input and output:            D(MLP(v), v),  v = LN(x1)
  * W_qkv columns are ordered [Q | K | V], each H heads of dh = D/H.
- * Any bias may be NULL (= zero).  Outputs (each may be NULL): x1, mlp, xhat [B*N, D];
- * scores [B*N].  Returns 0, or -1 if an allocation fails. */
+ * Any bias may be NULL (= zero).  Outputs (each may be NULL): sa, x1, mlp, xhat [B*N, D];
+ * scores [B*N].  Returns 0, -1 if an allocation fails, -2 for an unknown op. */
 int rs_oracle_block(int64_t B, int64_t N, int64_t D, int64_t H, int64_t Dm,
-                    double ln_eps, double attn_scale, int dist,
+                    double ln_eps, double attn_scale, int dist, int op,
                     const double *x,
                     const double *ln1_g, const double *ln1_b,
                     const double *w_qkv, const double *b_qkv,
@@ -223,7 +231,8 @@ int rs_oracle_block(int64_t B, int64_t N, int64_t D, int64_t H, int64_t Dm,
                     const double *ln2_g, const double *ln2_b,
                     const double *w_fc1, const double *b_fc1,
                     const double *w_fc2, const double *b_fc2,
-                    double *x1_out, double *mlp_out, double *xhat_out, double *scores) {
+                    double *sa_out, double *x1_out, double *mlp_out, double *xhat_out,
+                    double *scores) {
     int64_t M = B * N, dh = D / H;
     size_t md = (size_t)M * (size_t)D;
     double *u = (double *)malloc(sizeof(double) * md);
@@ -232,25 +241,33 @@ int rs_oracle_block(int64_t B, int64_t N, int64_t D, int64_t H, int64_t Dm,
     double *x1 = (double *)malloc(sizeof(double) * md);
     double *hid = (double *)malloc(sizeof(double) * (size_t)M * (size_t)Dm);
     double *mlp = (double *)malloc(sizeof(double) * md);
+    double *sa = (double *)malloc(sizeof(double) * md);
+    double *xhat = (double *)malloc(sizeof(double) * md);
     int rc = -1;
-    if (u && qkv && att && x1 && hid && mlp) {
+    if (op < 0 || op > 4) rc = -2;
+    else if (u && qkv && att && x1 && hid && mlp && sa && xhat) {
         rs_oracle_layernorm(x, ln1_g, ln1_b, ln_eps, M, D, u);
         rs_oracle_linear(u, w_qkv, b_qkv, M, D, 3 * D, qkv);
         rs_oracle_attention(qkv, qkv + D, qkv + 2 * D, att, B, H, N, dh,
                             N * 3 * D, 3 * D, dh, N * D, D, dh, attn_scale);
-        rs_oracle_linear(att, w_proj, b_proj, M, D, D, x1);
-        for (size_t t = 0; t < md; ++t) x1[t] += x[t];
+        rs_oracle_linear(att, w_proj, b_proj, M, D, D, sa);
+        for (size_t t = 0; t < md; ++t) x1[t] = sa[t] + x[t];
         rs_oracle_layernorm(x1, ln2_g, ln2_b, ln_eps, M, D, u);
         rs_oracle_linear(u, w_fc1, b_fc1, M, D, Dm, hid);
         for (size_t t = 0; t < (size_t)M * (size_t)Dm; ++t) hid[t] = rs_oracle_gelu(hid[t]);
         rs_oracle_linear(hid, w_fc2, b_fc2, M, Dm, D, mlp);
-        if (scores) rs_oracle_shift_scores(mlp, x1, M, D, dist, scores);
+        for (size_t t = 0; t < md; ++t) xhat[t] = mlp[t] + x1[t];
+        if (scores) {
+            const double *f_out = op == 0 ? mlp : op == 1 ? sa : op == 2 ? xhat : op == 3 ? xhat : mlp;
+            const double *f_in = op == 0 ? x1 : op == 1 ? x : op == 2 ? x : op == 3 ? x1 : u;
+            rs_oracle_shift_scores(f_out, f_in, M, D, dist, scores);   /* u still holds LN(x1) */
+        }
+        if (sa_out) memcpy(sa_out, sa, sizeof(double) * md);
         if (x1_out) memcpy(x1_out, x1, sizeof(double) * md);
         if (mlp_out) memcpy(mlp_out, mlp, sizeof(double) * md);
-        if (xhat_out)
-            for (size_t t = 0; t < md; ++t) xhat_out[t] = mlp[t] + x1[t];
+        if (xhat_out) memcpy(xhat_out, xhat, sizeof(double) * md);
         rc = 0;
     }
-    free(u); free(qkv); free(att); free(x1); free(hid); free(mlp);
+    free(u); free(qkv); free(att); free(x1); free(hid); free(mlp); free(sa); free(xhat);
     return rc;
 }

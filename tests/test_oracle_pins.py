@@ -256,6 +256,77 @@ def test_block_scores_permutation_equivariant():
 
 
 # ----------------------------------------------------------------------------
+# Operation choice (Sec. 3.3, cases (i)-(iii)) and the other readings of the MLP case
+# ----------------------------------------------------------------------------
+def test_operation_choice_closed_forms():
+    B, N, D, H, Dm = 2, 5, 8, 2, 16
+    x = RNG.standard_normal((B, N, D))
+    c = RNG.standard_normal(D)
+    # (i) attention: SA == c (zero projection, bias c)  =>  s_i = ||c - x_i||
+    w = _weights(D, Dm)
+    w["w_proj"][:] = 0
+    w["b_proj"][:] = c
+    r = oracle.block(x, w, H, op=oracle.OP_ATTN)
+    np.testing.assert_allclose(r["sa"], np.broadcast_to(c, x.shape), rtol=0, atol=0)
+    np.testing.assert_allclose(r["scores"], np.linalg.norm(c - x, axis=-1), rtol=1e-13)
+    # (iii) whole block: both branches constant  =>  xhat - x = c + d for every token
+    d = RNG.standard_normal(D)
+    w["w_fc2"][:] = 0
+    w["b_fc2"][:] = d
+    r = oracle.block(x, w, H, op=oracle.OP_BLOCK)
+    np.testing.assert_allclose(r["scores"], np.full((B, N), np.linalg.norm(c + d)), rtol=1e-12)
+    r = oracle.block(x, w, H, op=oracle.OP_BLOCK, dist=oracle.DIST_L1)
+    np.testing.assert_allclose(r["scores"], np.full((B, N), np.abs(c + d).sum()), rtol=1e-12)
+    # residual stream before/after the MLP: xhat - x1 = d
+    r = oracle.block(x, w, H, op=oracle.OP_MLP_STREAM)
+    np.testing.assert_allclose(r["scores"], np.full((B, N), np.linalg.norm(d)), rtol=1e-12)
+    # the MLP's own input and output with MLP == 0: s = ||LN(x1)|| = sqrt(D var / (var + eps)), gamma 1, beta 0
+    w["b_fc2"][:] = 0
+    w["ln2_g"][:] = 1
+    w["ln2_b"][:] = 0
+    r = oracle.block(x, w, H, op=oracle.OP_MLP_NORMED, ln_eps=1e-3)
+    var = r["x1"].var(axis=-1)
+    np.testing.assert_allclose(r["scores"], np.sqrt(D * var / (var + 1e-3)), rtol=1e-12)
+    # identity-like block: nothing added on either branch  =>  case (iii) is exactly 0
+    w["b_proj"][:] = 0
+    r = oracle.block(x, w, H, op=oracle.OP_BLOCK)
+    np.testing.assert_array_equal(r["scores"], 0.0)
+    with pytest.raises(ValueError):
+        oracle.block(x, w, H, op=7)
+
+
+@pytest.mark.parametrize("dist", [0, 1, 2])
+def test_operation_choice_against_torch_library(dist):
+    """Every pair (f_out, f_in) rebuilt from torch CPU library ops in fp64, every distance from
+    torch's own norm / cosine_similarity."""
+    B, N, D, H, Dm = 2, 9, 16, 2, 40
+    x = RNG.standard_normal((B, N, D))
+    w = _weights(D, Dm, seed=11)
+    w["ln2_g"], w["ln2_b"] = RNG.standard_normal(D), RNG.standard_normal(D)
+    t = {k: torch.from_numpy(v) for k, v in w.items()}
+    tx = torch.from_numpy(x)
+    u = F.layer_norm(tx, (D,), t["ln1_g"], t["ln1_b"], 1e-6)
+    qkv = F.linear(u, t["w_qkv"].T, t["b_qkv"]).reshape(B, N, 3, H, D // H).permute(2, 0, 3, 1, 4)
+    att = F.scaled_dot_product_attention(qkv[0], qkv[1], qkv[2]).permute(0, 2, 1, 3).reshape(B, N, D)
+    sa = F.linear(att, t["w_proj"].T, t["b_proj"])
+    x1 = tx + sa
+    v = F.layer_norm(x1, (D,), t["ln2_g"], t["ln2_b"], 1e-6)
+    mlp = F.linear(F.gelu(F.linear(v, t["w_fc1"].T, t["b_fc1"])), t["w_fc2"].T, t["b_fc2"])
+    xhat = x1 + mlp
+    pairs = {oracle.OP_MLP: (mlp, x1), oracle.OP_ATTN: (sa, tx), oracle.OP_BLOCK: (xhat, tx),
+             oracle.OP_MLP_STREAM: (xhat, x1), oracle.OP_MLP_NORMED: (mlp, v)}
+    for op, (fo, fi) in pairs.items():
+        if dist == 0:
+            want = torch.linalg.vector_norm(fo - fi, dim=-1)
+        elif dist == 1:
+            want = torch.linalg.vector_norm(fo - fi, ord=1, dim=-1)
+        else:
+            want = 1.0 - F.cosine_similarity(fo, fi, dim=-1, eps=0.0)
+        r = oracle.block(x, w, H, dist=dist, op=op)
+        np.testing.assert_allclose(r["scores"], want.numpy(), rtol=1e-9, atol=1e-12, err_msg="op %d" % op)
+
+
+# ----------------------------------------------------------------------------
 # Representation shift, Eq. (4), and the three distances of Sec. 3.3
 # ----------------------------------------------------------------------------
 def test_shift_identity_is_zero():
