@@ -54,10 +54,20 @@ typedef enum { RS_F32 = 0, RS_BF16 = 1 } rs_dtype;
  * L2 is the paper's default. */
 typedef enum { RS_DIST_L2 = 0, RS_DIST_L1 = 1, RS_DIST_COS = 2 } rs_dist;
 
-/* Which transformation F the shift is measured around ("Operation choice",
- * Sec. 3.3).  Case (ii), the MLP, is the paper's default and the only one
- * rs_block_fwd computes; the others are reachable through rs_shift_topk. */
-typedef enum { RS_SHIFT_MLP = 0 } rs_shift_op;
+/* Which pair (f_out, f_in) the shift s = D(f_out, f_in) of rs_block_fwd is taken over
+ * ("Operation choice", Sec. 3.3).  With x' = SA(LN(x)) + x and xhat = MLP(LN(x')) + x':
+ *   RS_SHIFT_MLP         case (ii), the paper's default:  D(MLP(LN(x')), x')
+ *   RS_SHIFT_ATTN        case (i):                        D(SA(LN(x)), x)
+ *   RS_SHIFT_BLOCK       case (iii):                      D(xhat, x)
+ * and the two other ways "the shift before and after the MLP" can be read:
+ *   RS_SHIFT_MLP_STREAM  residual stream around the MLP:  D(xhat, x')
+ *   RS_SHIFT_MLP_NORMED  the MLP's own input and output:  D(MLP(v), v), v = LN(x')
+ * Every choice is computed in the epilogue of the GEMM that produces f_out; pruning always
+ * happens after the whole block. */
+typedef enum {
+    RS_SHIFT_MLP = 0, RS_SHIFT_ATTN = 1, RS_SHIFT_BLOCK = 2, RS_SHIFT_MLP_STREAM = 3,
+    RS_SHIFT_MLP_NORMED = 4
+} rs_shift_op;
 
 /* Weights of one encoder block, Eqs. (5),(6) of Sec. 3.3.  Element type follows
  * cfg->dtype.  Any bias pointer may be NULL (= zero); LayerNorm gamma NULL = 1,

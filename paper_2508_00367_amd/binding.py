@@ -17,7 +17,7 @@ LIB_PATH = os.path.join(_HERE, "librs_hip.so")
 RS_OK, RS_ERR_INVALID_ARG, RS_ERR_UNSUPPORTED, RS_ERR_WORKSPACE_TOO_SMALL, RS_ERR_DEVICE = range(5)
 RS_F32, RS_BF16 = 0, 1
 RS_DIST_L2, RS_DIST_L1, RS_DIST_COS = 0, 1, 2
-RS_SHIFT_MLP = 0
+RS_SHIFT_MLP, RS_SHIFT_ATTN, RS_SHIFT_BLOCK, RS_SHIFT_MLP_STREAM, RS_SHIFT_MLP_NORMED = 0, 1, 2, 3, 4
 
 RS_PROFILE_CLASSES = 11
 RS_EPI_BIAS, RS_EPI_BIAS_GELU, RS_EPI_BIAS_RES = 0, 1, 2

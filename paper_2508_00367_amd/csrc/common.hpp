@@ -95,7 +95,8 @@ enum GemmEpilogue {
     EPI_BIAS = 0,            // out = acc + bias
     EPI_BIAS_GELU = 1,       // out = gelu(acc + bias)
     EPI_BIAS_RES = 2,        // out = acc + bias + res
-    EPI_BIAS_RES_SHIFT = 3   // out = acc + bias + res; partial sums of D(acc + bias, res) per row
+    EPI_BIAS_RES_SHIFT = 3   // out = acc + bias + res; partial sums of D(f_out, f_in) per row, with
+                             // f_out = acc + bias (or out, if `post`) and f_in = res (or `ref`, if given)
 };
 
 // Number of per-row partial slots the SHIFT epilogue writes for an output width N.
@@ -106,7 +107,7 @@ constexpr int kShiftLanes = 3;  // floats per slot (L2/L1 use the first, cosine 
 // caller's [K, N] matrix.  partials: float [M, slots, kShiftLanes] for EPI_BIAS_RES_SHIFT.
 hipError_t launch_gemm(rs_dtype dt, GemmEpilogue epi, rs_dist dist, const void* a, const void* w,
                        const void* bias, const void* res, void* out, float* partials,
-                       int64_t M, int N, int K, hipStream_t s);
+                       const void* ref, bool post, int64_t M, int N, int K, hipStream_t s);
 
 // bf16 [K, N] row-major -> [N, K] row-major.
 hipError_t launch_pack_transpose(const void* w, void* wt, int K, int N, hipStream_t s);

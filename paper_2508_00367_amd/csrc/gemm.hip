@@ -17,7 +17,7 @@ namespace rs {
 // ---------------------------------------------------------------------------
 // bf16 MFMA GEMM:  out[m, n] = epi( sum_k a[m, k] * wt[n, k] )
 //   a  : [M, K] bf16 (token rows),  wt : [N, K] bf16 (packed weights),  K % 64 == 0.
-// Workgroup tile BM x BN, K step 64, WGM x WGN waves, LDS double buffered.
+// Workgroup tile BM x BN, K slices of BK, WGM x WGN waves, a ring of LDS stages.
 // LDS rows are 64 bf16 = 8 slots of 16 B; chunk c of row r sits in slot c ^ ((r ^ (r >> 3)) & 7).
 // The LDS has 64 banks of 4 bytes and serves a 16-byte-per-lane read 16 lanes at a time, so the
 // 16 consecutive rows those lanes read for one MFMA operand must fall into 16 different
@@ -65,7 +65,7 @@ __device__ __forceinline__ __amdgpu_buffer_rsrc_t make_rsrc(const void* base, in
 // other counters left at their maximum).
 constexpr int vmcnt_imm(int n) { return (n & 15) | ((n >> 4) << 14) | 0x0F70; }
 
-// 256 threads = 2 x 2 waves; workgroup tile BM x BN, wave tile BM/2 x BN/2, K slice BK (32 or 64).
+// WGM x WGN waves; workgroup tile BM x BN, wave tile BM/WGM x BN/WGN, K slice BK (32 or 64).
 // A ring of NSTAGE LDS stages of (BM + BN) rows x 2*BK bytes: K slices stream from global
 // memory directly into LDS (buffer_load ... lds, no register staging), NSTAGE-1 slices ahead of
 // the one the matrix cores work on.  Loads return in order, so "slice t has landed" is
@@ -73,13 +73,14 @@ constexpr int vmcnt_imm(int n) { return (n & 15) | ((n >> 4) << 14) | 0x0F70; }
 // padded to a multiple of NSTAGE with copies aimed past the end of the buffer resource (they
 // deliver zeros), which keeps the loop free of tail branches.  Operand fragments are double
 // buffered in registers and each LDS read is interleaved with its share of the previous K step's
-// MFMAs (sched_group_barrier).  WPE = waves per SIMD the register budget must allow (2 = two
-// workgroups per CU, so one's epilogue and barrier waits hide behind the other's MFMAs).
+// MFMAs (sched_group_barrier).  One workgroup per CU; the register budget is that of NW / 4 waves
+// per SIMD.
 template <int BM, int BN, int BK, int NSTAGE, int WGM, int WGN, int EPI, int DIST>
 __global__ __launch_bounds__(WGM* WGN * 64, WGM* WGN / 4) void gemm_bf16_kernel(
     const bf16raw* __restrict__ a, const bf16raw* __restrict__ wt, const bf16raw* __restrict__ bias,
     const bf16raw* __restrict__ res, bf16raw* __restrict__ out, float* __restrict__ partials,
-    int M, int N, int K, int tiles_m, int tiles_n, int slots, int gm) {
+    const bf16raw* __restrict__ ref, int post, int M, int N, int K, int tiles_m, int tiles_n, int slots,
+    int gm) {
     constexpr int NW = WGM * WGN;               // waves: WGM along tokens x WGN along features
     constexpr int WM = BM / WGM, WN = BN / WGN; // wave tile
     constexpr int TM = WM / 32, TN = WN / 32;   // MFMA tiles per wave
@@ -306,11 +307,18 @@ __global__ __launch_bounds__(WGM* WGN * 64, WGM* WGN / 4) void gemm_bf16_kernel(
                     for (int e = 0; e < 8; ++e) rr[e] = 0.f;
                     if (ok) Elem<bf16raw>::load8(res + (int64_t)m * N + n, rr);
                     if (EPI == EPI_BIAS_RES_SHIFT && ok) {
+                        // D(f_out, f_in): f_out is the branch output, or (post) the residual stream
+                        // after the add; f_in is the residual operand, or `ref` when one is given
+                        float fi[8];
+#pragma unroll
+                        for (int e = 0; e < 8; ++e) fi[e] = rr[e];
+                        if (ref) Elem<bf16raw>::load8(ref + (int64_t)m * N + n, fi);
 #pragma unroll
                         for (int e = 0; e < 8; ++e) {
-                            if (DIST == RS_DIST_L2) { float d = v[e] - rr[e]; p0 += d * d; }
-                            else if (DIST == RS_DIST_L1) { p0 += fabsf(v[e] - rr[e]); }
-                            else { p0 += v[e] * rr[e]; p1 += v[e] * v[e]; p2 += rr[e] * rr[e]; }
+                            const float fo = post ? v[e] + rr[e] : v[e];
+                            if (DIST == RS_DIST_L2) { float d = fo - fi[e]; p0 += d * d; }
+                            else if (DIST == RS_DIST_L1) { p0 += fabsf(fo - fi[e]); }
+                            else { p0 += fo * fi[e]; p1 += fo * fo; p2 += fi[e] * fi[e]; }
                         }
                     }
 #pragma unroll
@@ -348,7 +356,8 @@ struct GemmCfg {
 
 template <int EPI, int DIST>
 static hipError_t launch_bf16(const void* a, const void* wt, const void* bias, const void* res,
-                              void* out, float* partials, int64_t M, int N, int K, hipStream_t s) {
+                              void* out, float* partials, const void* ref, bool post, int64_t M, int N,
+                              int K, hipStream_t s) {
     using C = GemmCfg;
     const int tiles_m = (int)((M + C::BM - 1) / C::BM), tiles_n = (N + C::BN - 1) / C::BN;
     const int slots = (tiles_n * C::BN) / C::WN;
@@ -356,7 +365,7 @@ static hipError_t launch_bf16(const void* a, const void* wt, const void* bias, c
     hipLaunchKernelGGL((gemm_bf16_kernel<C::BM, C::BN, C::BK, C::NSTAGE, C::WGM, C::WGN, EPI, DIST>),
                        dim3(tiles_m * tiles_n), dim3(C::WGM * C::WGN * 64), 0, s, (const bf16raw*)a,
                        (const bf16raw*)wt, (const bf16raw*)bias, (const bf16raw*)res, (bf16raw*)out, partials,
-                       (int)M, N, K, tiles_m, tiles_n, slots, gm);
+                       (const bf16raw*)ref, post ? 1 : 0, (int)M, N, K, tiles_m, tiles_n, slots, gm);
     return hipGetLastError();
 }
 
@@ -371,8 +380,9 @@ __global__ __launch_bounds__(256) void gemm_f32_kernel(const float* __restrict__
                                                        const float* __restrict__ bias,
                                                        const float* __restrict__ res,
                                                        float* __restrict__ out,
-                                                       float* __restrict__ partials, int M, int N,
-                                                       int K, int slots) {
+                                                       float* __restrict__ partials,
+                                                       const float* __restrict__ ref, int post, int M,
+                                                       int N, int K, int slots) {
     constexpr int T = 64, KS = 16;
     __shared__ float sa[KS][T + 4];  // a tile transposed: sa[k][m]
     __shared__ float sw[KS][T + 4];  // sw[k][n]
@@ -430,12 +440,18 @@ __global__ __launch_bounds__(256) void gemm_f32_kernel(const float* __restrict__
                     float4 rr = *reinterpret_cast<const float4*>(res + (int64_t)m * N + n);
                     r[0] = rr.x; r[1] = rr.y; r[2] = rr.z; r[3] = rr.w;
                 }
-                if (EPI == EPI_BIAS_RES_SHIFT) {
+                if (EPI == EPI_BIAS_RES_SHIFT && m_ok) {
+                    float fi[4] = {r[0], r[1], r[2], r[3]};
+                    if (ref) {
+                        float4 q = *reinterpret_cast<const float4*>(ref + (int64_t)m * N + n);
+                        fi[0] = q.x; fi[1] = q.y; fi[2] = q.z; fi[3] = q.w;
+                    }
 #pragma unroll
                     for (int e = 0; e < 4; ++e) {
-                        if (DIST == RS_DIST_L2) { float d = v[e] - r[e]; p0 += d * d; }
-                        else if (DIST == RS_DIST_L1) { p0 += fabsf(v[e] - r[e]); }
-                        else { p0 += v[e] * r[e]; p1 += v[e] * v[e]; p2 += r[e] * r[e]; }
+                        const float fo = post ? v[e] + r[e] : v[e];
+                        if (DIST == RS_DIST_L2) { float d = fo - fi[e]; p0 += d * d; }
+                        else if (DIST == RS_DIST_L1) { p0 += fabsf(fo - fi[e]); }
+                        else { p0 += fo * fi[e]; p1 += fo * fo; p2 += fi[e] * fi[e]; }
                     }
                 }
 #pragma unroll
@@ -461,11 +477,12 @@ __global__ __launch_bounds__(256) void gemm_f32_kernel(const float* __restrict__
 
 template <int EPI, int DIST>
 static hipError_t launch_f32(const void* a, const void* w, const void* bias, const void* res,
-                             void* out, float* partials, int64_t M, int N, int K, hipStream_t s) {
+                             void* out, float* partials, const void* ref, bool post, int64_t M, int N,
+                             int K, hipStream_t s) {
     dim3 grid((N + 63) / 64, (unsigned)((M + 63) / 64));
     hipLaunchKernelGGL((gemm_f32_kernel<EPI, DIST>), grid, dim3(256), 0, s, (const float*)a,
                        (const float*)w, (const float*)bias, (const float*)res, (float*)out, partials,
-                       (int)M, N, K, (N + 63) / 64);
+                       (const float*)ref, post ? 1 : 0, (int)M, N, K, (N + 63) / 64);
     return hipGetLastError();
 }
 
@@ -476,24 +493,24 @@ int gemm_shift_slots(rs_dtype dt, int N) {
 
 template <int EPI, int DIST>
 static hipError_t launch_any(rs_dtype dt, const void* a, const void* w, const void* bias,
-                             const void* res, void* out, float* partials, int64_t M, int N, int K,
-                             hipStream_t s) {
-    return dt == RS_F32 ? launch_f32<EPI, DIST>(a, w, bias, res, out, partials, M, N, K, s)
-                        : launch_bf16<EPI, DIST>(a, w, bias, res, out, partials, M, N, K, s);
+                             const void* res, void* out, float* partials, const void* ref, bool post,
+                             int64_t M, int N, int K, hipStream_t s) {
+    return dt == RS_F32 ? launch_f32<EPI, DIST>(a, w, bias, res, out, partials, ref, post, M, N, K, s)
+                        : launch_bf16<EPI, DIST>(a, w, bias, res, out, partials, ref, post, M, N, K, s);
 }
 
 hipError_t launch_gemm(rs_dtype dt, GemmEpilogue epi, rs_dist dist, const void* a, const void* w,
-                       const void* bias, const void* res, void* out, float* partials, int64_t M,
-                       int N, int K, hipStream_t s) {
+                       const void* bias, const void* res, void* out, float* partials, const void* ref,
+                       bool post, int64_t M, int N, int K, hipStream_t s) {
     if (M == 0) return hipSuccess;
     switch (epi) {
-        case EPI_BIAS: return launch_any<EPI_BIAS, 0>(dt, a, w, bias, res, out, partials, M, N, K, s);
-        case EPI_BIAS_GELU: return launch_any<EPI_BIAS_GELU, 0>(dt, a, w, bias, res, out, partials, M, N, K, s);
-        case EPI_BIAS_RES: return launch_any<EPI_BIAS_RES, 0>(dt, a, w, bias, res, out, partials, M, N, K, s);
+        case EPI_BIAS: return launch_any<EPI_BIAS, 0>(dt, a, w, bias, res, out, partials, ref, post, M, N, K, s);
+        case EPI_BIAS_GELU: return launch_any<EPI_BIAS_GELU, 0>(dt, a, w, bias, res, out, partials, ref, post, M, N, K, s);
+        case EPI_BIAS_RES: return launch_any<EPI_BIAS_RES, 0>(dt, a, w, bias, res, out, partials, ref, post, M, N, K, s);
         case EPI_BIAS_RES_SHIFT:
-            if (dist == RS_DIST_L2) return launch_any<EPI_BIAS_RES_SHIFT, RS_DIST_L2>(dt, a, w, bias, res, out, partials, M, N, K, s);
-            if (dist == RS_DIST_L1) return launch_any<EPI_BIAS_RES_SHIFT, RS_DIST_L1>(dt, a, w, bias, res, out, partials, M, N, K, s);
-            return launch_any<EPI_BIAS_RES_SHIFT, RS_DIST_COS>(dt, a, w, bias, res, out, partials, M, N, K, s);
+            if (dist == RS_DIST_L2) return launch_any<EPI_BIAS_RES_SHIFT, RS_DIST_L2>(dt, a, w, bias, res, out, partials, ref, post, M, N, K, s);
+            if (dist == RS_DIST_L1) return launch_any<EPI_BIAS_RES_SHIFT, RS_DIST_L1>(dt, a, w, bias, res, out, partials, ref, post, M, N, K, s);
+            return launch_any<EPI_BIAS_RES_SHIFT, RS_DIST_COS>(dt, a, w, bias, res, out, partials, ref, post, M, N, K, s);
     }
     return hipErrorInvalidValue;
 }

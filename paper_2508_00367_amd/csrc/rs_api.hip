@@ -128,7 +128,8 @@ static rs_status check_cfg(const rs_block_cfg* c) {
     RS_REQUIRE(c->dtype == RS_F32 || c->dtype == RS_BF16, RS_ERR_INVALID_ARG, "unknown dtype %d", (int)c->dtype);
     RS_REQUIRE(c->dist == RS_DIST_L2 || c->dist == RS_DIST_L1 || c->dist == RS_DIST_COS, RS_ERR_INVALID_ARG,
                "unknown distance %d", (int)c->dist);
-    RS_REQUIRE(c->op == RS_SHIFT_MLP, RS_ERR_INVALID_ARG, "unknown shift operation %d", (int)c->op);
+    RS_REQUIRE(c->op >= RS_SHIFT_MLP && c->op <= RS_SHIFT_MLP_NORMED, RS_ERR_INVALID_ARG,
+               "unknown shift operation %d", (int)c->op);
     RS_REQUIRE(c->B >= 0 && c->N >= 0, RS_ERR_INVALID_ARG, "negative B or N");
     RS_REQUIRE(c->D > 0 && c->H > 0 && c->Dm > 0, RS_ERR_INVALID_ARG, "D, H, Dm must be positive");
     RS_REQUIRE(c->D % c->H == 0, RS_ERR_INVALID_ARG, "D %d not divisible by H %d", c->D, c->H);
@@ -310,7 +311,7 @@ rs_status rs_linear_fwd(const void* a, const void* w, const void* bias, const vo
                RS_ERR_INVALID_ARG, "tensors must be 16-byte aligned");
     hipStream_t st = (hipStream_t)hip_stream;
     const GemmEpilogue e = epi == RS_EPI_BIAS ? EPI_BIAS : epi == RS_EPI_BIAS_GELU ? EPI_BIAS_GELU : EPI_BIAS_RES;
-    RS_LAUNCH_K(K_LINEAR, st, launch_gemm(dtype, e, RS_DIST_L2, a, w, bias, res, out, nullptr, M, N, K, st));
+    RS_LAUNCH_K(K_LINEAR, st, launch_gemm(dtype, e, RS_DIST_L2, a, w, bias, res, out, nullptr, nullptr, false, M, N, K, st));
     return RS_OK;
 }
 
@@ -374,20 +375,28 @@ rs_status rs_block_fwd(const rs_block_cfg* cfg, const rs_block_weights* w, const
 
     // x1 = SA(LN(x)) + x                                                     Eq. (5)
     RS_LAUNCH_K(K_LN, s, launch_layernorm(dt, x, w->ln1_g, w->ln1_b, u, M, D, c.ln_eps, s));
-    RS_LAUNCH_K(K_GEMM_QKV, s, launch_gemm(dt, EPI_BIAS, RS_DIST_L2, u, wq, w->b_qkv, nullptr, qkv, nullptr, M, 3 * D, D, s));
+    RS_LAUNCH_K(K_GEMM_QKV, s, launch_gemm(dt, EPI_BIAS, RS_DIST_L2, u, wq, w->b_qkv, nullptr, qkv, nullptr, nullptr, false, M, 3 * D, D, s));
     {
         const size_t e = elem_size(dt);
         const char* qp = (const char*)qkv;
         RS_LAUNCH_K(K_ATTN, s, launch_attention(dt, qp, qp + (size_t)D * e, qp + 2 * (size_t)D * e, att, c.B, c.H, c.N,
                                    (int64_t)c.N * 3 * D, 3 * D, 64, (int64_t)c.N * D, D, 64, scale, s));
     }
-    RS_LAUNCH_K(K_GEMM_PROJ, s, launch_gemm(dt, EPI_BIAS_RES, RS_DIST_L2, att, wp, w->b_proj, x, x1, nullptr, M, D, D, s));
+    // the shift around the attention layer, case (i), comes out of the projection's epilogue
+    const bool attn_scores = want_scores && c.op == RS_SHIFT_ATTN;
+    RS_LAUNCH_K(K_GEMM_PROJ, s, launch_gemm(dt, attn_scores ? EPI_BIAS_RES_SHIFT : EPI_BIAS_RES, c.dist, att, wp, w->b_proj, x, x1,
+                            partials, nullptr, false, M, D, D, s));
     // xhat = MLP(LN(x1)) + x1, with the shift partial sums of D(MLP(LN(x1)), x1)   Eq. (6), Eq. (4)
     RS_LAUNCH_K(K_LN, s, launch_layernorm(dt, x1, w->ln2_g, w->ln2_b, u, M, D, c.ln_eps, s));
-    RS_LAUNCH_K(K_GEMM_FC1, s, launch_gemm(dt, EPI_BIAS_GELU, RS_DIST_L2, u, w1, w->b_fc1, nullptr, hid, nullptr, M, Dm, D, s));
+    RS_LAUNCH_K(K_GEMM_FC1, s, launch_gemm(dt, EPI_BIAS_GELU, RS_DIST_L2, u, w1, w->b_fc1, nullptr, hid, nullptr, nullptr, false, M, Dm, D, s));
     void* xhat = prune ? att : y;  // without pruning the block output goes straight to y
-    RS_LAUNCH_K(K_GEMM_FC2, s, launch_gemm(dt, want_scores ? EPI_BIAS_RES_SHIFT : EPI_BIAS_RES, c.dist, hid, w2, w->b_fc2, x1,
-                          xhat, partials, M, D, Dm, s));
+    // every other choice of (f_out, f_in) comes out of fc2's epilogue: f_out is the MLP output or
+    // (post) xhat, f_in the residual operand x1 or another tensor still in memory (x, LN(x1))
+    const bool fc2_scores = want_scores && !attn_scores;
+    const bool post = c.op == RS_SHIFT_BLOCK || c.op == RS_SHIFT_MLP_STREAM;
+    const void* ref = c.op == RS_SHIFT_BLOCK ? x : c.op == RS_SHIFT_MLP_NORMED ? (const void*)u : nullptr;
+    RS_LAUNCH_K(K_GEMM_FC2, s, launch_gemm(dt, fc2_scores ? EPI_BIAS_RES_SHIFT : EPI_BIAS_RES, c.dist, hid, w2, w->b_fc2, x1,
+                          xhat, partials, ref, post, M, D, Dm, s));
     if (want_scores) RS_LAUNCH_K(K_SCORE, s, launch_finalize_scores(c.dist, partials, L.slots, sc, M, s));
     // keep the n_keep highest-shift tokens (plus the prefix) and compact them
     RS_LAUNCH_K(K_SELECT, s, launch_select(sc, kept_idx, c.B, c.N, c.n_prefix, c.n_keep, s));

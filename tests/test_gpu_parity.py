@@ -153,12 +153,13 @@ def _block_inputs(seed, B, N, D, Dm, dtype, block=0, std=0.02, spread=0.0, affin
     return x, w
 
 
-def _run_block(x, w, H, P, K, dtype, dist=rs.RS_DIST_L2, want_scores=True, pack=False, ln_eps=1e-6):
+def _run_block(x, w, H, P, K, dtype, dist=rs.RS_DIST_L2, want_scores=True, pack=False, ln_eps=1e-6,
+               op=rs.RS_SHIFT_MLP):
     B, N, D = x.shape
     Dm = w["w_fc1"].shape[1]
     dw = {k: to_dev(v, dtype) for k, v in w.items()}
     dx = to_dev(x, dtype)
-    cfg = rs.make_cfg(B, N, D, H, Dm, P, K, dx.dtype, ln_eps=ln_eps, dist=dist)
+    cfg = rs.make_cfg(B, N, D, H, Dm, P, K, dx.dtype, ln_eps=ln_eps, dist=dist, op=op)
     packed = None
     if pack and dtype == "bf16":
         packed = torch.empty(rs.rs_packed_weights_size(cfg), dtype=torch.uint8, device="cuda")
@@ -174,7 +175,7 @@ def _run_block(x, w, H, P, K, dtype, dist=rs.RS_DIST_L2, want_scores=True, pack=
 
 def _check_block(x, w, H, P, K, dtype, dist=rs.RS_DIST_L2, **kw):
     y, kept, scores = _run_block(x, w, H, P, K, dtype, dist=dist, **kw)
-    ref = oracle.block(x, w, H, ln_eps=kw.get("ln_eps", 1e-6), dist=dist)
+    ref = oracle.block(x, w, H, ln_eps=kw.get("ln_eps", 1e-6), dist=dist, op=kw.get("op", 0))
     s, kept_h = to_host(scores), kept.cpu().numpy()
     e_s = norm_err(s, ref["scores"])
     exact = check_kept_admissible(kept_h, s, ref["scores"], P, K)
@@ -213,6 +214,20 @@ def test_block_other_distances(dist):
     _say("block dist", dist)
     _check_block(x, w, 2, 1, 40, "bf16", dist=dist)
     _check_block(x.astype(np.float32), w, 2, 1, 40, "f32", dist=dist)
+
+
+@pytest.mark.parametrize("dtype", ["bf16", "f32"])
+@pytest.mark.parametrize("dist", [rs.RS_DIST_L2, rs.RS_DIST_L1, rs.RS_DIST_COS])
+@pytest.mark.parametrize("op", [rs.RS_SHIFT_ATTN, rs.RS_SHIFT_BLOCK, rs.RS_SHIFT_MLP_STREAM, rs.RS_SHIFT_MLP_NORMED])
+def test_block_operation_choice(op, dist, dtype):
+    """The shift around the attention layer, around the whole block, and the two other readings
+    of the MLP case (Sec. 3.3, "Operation choice"), each with every distance; ragged row and
+    column tiles (300 tokens x 3 images, D 192)."""
+    assert (rs.RS_SHIFT_MLP, rs.RS_SHIFT_ATTN, rs.RS_SHIFT_BLOCK, rs.RS_SHIFT_MLP_STREAM, rs.RS_SHIFT_MLP_NORMED) == \
+        (oracle.OP_MLP, oracle.OP_ATTN, oracle.OP_BLOCK, oracle.OP_MLP_STREAM, oracle.OP_MLP_NORMED)
+    _say("block op", op, "dist", dist, dtype)
+    x, w = _block_inputs(6, 3, 300, 192, 768, dtype, std=0.1, spread=0.3, affine_ln=True)
+    _check_block(x, w, 3, 1, 120, dtype, dist=dist, op=op)
 
 
 @pytest.mark.parametrize("dtype", ["bf16", "f32"])
