@@ -33,7 +33,8 @@ def parse():
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--workload", default="vit_b16",
-                    help="vit_s16 | vit_b16 | video_vit_b16 | video_vit_l14 (synth_inputs.WORKLOADS)")
+                    help="a key of synth_inputs.WORKLOADS: vit_b16 (default) | vit_s16 | video_vit_b16 | "
+                         "video_vit_l14 | deit_t/s/b | umt_b_ret/qa | umt_l_ret/qa | deit_s_toy | umt_b_toy")
     ap.add_argument("--unpruned", action="store_true", help="run the same stack without pruning")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-sample", type=int, default=0, help="images for the CPU baseline (0 = auto)")
@@ -74,8 +75,10 @@ def main():
     wl = dict(si.WORKLOADS[a.workload])
     assert wl["dtype"] == "bf16"
     B, N, D, H, Dm, L = wl["B"], wl["N"], wl["D"], wl["H"], wl["Dm"], wl["blocks"]
+    P = wl.get("n_prefix", 1)                        # protected prefix (class token), 0 for the video models
+    op = {"mlp": rs.RS_SHIFT_MLP, "attn": rs.RS_SHIFT_ATTN, "block": rs.RS_SHIFT_BLOCK}[wl.get("op", "mlp")]
     prune = None if a.unpruned else wl["prune"]
-    sched = rs.keep_counts(N, 1, L, prune)           # per block: (tokens in, non-prefix kept)
+    sched = rs.keep_counts(N, P, L, prune)           # per block: (tokens in, non-prefix kept)
     tdt = torch.bfloat16
     dev = "cuda"
 
@@ -87,12 +90,12 @@ def main():
     weights, keep_alive = [], []
     for l in range(L):
         w = {k: up(v) for k, v in si.block_weights(0, l, D, Dm).items()}
-        cfg0 = rs.make_cfg(B, N, D, H, Dm, 1, N - 1, tdt)
+        cfg0 = rs.make_cfg(B, N, D, H, Dm, P, N - P, tdt)
         packed = torch.empty(rs.rs_packed_weights_size(cfg0), dtype=torch.uint8, device=dev)
         rs.rs_pack_weights(cfg0, rs.make_weights(w), packed)      # one-off, untimed
         keep_alive.append((w, packed))
         weights.append(rs.make_weights(w, packed))
-    cfgs = [rs.make_cfg(B, n_in, D, H, Dm, 1, n_keep, tdt) for n_in, n_keep in sched]
+    cfgs = [rs.make_cfg(B, n_in, D, H, Dm, P, n_keep, tdt, op=op) for n_in, n_keep in sched]
     ws = torch.empty(max(rs.rs_block_workspace_size(c) for c in cfgs), dtype=torch.uint8, device=dev)
     bufs = [torch.empty((B, N, D), device=dev, dtype=tdt) for _ in range(2)]
     kept = torch.empty((B, N), device=dev, dtype=torch.int32)
@@ -141,8 +144,8 @@ def main():
         fl["attention"] += 4.0 * B * n_in * n_in * D
         by["attention"] += 4.0 * M * D * e            # read q, k, v once, write o
         by["layernorm"] += 2 * 2.0 * M * D * e
-        if n_keep < n_in - 1:                          # score finalise + select + gather of K rows
-            K = 1 + n_keep
+        if n_keep < n_in - P:                          # score finalise + select + gather of K rows
+            K = P + n_keep
             by["prune"] += B * (8.0 * n_in + 4.0 * K + 2.0 * K * D * e)
     total_flops = sum(fl.values())
 
@@ -165,7 +168,7 @@ def main():
         kernels["layernorm"] = {"avg_us": round(avg_s * 1e6, 2), "launches_per_step": per_step,
                                 "GB/s": round(by["layernorm"] / per_step / avg_s / 1e9, 1)}
     prune_ms = sum(prof[k][0] for k in ("shift_score", "select", "gather")) / a.steps
-    n_prune = sum(1 for (n_in, n_keep) in sched if n_keep < n_in - 1)
+    n_prune = sum(1 for (n_in, n_keep) in sched if n_keep < n_in - P)
     if n_prune:
         kernels["prune_pass"] = {"ms_per_step": round(prune_ms, 4), "passes_per_step": n_prune,
                                  "GB/s": round(by["prune"] / (prune_ms * 1e-3) / 1e9, 1),
@@ -182,7 +185,8 @@ def main():
                 "whole_step_frac_of_mfma_peak": round(total_flops / (ms_per_step * 1e-3) / 1e12 / PEAK_BF16_TFLOPS, 4)}
 
     out = {
-        "metric": "images/s ViT-B fwd w/ rep-shift pruning", "value": round(images_s, 1), "unit": "images/s",
+        "metric": "images/s ViT-B fwd w/ rep-shift pruning" if a.workload == "vit_b16" else
+                  "images/s encoder fwd w/ rep-shift pruning", "value": round(images_s, 1), "unit": "images/s",
         "n_gpus": 1, "steps": a.steps, "warmup": a.warmup, "ms_per_step": round(ms_per_step, 4),
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16",
         "data": "synthetic (seeded N(0,1) tokens, N(0,0.02) weights, resident in HBM)",
@@ -237,7 +241,7 @@ def main():
         wts = [{k: si.round_to_bf16(v) for k, v in si.block_weights(0, l, D, Dm).items()} for l in range(L)]
         t0 = time.perf_counter()
         for l, (n_in, n_keep) in enumerate(sched):
-            r = oracle.block_pruned(xs, wts[l], H, 1, n_keep)
+            r = oracle.block_pruned(xs, wts[l], H, P, n_keep, op=op)   # the op codes are the same on both sides
             xs = r["y"]
         tc = time.perf_counter() - t0
         out["cpu_baseline"] = {"value": round(ns / tc, 3), "unit": "images/s", "cores": oracle.num_threads(),

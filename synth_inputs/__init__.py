@@ -121,4 +121,28 @@ WORKLOADS = {
                           prune=dict(kind="drop_pct", pct=50, after=[2, 5, 8])),
     "video_vit_l14": dict(dtype="bf16", B=4, N=4097, D=1024, H=16, Dm=4096, blocks=24,
                           prune=dict(kind="drop_pct", pct=30, after=[4, 8, 12, 16])),
+    # --- the shapes and schedules of the paper's own runs (Sec. 4.1, 4.2, 3.2), synthetic data ---
+    # image classification, Sec. 4.2: batch 512, 20 % of the patch tokens dropped after blocks 1, 4, 7
+    "deit_t": dict(dtype="bf16", B=512, N=197, D=192, H=3, Dm=768, blocks=12,
+                   prune=dict(kind="drop_pct", pct=20, after=[1, 4, 7])),
+    "deit_s": dict(dtype="bf16", B=512, N=197, D=384, H=6, Dm=1536, blocks=12,
+                   prune=dict(kind="drop_pct", pct=20, after=[1, 4, 7])),
+    "deit_b": dict(dtype="bf16", B=512, N=197, D=768, H=12, Dm=3072, blocks=12,
+                   prune=dict(kind="drop_pct", pct=20, after=[1, 4, 7])),
+    # video-text retrieval / video QA, Sec. 4.1: batch 20, 12 frames x 196 patches, no class token,
+    # 20 % (retrieval) or 10 % (QA) dropped in each of the first three blocks
+    "umt_b_ret": dict(dtype="bf16", B=20, N=2352, n_prefix=0, D=768, H=12, Dm=3072, blocks=12,
+                      prune=dict(kind="drop_pct", pct=20, after=[1, 2, 3])),
+    "umt_b_qa": dict(dtype="bf16", B=20, N=2352, n_prefix=0, D=768, H=12, Dm=3072, blocks=12,
+                     prune=dict(kind="drop_pct", pct=10, after=[1, 2, 3])),
+    "umt_l_ret": dict(dtype="bf16", B=20, N=2352, n_prefix=0, D=1024, H=16, Dm=4096, blocks=24,
+                      prune=dict(kind="drop_pct", pct=20, after=[1, 2, 3])),
+    "umt_l_qa": dict(dtype="bf16", B=20, N=2352, n_prefix=0, D=1024, H=16, Dm=4096, blocks=24,
+                     prune=dict(kind="drop_pct", pct=10, after=[1, 2, 3])),
+    # toy study of Sec. 3.2: the k lowest-score tokens dropped at ONE layer (here layer index 4 of
+    # [0, 2, 4, 6, 8], i.e. after block 5), shift taken around the attention layer
+    "deit_s_toy": dict(dtype="bf16", B=512, N=197, D=384, H=6, Dm=1536, blocks=12, op="attn",
+                       prune=dict(kind="drop_count", r=40, after=[5])),
+    "umt_b_toy": dict(dtype="bf16", B=20, N=2352, n_prefix=0, D=768, H=12, Dm=3072, blocks=12, op="attn",
+                      prune=dict(kind="drop_count", r=1100, after=[5])),
 }

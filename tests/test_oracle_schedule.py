@@ -60,3 +60,27 @@ def test_token_counts_of_the_workloads():
         [1569, 1569, 785, 785, 785, 393, 393, 393, 197, 197, 197, 197]
     assert sch.tokens_per_block(4097, 1, 24, w["video_vit_l14"]["prune"]) == \
         [4097] * 4 + [2869] * 4 + [2009] * 4 + [1407] * 4 + [986] * 8
+
+
+def test_paper_workloads_match_the_printed_rows(golden_dir):
+    """The bench workloads named after the paper's runs carry exactly the shape and schedule of
+    the fixture row whose printed cost they reproduce."""
+    import synth_inputs as si
+    rows = {r[0]: r for r in _rows(golden_dir)}
+    for wl_name, row in (("deit_t", "deit_t_ours"), ("deit_s", "deit_s_ours"), ("deit_b", "deit_b_ours"),
+                         ("umt_b_ret", "umt_b_ret"), ("umt_b_qa", "umt_b_qa"),
+                         ("umt_l_ret", "umt_l_ret"), ("umt_l_qa", "umt_l_qa")):
+        w = si.WORKLOADS[wl_name]
+        _, N, P, D, blocks, pct, after, _ = rows[row]
+        assert (w["N"], w.get("n_prefix", 1), w["D"], w["blocks"]) == (N, P, D, blocks), wl_name
+        assert w["prune"] == dict(kind="drop_pct", pct=pct, after=after), wl_name
+        assert w["Dm"] == 4 * D and w["D"] // w["H"] == 64
+    # the product's schedule helper agrees with the checker's on every workload
+    from paper_2508_00367_amd import schedule as psch
+    for name, w in si.WORKLOADS.items():
+        P = w.get("n_prefix", 1)
+        assert [n for n, _ in psch.keep_counts(w["N"], P, w["blocks"], w["prune"])] == \
+            sch.tokens_per_block(w["N"], P, w["blocks"], w["prune"]), name
+    assert sch.tokens_per_block(2352, 0, 12, si.WORKLOADS["umt_b_ret"]["prune"])[:5] == [2352, 1882, 1506, 1205, 1205]
+    assert sch.tokens_per_block(197, 1, 12, si.WORKLOADS["deit_b"]["prune"]) == \
+        [197, 158, 158, 158, 127, 127, 127, 102, 102, 102, 102, 102]
