@@ -202,49 +202,43 @@ __global__ __launch_bounds__(WGM* WGN * 64, WGM* WGN / 4) void gemm_bf16_kernel(
         }                                                                                                 \
         __builtin_amdgcn_sched_barrier(0);                                                                \
     }
-// One K slice from cur_: wait until it has landed, barrier, start the copies of the slice
-// NSTAGE-1 ahead into the stage every wave has just left, then the MFMAs.
+// One K slice from cur_ (its first fragments are already in f0).  Three of the four K steps run
+// with the LDS reads of the following step between their MFMAs; then the wave waits for slice
+// t+1 (in nxt_) to land, meets the others at the slice's one barrier -- after it every wave has
+// finished reading cur_, so the copies of slice t+2 may overwrite it -- and the last K step's
+// MFMAs cover those copies and the first fragment reads of slice t+1: the matrix cores have
+// work on both sides of the barrier.
 #define RS_GEMM_SLICE(cur_, nxt_, t_)                                                                     \
     {                                                                                                     \
-        __builtin_amdgcn_s_waitcnt(vmcnt_imm((NSTAGE - 2) * LPW));                                        \
-        __syncthreads();                                                                                  \
-        Frags<TN, TM> f0, f1;                                                                             \
-        RS_GEMM_LOAD_FRAGS(f0, cur_, 0)                                                                   \
-        __builtin_amdgcn_sched_barrier(0);                                                                \
-        RS_GEMM_DMA(nxt_, (t_) + NSTAGE - 1)                                                              \
         RS_GEMM_LOAD_FRAGS(f1, cur_, 1)                                                                   \
         RS_GEMM_MFMA(f0)                                                                                  \
-        RS_GEMM_INTERLEAVE(1)                                                                             \
-        if (KK == 4) {                                                                                    \
-            RS_GEMM_LOAD_FRAGS(f0, cur_, 2)                                                               \
-            RS_GEMM_MFMA(f1)                                                                              \
-            RS_GEMM_INTERLEAVE(0)                                                                         \
-            RS_GEMM_LOAD_FRAGS(f1, cur_, 3)                                                               \
-            RS_GEMM_MFMA(f0)                                                                              \
-            RS_GEMM_INTERLEAVE(0)                                                                         \
-        }                                                                                                 \
+        RS_GEMM_INTERLEAVE(0)                                                                             \
+        RS_GEMM_LOAD_FRAGS(f0, cur_, 2)                                                                   \
         RS_GEMM_MFMA(f1)                                                                                  \
-        __builtin_amdgcn_sched_barrier(0);                                                                \
+        RS_GEMM_INTERLEAVE(0)                                                                             \
+        RS_GEMM_LOAD_FRAGS(f1, cur_, 3)                                                                   \
+        RS_GEMM_MFMA(f0)                                                                                  \
+        RS_GEMM_INTERLEAVE(0)                                                                             \
+        __builtin_amdgcn_s_waitcnt(vmcnt_imm(0));                                                         \
+        __syncthreads();                                                                                  \
+        RS_GEMM_DMA(cur_, (t_) + 2)                                                                       \
+        RS_GEMM_LOAD_FRAGS(f0, nxt_, 0)                                                                   \
+        RS_GEMM_MFMA(f1)                                                                                  \
+        RS_GEMM_INTERLEAVE(1)                                                                             \
     }
 
-    // prologue: slices 0 .. NSTAGE-2
+    // prologue: slice 0 lands, slice 1 is on its way, the first fragments are in registers
+    static_assert(NSTAGE == 2 && KK == 4, "the slice schedule below is written for two stages of 64-wide slices");
+    Frags<TN, TM> f0, f1;
     RS_GEMM_DMA(stage0, 0)
-    if (NSTAGE > 2) RS_GEMM_DMA(stage1, 1)
-    if (NSTAGE > 3) RS_GEMM_DMA(stage2, 2)
-    for (int t = 0; t < S_pad; t += NSTAGE) {
-        if (NSTAGE == 2) {
-            RS_GEMM_SLICE(stage0, stage1, t)
-            RS_GEMM_SLICE(stage1, stage0, t + 1)
-        } else if (NSTAGE == 3) {
-            RS_GEMM_SLICE(stage0, stage2, t)
-            RS_GEMM_SLICE(stage1, stage0, t + 1)
-            RS_GEMM_SLICE(stage2, stage1, t + 2)
-        } else {
-            RS_GEMM_SLICE(stage0, stage3, t)
-            RS_GEMM_SLICE(stage1, stage0, t + 1)
-            RS_GEMM_SLICE(stage2, stage1, t + 2)
-            RS_GEMM_SLICE(stage3, stage2, t + 3)
-        }
+    __builtin_amdgcn_s_waitcnt(vmcnt_imm(0));
+    __syncthreads();
+    RS_GEMM_DMA(stage1, 1)
+    RS_GEMM_LOAD_FRAGS(f0, stage0, 0)
+    __builtin_amdgcn_sched_barrier(0);
+    for (int t = 0; t < S_pad; t += 2) {
+        RS_GEMM_SLICE(stage0, stage1, t)
+        RS_GEMM_SLICE(stage1, stage0, t + 1)
     }
     __builtin_amdgcn_s_waitcnt(vmcnt_imm(0));  // the trailing (empty) copies too: the stages get reused
 #undef RS_GEMM_DMA
