@@ -91,12 +91,28 @@ inline size_t elem_size(rs_dtype t) { return t == RS_F32 ? 4 : 2; }
 hipError_t launch_layernorm(rs_dtype dt, const void* x, const void* gamma, const void* beta,
                             void* out, int64_t M, int D, float eps, hipStream_t s);
 
+// stats[M] = (mean, 1 / sqrt(population variance + eps)) of each row of x[M, D], as float pairs.
+hipError_t launch_rowstats(rs_dtype dt, const void* x, float* stats, int64_t M, int D, float eps,
+                           hipStream_t s);
+
 enum GemmEpilogue {
     EPI_BIAS = 0,            // out = acc + bias
     EPI_BIAS_GELU = 1,       // out = gelu(acc + bias)
     EPI_BIAS_RES = 2,        // out = acc + bias + res
-    EPI_BIAS_RES_SHIFT = 3   // out = acc + bias + res; partial sums of D(f_out, f_in) per row, with
+    EPI_BIAS_RES_SHIFT = 3,  // out = acc + bias + res; partial sums of D(f_out, f_in) per row, with
                              // f_out = acc + bias (or out, if `post`) and f_in = res (or `ref`, if given)
+    // bf16 only: the A operand is the raw input x of a LayerNorm whose scale is folded into the
+    // packed weights, acc = x (gamma * W);  LN(x) W + b = rstd * (acc - mean * colsum) + bias'
+    // with per-row (mean, rstd) and per-column colsum = sum_k gamma_k W_kn, bias' = beta W + b.
+    EPI_LN_BIAS = 4,         // out = rstd * (acc - mean * colsum) + bias'
+    EPI_LN_BIAS_GELU = 5     // out = gelu(rstd * (acc - mean * colsum) + bias')
+};
+
+// Per-row and per-column vectors of the EPI_LN_* epilogues (all fp32, device memory).
+struct GemmLnFold {
+    const float* stats;   // [M][2]  (mean, rstd)
+    const float* colsum;  // [N]
+    const float* bias;    // [N]
 };
 
 // Number of per-row partial slots the SHIFT epilogue writes for an output width N.
@@ -108,9 +124,17 @@ constexpr int kShiftLanes = 3;  // floats per slot (L2/L1 use the first, cosine 
 hipError_t launch_gemm(rs_dtype dt, GemmEpilogue epi, rs_dist dist, const void* a, const void* w,
                        const void* bias, const void* res, void* out, float* partials,
                        const void* ref, bool post, int64_t M, int N, int K, hipStream_t s);
+// bf16 GEMM behind a LayerNorm (EPI_LN_BIAS / EPI_LN_BIAS_GELU).
+hipError_t launch_gemm_ln(GemmEpilogue epi, const void* x, const void* w_folded, GemmLnFold ln, void* out,
+                          int64_t M, int N, int K, hipStream_t s);
 
-// bf16 [K, N] row-major -> [N, K] row-major.
-hipError_t launch_pack_transpose(const void* w, void* wt, int K, int N, hipStream_t s);
+// bf16 [K, N] row-major -> [N, K] row-major; with `gamma` ([K] bf16) row k is scaled by gamma[k]
+// (product rounded to bf16).
+hipError_t launch_pack_transpose(const void* w, const void* gamma, void* wt, int K, int N, hipStream_t s);
+// colsum[n] = sum_k bf16(gamma[k] * w[k][n]),  bias_out[n] = sum_k beta[k] * w[k][n] + bias[n]
+// (w [K, N] bf16; gamma, beta, bias bf16 or null = 1, 0, 0; outputs fp32).
+hipError_t launch_pack_ln_fold(const void* w, const void* gamma, const void* beta, const void* bias,
+                               float* colsum, float* bias_out, int K, int N, hipStream_t s);
 
 hipError_t launch_attention(rs_dtype dt, const void* q, const void* k, const void* v, void* o,
                             int B, int H, int N, int64_t sb, int64_t sn, int64_t sh,

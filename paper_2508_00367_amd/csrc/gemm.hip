@@ -79,8 +79,8 @@ template <int BM, int BN, int BK, int NSTAGE, int WGM, int WGN, int EPI, int DIS
 __global__ __launch_bounds__(WGM* WGN * 64, WGM* WGN / 4) void gemm_bf16_kernel(
     const bf16raw* __restrict__ a, const bf16raw* __restrict__ wt, const bf16raw* __restrict__ bias,
     const bf16raw* __restrict__ res, bf16raw* __restrict__ out, float* __restrict__ partials,
-    const bf16raw* __restrict__ ref, int post, int M, int N, int K, int tiles_m, int tiles_n, int slots,
-    int gm) {
+    const bf16raw* __restrict__ ref, int post, GemmLnFold ln, int M, int N, int K, int tiles_m,
+    int tiles_n, int slots, int gm) {
     constexpr int NW = WGM * WGN;               // waves: WGM along tokens x WGN along features
     constexpr int WM = BM / WGM, WN = BN / WGN; // wave tile
     constexpr int TM = WM / 32, TN = WN / 32;   // MFMA tiles per wave
@@ -152,6 +152,18 @@ __global__ __launch_bounds__(WGM* WGN * 64, WGM* WGN / 4) void gemm_bf16_kernel(
         voff_e = voff_o = ((wave * RPI + ld_r) * K + ((ld_p ^ ((ld_r >> 2) & 3)) << 3)) * 2;
     }
     const int pass_bytes = NW * RPI * K * 2;
+
+    // LayerNorm-folded epilogues: fetch the (mean, rstd) of this wave's WM rows now (lane l: rows
+    // l, l + 64, ...), so that the loads are long done when the epilogue wants them
+    constexpr bool LN_EPI = EPI == EPI_LN_BIAS || EPI == EPI_LN_BIAS_GELU;
+    float2 row_st[LN_EPI ? WM / 64 : 1];
+    if (LN_EPI) {
+#pragma unroll
+        for (int h = 0; h < WM / 64; ++h) {
+            const int m = m0 + wm * WM + h * 64 + lane;
+            row_st[h] = m < M ? reinterpret_cast<const float2*>(ln.stats)[m] : make_float2(0.f, 0.f);
+        }
+    }
 
     f32x16 acc[TN][TM];
 #pragma unroll
@@ -259,16 +271,29 @@ __global__ __launch_bounds__(WGM* WGN * 64, WGM* WGN / 4) void gemm_bf16_kernel(
         constexpr int PITCH = WN * 4 + 16;         // bytes per staged row
         constexpr int LPR = WN / 8;                // lanes per row on the way out (16 for WN = 128)
         constexpr int RPS = 64 / LPR;              // rows per step
-        static_assert(32 * PITCH <= 2 * STAGE / NW, "epilogue staging does not fit");
+        static_assert(32 * PITCH + WM * 8 <= 2 * STAGE / NW, "epilogue staging does not fit");
         unsigned char* ep = ((wave & 1) ? stage1 : stage0) + (wave >> 1) * (2 * STAGE / NW);
+        float2* ep_st = reinterpret_cast<float2*>(ep + 32 * PITCH);  // the wave's row statistics
+        if (LN_EPI) {
+#pragma unroll
+            for (int h = 0; h < WM / 64; ++h) ep_st[h * 64 + lane] = row_st[h];
+        }
         const int oc = (lane % LPR) * 8;           // this lane's first feature inside the wave tile
         const int orow = lane / LPR;
         const int n = n0 + wn * WN + oc;
         const bool n_ok = n < N;                   // N % 8 == 0
-        float bv[8];
+        constexpr bool LN = EPI == EPI_LN_BIAS || EPI == EPI_LN_BIAS_GELU;
+        float bv[8], cs[8];
 #pragma unroll
-        for (int e = 0; e < 8; ++e) bv[e] = 0.f;
-        if (bias && n_ok) Elem<bf16raw>::load8(bias + n, bv);
+        for (int e = 0; e < 8; ++e) { bv[e] = 0.f; cs[e] = 0.f; }
+        if (LN) {
+            if (n_ok) {
+                Elem<float>::load8(ln.bias + n, bv);
+                Elem<float>::load8(ln.colsum + n, cs);
+            }
+        } else if (bias && n_ok) {
+            Elem<bf16raw>::load8(bias + n, bv);
+        }
 #pragma unroll
         for (int j = 0; j < TM; ++j) {
 #pragma unroll
@@ -287,10 +312,20 @@ __global__ __launch_bounds__(WGM* WGN * 64, WGM* WGN / 4) void gemm_bf16_kernel(
                 {
                     const f32x4 lo = *reinterpret_cast<const f32x4*>(ep + r * PITCH + oc * 4);
                     const f32x4 hi = *reinterpret_cast<const f32x4*>(ep + r * PITCH + oc * 4 + 16);
+                    if (LN) {
+                        const float2 st = ep_st[j * 32 + r];
+                        const float nm = -st.x;
 #pragma unroll
-                    for (int e = 0; e < 4; ++e) { v[e] = lo[e] + bv[e]; v[4 + e] = hi[e] + bv[4 + e]; }
+                        for (int e = 0; e < 4; ++e) {
+                            v[e] = fmaf(st.y, fmaf(nm, cs[e], lo[e]), bv[e]);
+                            v[4 + e] = fmaf(st.y, fmaf(nm, cs[4 + e], hi[e]), bv[4 + e]);
+                        }
+                    } else {
+#pragma unroll
+                        for (int e = 0; e < 4; ++e) { v[e] = lo[e] + bv[e]; v[4 + e] = hi[e] + bv[4 + e]; }
+                    }
                 }
-                if (EPI == EPI_BIAS_GELU) {
+                if (EPI == EPI_BIAS_GELU || EPI == EPI_LN_BIAS_GELU) {
 #pragma unroll
                     for (int e = 0; e < 8; ++e) v[e] = gelu_sp(v[e]);
                 }
@@ -350,8 +385,8 @@ struct GemmCfg {
 
 template <int EPI, int DIST>
 static hipError_t launch_bf16(const void* a, const void* wt, const void* bias, const void* res,
-                              void* out, float* partials, const void* ref, bool post, int64_t M, int N,
-                              int K, hipStream_t s) {
+                              void* out, float* partials, const void* ref, bool post, GemmLnFold ln,
+                              int64_t M, int N, int K, hipStream_t s) {
     using C = GemmCfg;
     const int tiles_m = (int)((M + C::BM - 1) / C::BM), tiles_n = (N + C::BN - 1) / C::BN;
     const int slots = (tiles_n * C::BN) / C::WN;
@@ -359,7 +394,7 @@ static hipError_t launch_bf16(const void* a, const void* wt, const void* bias, c
     hipLaunchKernelGGL((gemm_bf16_kernel<C::BM, C::BN, C::BK, C::NSTAGE, C::WGM, C::WGN, EPI, DIST>),
                        dim3(tiles_m * tiles_n), dim3(C::WGM * C::WGN * 64), 0, s, (const bf16raw*)a,
                        (const bf16raw*)wt, (const bf16raw*)bias, (const bf16raw*)res, (bf16raw*)out, partials,
-                       (const bf16raw*)ref, post ? 1 : 0, (int)M, N, K, tiles_m, tiles_n, slots, gm);
+                       (const bf16raw*)ref, post ? 1 : 0, ln, (int)M, N, K, tiles_m, tiles_n, slots, gm);
     return hipGetLastError();
 }
 
@@ -490,7 +525,7 @@ static hipError_t launch_any(rs_dtype dt, const void* a, const void* w, const vo
                              const void* res, void* out, float* partials, const void* ref, bool post,
                              int64_t M, int N, int K, hipStream_t s) {
     return dt == RS_F32 ? launch_f32<EPI, DIST>(a, w, bias, res, out, partials, ref, post, M, N, K, s)
-                        : launch_bf16<EPI, DIST>(a, w, bias, res, out, partials, ref, post, M, N, K, s);
+                        : launch_bf16<EPI, DIST>(a, w, bias, res, out, partials, ref, post, GemmLnFold{}, M, N, K, s);
 }
 
 hipError_t launch_gemm(rs_dtype dt, GemmEpilogue epi, rs_dist dist, const void* a, const void* w,
@@ -509,18 +544,34 @@ hipError_t launch_gemm(rs_dtype dt, GemmEpilogue epi, rs_dist dist, const void* 
     return hipErrorInvalidValue;
 }
 
+hipError_t launch_gemm_ln(GemmEpilogue epi, const void* x, const void* w_folded, GemmLnFold ln, void* out,
+                          int64_t M, int N, int K, hipStream_t s) {
+    if (M == 0) return hipSuccess;
+    if (epi == EPI_LN_BIAS)
+        return launch_bf16<EPI_LN_BIAS, 0>(x, w_folded, nullptr, nullptr, out, nullptr, nullptr, false, ln, M, N, K, s);
+    if (epi == EPI_LN_BIAS_GELU)
+        return launch_bf16<EPI_LN_BIAS_GELU, 0>(x, w_folded, nullptr, nullptr, out, nullptr, nullptr, false, ln, M, N, K, s);
+    return hipErrorInvalidValue;
+}
+
 // ---------------------------------------------------------------------------
-// Weight re-layout for the bf16 path: [K, N] row-major -> [N, K] row-major.
-// 64 x 64 tiles through LDS, coalesced on both sides.
+// Weight re-layout for the bf16 path: [K, N] row-major -> [N, K] row-major, optionally with
+// row k scaled by gamma[k] (a LayerNorm scale folded into the weights; the product is rounded
+// to bf16).  64 x 64 tiles through LDS, coalesced on both sides.
 // ---------------------------------------------------------------------------
+__device__ __forceinline__ bf16raw fold_gamma(bf16raw w, const bf16raw* gamma, int k) {
+    return gamma ? f2bf(bf2f(gamma[k]) * bf2f(w)) : w;
+}
+
 __global__ __launch_bounds__(256) void transpose_bf16_kernel(const bf16raw* __restrict__ w,
+                                                             const bf16raw* __restrict__ gamma,
                                                              bf16raw* __restrict__ wt, int K, int N) {
     __shared__ bf16raw tile[64][66];
     const int k0 = blockIdx.y * 64, n0 = blockIdx.x * 64;
     const int tx = threadIdx.x & 63, ty = threadIdx.x >> 6;
     for (int r = ty; r < 64; r += 4) {
         const int k = k0 + r, n = n0 + tx;
-        tile[r][tx] = (k < K && n < N) ? w[(int64_t)k * N + n] : (bf16raw)0;
+        tile[r][tx] = (k < K && n < N) ? fold_gamma(w[(int64_t)k * N + n], gamma, k) : (bf16raw)0;
     }
     __syncthreads();
     for (int r = ty; r < 64; r += 4) {
@@ -529,9 +580,48 @@ __global__ __launch_bounds__(256) void transpose_bf16_kernel(const bf16raw* __re
     }
 }
 
-hipError_t launch_pack_transpose(const void* w, void* wt, int K, int N, hipStream_t s) {
+hipError_t launch_pack_transpose(const void* w, const void* gamma, void* wt, int K, int N, hipStream_t s) {
     dim3 grid((N + 63) / 64, (K + 63) / 64);
-    hipLaunchKernelGGL(transpose_bf16_kernel, grid, dim3(256), 0, s, (const bf16raw*)w, (bf16raw*)wt, K, N);
+    hipLaunchKernelGGL(transpose_bf16_kernel, grid, dim3(256), 0, s, (const bf16raw*)w, (const bf16raw*)gamma,
+                       (bf16raw*)wt, K, N);
+    return hipGetLastError();
+}
+
+// Column vectors of a LayerNorm folded into the linear layer behind it:
+//   colsum[n] = sum_k bf16(gamma_k w_kn)   -- over exactly the values transpose_bf16_kernel stores,
+//                                             so that mean * colsum cancels the mean's share of acc
+//   bias_out[n] = sum_k beta_k w_kn + bias[n]
+// One thread per column, 4 row groups per workgroup reduced through LDS; fp64 sums (one-off work).
+__global__ __launch_bounds__(256) void ln_fold_kernel(const bf16raw* __restrict__ w, const bf16raw* __restrict__ gamma,
+                                                      const bf16raw* __restrict__ beta, const bf16raw* __restrict__ bias,
+                                                      float* __restrict__ colsum, float* __restrict__ bias_out,
+                                                      int K, int N) {
+    __shared__ double s_cs[4][64], s_bb[4][64];
+    const int tx = threadIdx.x & 63, ty = threadIdx.x >> 6;
+    const int n = blockIdx.x * 64 + tx;
+    double cs = 0.0, bb = 0.0;
+    if (n < N)
+        for (int k = ty; k < K; k += 4) {
+            const bf16raw wv = w[(int64_t)k * N + n];
+            cs += (double)bf2f(fold_gamma(wv, gamma, k));
+            if (beta) bb += (double)bf2f(beta[k]) * (double)bf2f(wv);
+        }
+    s_cs[ty][tx] = cs;
+    s_bb[ty][tx] = bb;
+    __syncthreads();
+    if (ty == 0 && n < N) {
+        cs = ((s_cs[0][tx] + s_cs[1][tx]) + s_cs[2][tx]) + s_cs[3][tx];
+        bb = ((s_bb[0][tx] + s_bb[1][tx]) + s_bb[2][tx]) + s_bb[3][tx];
+        if (bias) bb += (double)bf2f(bias[n]);
+        colsum[n] = (float)cs;
+        bias_out[n] = (float)bb;
+    }
+}
+
+hipError_t launch_pack_ln_fold(const void* w, const void* gamma, const void* beta, const void* bias,
+                               float* colsum, float* bias_out, int K, int N, hipStream_t s) {
+    hipLaunchKernelGGL(ln_fold_kernel, dim3((N + 63) / 64), dim3(256), 0, s, (const bf16raw*)w,
+                       (const bf16raw*)gamma, (const bf16raw*)beta, (const bf16raw*)bias, colsum, bias_out, K, N);
     return hipGetLastError();
 }
 

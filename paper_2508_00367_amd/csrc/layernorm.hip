@@ -62,6 +62,60 @@ __global__ __launch_bounds__(256) void layernorm_kernel(const T* __restrict__ x,
     }
 }
 
+// Row statistics only: stats[row] = (mean, 1 / sqrt(var + eps)), same two-pass arithmetic as above.
+// The bf16 block feeds them to the GEMM that follows the LayerNorm, which applies the
+// normalisation in its epilogue (the normalised rows are never written).
+template <typename T, int MAXC>
+__global__ __launch_bounds__(256) void rowstats_kernel(const T* __restrict__ x, float2* __restrict__ stats,
+                                                       int64_t M, int D, float eps) {
+    const int lane = threadIdx.x & 63;
+    const int64_t row = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
+    if (row >= M) return;
+    const int nchunk = D >> 3;
+    const T* xr = x + row * D;
+    float v[MAXC][8];
+    float sum = 0.f;
+#pragma unroll
+    for (int c = 0; c < MAXC; ++c) {
+        const int ch = lane + c * 64;
+        if (ch < nchunk) {
+            Elem<T>::load8(xr + ch * 8, v[c]);
+#pragma unroll
+            for (int i = 0; i < 8; ++i) sum += v[c][i];
+        }
+    }
+    const float mean = wave_sum(sum) / (float)D;
+    float sq = 0.f;
+#pragma unroll
+    for (int c = 0; c < MAXC; ++c) {
+        const int ch = lane + c * 64;
+        if (ch < nchunk) {
+#pragma unroll
+            for (int i = 0; i < 8; ++i) {
+                const float d = v[c][i] - mean;
+                sq += d * d;
+            }
+        }
+    }
+    const float inv = rsqrtf(wave_sum(sq) / (float)D + eps);
+    if (lane == 0) stats[row] = make_float2(mean, inv);
+}
+
+hipError_t launch_rowstats(rs_dtype dt, const void* x, float* stats, int64_t M, int D, float eps,
+                           hipStream_t s) {
+    if (M == 0) return hipSuccess;
+    dim3 grid((unsigned)((M + 3) / 4)), block(256);
+    float2* st = reinterpret_cast<float2*>(stats);
+    if (dt == RS_F32) {
+        if (D <= 2 * 512) hipLaunchKernelGGL((rowstats_kernel<float, 2>), grid, block, 0, s, (const float*)x, st, M, D, eps);
+        else hipLaunchKernelGGL((rowstats_kernel<float, 8>), grid, block, 0, s, (const float*)x, st, M, D, eps);
+    } else {
+        if (D <= 2 * 512) hipLaunchKernelGGL((rowstats_kernel<bf16raw, 2>), grid, block, 0, s, (const bf16raw*)x, st, M, D, eps);
+        else hipLaunchKernelGGL((rowstats_kernel<bf16raw, 8>), grid, block, 0, s, (const bf16raw*)x, st, M, D, eps);
+    }
+    return hipGetLastError();
+}
+
 template <typename T>
 static hipError_t launch_ln_t(const void* x, const void* g, const void* b, void* out, int64_t M,
                               int D, float eps, hipStream_t s) {

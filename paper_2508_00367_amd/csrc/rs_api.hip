@@ -94,14 +94,35 @@ static hipError_t timed(int cls, hipStream_t s, F launch) {
 
 // ---- workspace layout of rs_block_fwd ---------------------------------------
 struct BlockLayout {
-    size_t packed, u, qkv, att, x1, hid, partials, scores, total;
+    size_t packed, u, qkv, att, x1, hid, partials, scores, stats, total;
     int slots;
 };
 
-static size_t packed_bytes(const rs_block_cfg* c) {
-    if (c->dtype != RS_BF16) return 0;
+// Packed bf16 weights: the four matrices as [out, in] (LayerNorm scales folded into W_qkv and
+// W_fc1), then the fp32 column vectors of the two folded LayerNorms.
+struct PackedLayout {
+    size_t w_qkv, w_proj, w_fc1, w_fc2, cs_qkv, b_qkv, cs_fc1, b_fc1, total;
+};
+
+static PackedLayout packed_layout(const rs_block_cfg* c) {
+    PackedLayout P;
     const size_t D = c->D, Dm = c->Dm;
-    return align_up((3 * D * D + D * D + 2 * D * Dm) * 2, 256);
+    size_t off = 0;
+    auto take = [&](size_t bytes) { size_t o = off; off += align_up(bytes, 256); return o; };
+    P.w_qkv = take(3 * D * D * 2);
+    P.w_proj = take(D * D * 2);
+    P.w_fc1 = take(D * Dm * 2);
+    P.w_fc2 = take(D * Dm * 2);
+    P.cs_qkv = take(3 * D * sizeof(float));
+    P.b_qkv = take(3 * D * sizeof(float));
+    P.cs_fc1 = take(Dm * sizeof(float));
+    P.b_fc1 = take(Dm * sizeof(float));
+    P.total = off;
+    return P;
+}
+
+static size_t packed_bytes(const rs_block_cfg* c) {
+    return c->dtype == RS_BF16 ? packed_layout(c).total : 0;
 }
 
 static BlockLayout block_layout(const rs_block_cfg* c) {
@@ -119,6 +140,7 @@ static BlockLayout block_layout(const rs_block_cfg* c) {
     L.hid = take(M * Dm * e);
     L.partials = take(M * (size_t)L.slots * kShiftLanes * sizeof(float));
     L.scores = take(M * sizeof(float));
+    L.stats = take(M * 2 * sizeof(float));
     L.total = off;
     return L;
 }
@@ -152,7 +174,7 @@ extern "C" {
 
 const char* rs_last_error(void) { return g_err; }
 
-int32_t rs_version(void) { return 100; }
+int32_t rs_version(void) { return 101; }
 
 rs_status rs_profile_enable(int32_t enable) {
     std::lock_guard<std::mutex> lk(g_prof.mu);
@@ -249,15 +271,17 @@ size_t rs_packed_weights_size(const rs_block_cfg* cfg) {
 }
 
 static rs_status pack_into(const rs_block_cfg* c, const rs_block_weights* w, void* dst, hipStream_t st) {
-    const size_t D = c->D, Dm = c->Dm;
+    const PackedLayout P = packed_layout(c);
     char* p = (char*)dst;
-    RS_LAUNCH_K(K_PACK, st, launch_pack_transpose(w->w_qkv, p, c->D, 3 * c->D, st));
-    p += 3 * D * D * 2;
-    RS_LAUNCH_K(K_PACK, st, launch_pack_transpose(w->w_proj, p, c->D, c->D, st));
-    p += D * D * 2;
-    RS_LAUNCH_K(K_PACK, st, launch_pack_transpose(w->w_fc1, p, c->D, c->Dm, st));
-    p += D * Dm * 2;
-    RS_LAUNCH_K(K_PACK, st, launch_pack_transpose(w->w_fc2, p, c->Dm, c->D, st));
+    const int D = c->D, Dm = c->Dm;
+    RS_LAUNCH_K(K_PACK, st, launch_pack_transpose(w->w_qkv, w->ln1_g, p + P.w_qkv, D, 3 * D, st));
+    RS_LAUNCH_K(K_PACK, st, launch_pack_transpose(w->w_proj, nullptr, p + P.w_proj, D, D, st));
+    RS_LAUNCH_K(K_PACK, st, launch_pack_transpose(w->w_fc1, w->ln2_g, p + P.w_fc1, D, Dm, st));
+    RS_LAUNCH_K(K_PACK, st, launch_pack_transpose(w->w_fc2, nullptr, p + P.w_fc2, Dm, D, st));
+    RS_LAUNCH_K(K_PACK, st, launch_pack_ln_fold(w->w_qkv, w->ln1_g, w->ln1_b, w->b_qkv, (float*)(p + P.cs_qkv),
+                                              (float*)(p + P.b_qkv), D, 3 * D, st));
+    RS_LAUNCH_K(K_PACK, st, launch_pack_ln_fold(w->w_fc1, w->ln2_g, w->ln2_b, w->b_fc1, (float*)(p + P.cs_fc1),
+                                              (float*)(p + P.b_fc1), D, Dm, st));
     return RS_OK;
 }
 
@@ -291,7 +315,7 @@ rs_status rs_pack_linear(const void* w, void* wt, int32_t K, int32_t N, rs_dtype
     if (dtype == RS_F32) return RS_OK;  // the fp32 path reads the caller's layout
     RS_REQUIRE(w && wt && w != wt, RS_ERR_INVALID_ARG, "w and wt must be distinct non-NULL buffers");
     hipStream_t st = (hipStream_t)hip_stream;
-    RS_LAUNCH_K(K_PACK, st, launch_pack_transpose(w, wt, K, N, st));
+    RS_LAUNCH_K(K_PACK, st, launch_pack_transpose(w, nullptr, wt, K, N, st));
     return RS_OK;
 }
 
@@ -358,6 +382,7 @@ rs_status rs_block_fwd(const rs_block_cfg* cfg, const rs_block_weights* w, const
 
     // weights as the GEMMs read them
     const void *wq = w->w_qkv, *wp = w->w_proj, *w1 = w->w_fc1, *w2 = w->w_fc2;
+    GemmLnFold ln1{}, ln2{};
     if (dt == RS_BF16) {
         const char* pk = (const char*)w->packed;
         if (!pk) {
@@ -365,17 +390,27 @@ rs_status rs_block_fwd(const rs_block_cfg* cfg, const rs_block_weights* w, const
             if (st != RS_OK) return st;
             pk = ws + L.packed;
         }
-        const size_t Ds = D, Dms = Dm;
-        wq = pk;
-        wp = pk + 3 * Ds * Ds * 2;
-        w1 = pk + 4 * Ds * Ds * 2;
-        w2 = pk + (4 * Ds * Ds + Ds * Dms) * 2;
+        const PackedLayout P = packed_layout(cfg);
+        wq = pk + P.w_qkv;
+        wp = pk + P.w_proj;
+        w1 = pk + P.w_fc1;
+        w2 = pk + P.w_fc2;
+        float* stats = (float*)(ws + L.stats);
+        ln1 = GemmLnFold{stats, (const float*)(pk + P.cs_qkv), (const float*)(pk + P.b_qkv)};
+        ln2 = GemmLnFold{stats, (const float*)(pk + P.cs_fc1), (const float*)(pk + P.b_fc1)};
     }
     const float scale = c.attn_scale > 0.f ? c.attn_scale : 0.125f;  // 1/sqrt(64)
 
     // x1 = SA(LN(x)) + x                                                     Eq. (5)
-    RS_LAUNCH_K(K_LN, s, launch_layernorm(dt, x, w->ln1_g, w->ln1_b, u, M, D, c.ln_eps, s));
-    RS_LAUNCH_K(K_GEMM_QKV, s, launch_gemm(dt, EPI_BIAS, RS_DIST_L2, u, wq, w->b_qkv, nullptr, qkv, nullptr, nullptr, false, M, 3 * D, D, s));
+    // bf16: the LayerNorm in front of a GEMM is a pass for the row statistics only; the GEMM reads
+    // the raw rows against weights that carry the LayerNorm scale and normalises in its epilogue
+    if (dt == RS_BF16) {
+        RS_LAUNCH_K(K_LN, s, launch_rowstats(dt, x, (float*)(ws + L.stats), M, D, c.ln_eps, s));
+        RS_LAUNCH_K(K_GEMM_QKV, s, launch_gemm_ln(EPI_LN_BIAS, x, wq, ln1, qkv, M, 3 * D, D, s));
+    } else {
+        RS_LAUNCH_K(K_LN, s, launch_layernorm(dt, x, w->ln1_g, w->ln1_b, u, M, D, c.ln_eps, s));
+        RS_LAUNCH_K(K_GEMM_QKV, s, launch_gemm(dt, EPI_BIAS, RS_DIST_L2, u, wq, w->b_qkv, nullptr, qkv, nullptr, nullptr, false, M, 3 * D, D, s));
+    }
     {
         const size_t e = elem_size(dt);
         const char* qp = (const char*)qkv;
@@ -387,8 +422,15 @@ rs_status rs_block_fwd(const rs_block_cfg* cfg, const rs_block_weights* w, const
     RS_LAUNCH_K(K_GEMM_PROJ, s, launch_gemm(dt, attn_scores ? EPI_BIAS_RES_SHIFT : EPI_BIAS_RES, c.dist, att, wp, w->b_proj, x, x1,
                             partials, nullptr, false, M, D, D, s));
     // xhat = MLP(LN(x1)) + x1, with the shift partial sums of D(MLP(LN(x1)), x1)   Eq. (6), Eq. (4)
-    RS_LAUNCH_K(K_LN, s, launch_layernorm(dt, x1, w->ln2_g, w->ln2_b, u, M, D, c.ln_eps, s));
-    RS_LAUNCH_K(K_GEMM_FC1, s, launch_gemm(dt, EPI_BIAS_GELU, RS_DIST_L2, u, w1, w->b_fc1, nullptr, hid, nullptr, nullptr, false, M, Dm, D, s));
+    const bool need_v = want_scores && c.op == RS_SHIFT_MLP_NORMED;  // LN(x1) itself is an operand of the score
+    if (dt == RS_BF16) {
+        RS_LAUNCH_K(K_LN, s, launch_rowstats(dt, x1, (float*)(ws + L.stats), M, D, c.ln_eps, s));
+        if (need_v) RS_LAUNCH_K(K_LN, s, launch_layernorm(dt, x1, w->ln2_g, w->ln2_b, u, M, D, c.ln_eps, s));
+        RS_LAUNCH_K(K_GEMM_FC1, s, launch_gemm_ln(EPI_LN_BIAS_GELU, x1, w1, ln2, hid, M, Dm, D, s));
+    } else {
+        RS_LAUNCH_K(K_LN, s, launch_layernorm(dt, x1, w->ln2_g, w->ln2_b, u, M, D, c.ln_eps, s));
+        RS_LAUNCH_K(K_GEMM_FC1, s, launch_gemm(dt, EPI_BIAS_GELU, RS_DIST_L2, u, w1, w->b_fc1, nullptr, hid, nullptr, nullptr, false, M, Dm, D, s));
+    }
     void* xhat = prune ? att : y;  // without pruning the block output goes straight to y
     // every other choice of (f_out, f_in) comes out of fc2's epilogue: f_out is the MLP output or
     // (post) xhat, f_in the residual operand x1 or another tensor still in memory (x, LN(x1))

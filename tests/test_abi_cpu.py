@@ -134,7 +134,10 @@ def test_shift_topk_rejects_bad_arguments():
 
 def test_pack_weights_validation():
     cfg = _cfg()
-    assert rs.rs_packed_weights_size(cfg) == (3 * 128 * 128 + 128 * 128 + 2 * 128 * 256) * 2
+    # four bf16 matrices plus, for the two LayerNorms folded into W_qkv and W_fc1, an fp32 column-sum
+    # and bias vector each (every piece a multiple of 256 bytes here)
+    assert rs.rs_packed_weights_size(cfg) == (3 * 128 * 128 + 128 * 128 + 2 * 128 * 256) * 2 + \
+        2 * (3 * 128 + 256) * 4
     L = rs.lib()
     w = _weights()
     assert L.rs_pack_weights(ctypes.byref(cfg), ctypes.byref(w), None, None) == rs.RS_ERR_INVALID_ARG
