@@ -165,6 +165,24 @@ __global__ __launch_bounds__(WGM* WGN * 64, WGM* WGN / 4) void gemm_bf16_kernel(
         }
     }
 
+    // Likewise the per-column epilogue vectors of the lane's 8 output features (on the way out a
+    // row of the wave tile is covered by WN / 8 lanes, 8 consecutive features each).
+    const int ep_oc = (lane % (WN / 8)) * 8;
+    const int ep_n = n0 + wn * WN + ep_oc;
+    const bool ep_n_ok = ep_n < N;  // N % 8 == 0
+    uint4 bias_raw = make_uint4(0u, 0u, 0u, 0u);
+    float ln_bv[LN_EPI ? 8 : 1], ln_cs[LN_EPI ? 8 : 1];
+    if (LN_EPI) {
+#pragma unroll
+        for (int e = 0; e < 8; ++e) { ln_bv[e] = 0.f; ln_cs[e] = 0.f; }
+        if (ep_n_ok) {
+            Elem<float>::load8(ln.bias + ep_n, reinterpret_cast<float(&)[8]>(ln_bv));
+            Elem<float>::load8(ln.colsum + ep_n, reinterpret_cast<float(&)[8]>(ln_cs));
+        }
+    } else if (bias && ep_n_ok) {
+        bias_raw = *reinterpret_cast<const uint4*>(bias + ep_n);
+    }
+
     f32x16 acc[TN][TM];
 #pragma unroll
     for (int i = 0; i < TN; ++i)
@@ -278,24 +296,38 @@ __global__ __launch_bounds__(WGM* WGN * 64, WGM* WGN / 4) void gemm_bf16_kernel(
 #pragma unroll
             for (int h = 0; h < WM / 64; ++h) ep_st[h * 64 + lane] = row_st[h];
         }
-        const int oc = (lane % LPR) * 8;           // this lane's first feature inside the wave tile
+        const int oc = ep_oc;                      // this lane's first feature inside the wave tile
         const int orow = lane / LPR;
-        const int n = n0 + wn * WN + oc;
-        const bool n_ok = n < N;                   // N % 8 == 0
-        constexpr bool LN = EPI == EPI_LN_BIAS || EPI == EPI_LN_BIAS_GELU;
+        const int n = ep_n;
+        const bool n_ok = ep_n_ok;
+        constexpr bool LN = LN_EPI;
         float bv[8], cs[8];
 #pragma unroll
-        for (int e = 0; e < 8; ++e) { bv[e] = 0.f; cs[e] = 0.f; }
-        if (LN) {
-            if (n_ok) {
-                Elem<float>::load8(ln.bias + n, bv);
-                Elem<float>::load8(ln.colsum + n, cs);
+        for (int e = 0; e < 8; ++e) {
+            bv[e] = LN ? ln_bv[LN ? e : 0] : 0.f;
+            cs[e] = LN ? ln_cs[LN ? e : 0] : 0.f;
+        }
+        if (!LN) {
+            const uint32_t w4[4] = {bias_raw.x, bias_raw.y, bias_raw.z, bias_raw.w};
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                bv[2 * e] = __uint_as_float(w4[e] << 16);
+                bv[2 * e + 1] = __uint_as_float(w4[e] & 0xffff0000u);
             }
-        } else if (bias && n_ok) {
-            Elem<bf16raw>::load8(bias + n, bv);
         }
 #pragma unroll
         for (int j = 0; j < TM; ++j) {
+            // the residual rows of this 32-row group: issued before the staging round trip
+            constexpr bool RES = EPI == EPI_BIAS_RES || EPI == EPI_BIAS_RES_SHIFT;
+            uint4 res_raw[RES ? 32 / RPS : 1];
+            if (RES) {
+#pragma unroll
+                for (int st = 0; st < 32 / RPS; ++st) {
+                    const int m = m0 + wm * WM + j * 32 + st * RPS + orow;
+                    res_raw[st] = (m < M && n_ok) ? *reinterpret_cast<const uint4*>(res + (int64_t)m * N + n)
+                                                  : make_uint4(0u, 0u, 0u, 0u);
+                }
+            }
 #pragma unroll
             for (int i = 0; i < TN; ++i)
 #pragma unroll
@@ -332,9 +364,15 @@ __global__ __launch_bounds__(WGM* WGN * 64, WGM* WGN / 4) void gemm_bf16_kernel(
                 float p0 = 0.f, p1 = 0.f, p2 = 0.f;
                 if (EPI == EPI_BIAS_RES || EPI == EPI_BIAS_RES_SHIFT) {
                     float rr[8];
+                    {
+                        const uint4 q4 = res_raw[RES ? st : 0];
+                        const uint32_t w4[4] = {q4.x, q4.y, q4.z, q4.w};
 #pragma unroll
-                    for (int e = 0; e < 8; ++e) rr[e] = 0.f;
-                    if (ok) Elem<bf16raw>::load8(res + (int64_t)m * N + n, rr);
+                        for (int e = 0; e < 4; ++e) {
+                            rr[2 * e] = __uint_as_float(w4[e] << 16);
+                            rr[2 * e + 1] = __uint_as_float(w4[e] & 0xffff0000u);
+                        }
+                    }
                     if (EPI == EPI_BIAS_RES_SHIFT && ok) {
                         // D(f_out, f_in): f_out is the branch output, or (post) the residual stream
                         // after the add; f_in is the residual operand, or `ref` when one is given
