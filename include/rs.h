@@ -80,8 +80,12 @@ typedef struct {
     const void *w_fc1, *b_fc1;     /* [D, Dm], [Dm]       */
     const void *w_fc2, *b_fc2;     /* [Dm, D], [D]        */
     /* Optional: buffer of rs_packed_weights_size() bytes filled by rs_pack_weights()
-     * from the four matrices above.  NULL = the library re-packs into the workspace
-     * on every rs_block_fwd call (RS_BF16 only; RS_F32 needs no packing). */
+     * from the tensors above: the four matrices as [out, in], with the LayerNorm scales
+     * folded into W_qkv and W_fc1 (rounded to bf16), plus the fp32 column sums and the
+     * biases beta W + b those two GEMMs need to apply the normalisation in their
+     * epilogues.  It depends on every pointer above except b_proj and b_fc2: re-pack when
+     * any of them changes.  NULL = the library re-packs into the workspace on every
+     * rs_block_fwd call (RS_BF16 only; RS_F32 needs no packing). */
     const void *packed;
 } rs_block_weights;
 

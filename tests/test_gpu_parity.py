@@ -230,6 +230,22 @@ def test_block_operation_choice(op, dist, dtype):
     _check_block(x, w, 3, 1, 120, dtype, dist=dist, op=op)
 
 
+@pytest.mark.parametrize("pack", [False, True])
+def test_block_offset_rows_and_outlier_channels(pack):
+    """Rows far from zero mean (offset 6 standard deviations) with two channels 30 times larger
+    than the rest and affine LayerNorm parameters: the bf16 path applies the LayerNorm inside
+    the GEMM epilogue as rstd * (x W' - mean * colsum) + bias', which must not lose the signal
+    next to the mean's share of the accumulator."""
+    B, N, D, H, Dm = 2, 197, 384, 6, 1536
+    x, w = _block_inputs(8, B, N, D, Dm, "bf16", std=0.05, spread=0.3, affine_ln=True)
+    x = x.astype(np.float64)
+    x[..., 7] *= 30.0
+    x[..., 300] *= 30.0
+    x = host_round(x + 6.0, "bf16")
+    _say("block offset rows, packed", pack)
+    _check_block(x, w, H, 1, 150, "bf16", ln_eps=1e-5, pack=pack)
+
+
 @pytest.mark.parametrize("dtype", ["bf16", "f32"])
 def test_block_without_pruning_and_null_biases(dtype):
     B, N, D, H, Dm = 2, 70, 128, 2, 256
