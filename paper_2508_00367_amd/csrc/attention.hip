@@ -31,78 +31,98 @@ __device__ __forceinline__ int att_swz(int r, int c) { return r * 128 + (((c ^ r
 
 typedef __attribute__((address_space(3))) void* att_lds_ptr;
 
-// One query-row block of 32 rows against one resident tile of 64 keys: S^T = K Q^T, online
-// softmax in registers (one lane = one query row, half of the tile's keys), O^T += V^T P^T.
+// QB query-row blocks of 32 rows against one resident tile of 64 keys: S^T = K Q^T, online
+// softmax in registers (one lane = one query row per block, half of the tile's keys),
+// O^T += V^T P^T.  Every K and V^T fragment read from LDS serves all QB blocks.
 // `sk`: K tile [64 keys][128 B] swizzled; `svt`: V^T tile [64 channels][64 key positions].
-template <bool MASK>
+template <bool MASK, int QB>
 __device__ __forceinline__ void att_tile(const unsigned char* sk, const unsigned char* svt,
-                                         const bf16x8 (&qf)[4], f32x16 (&oacc)[2], float& m_run,
-                                         float& l_run, int key0, int N, float scale_log2e, int l32, int g) {
-    f32x16 sacc[2];
+                                         const bf16x8 (&qf)[QB][4], f32x16 (&oacc)[QB][2],
+                                         float (&m_run)[QB], float (&l_run)[QB], int key0, int N,
+                                         float scale_log2e, int l32, int g) {
+    f32x16 sacc[QB][2];
 #pragma unroll
-    for (int kb2 = 0; kb2 < 2; ++kb2)
-#pragma unroll
-        for (int r = 0; r < 16; ++r) sacc[kb2][r] = 0.f;
-#pragma unroll
-    for (int kk = 0; kk < 4; ++kk)
-#pragma unroll
-        for (int kb2 = 0; kb2 < 2; ++kb2) {  // two independent accumulator chains alternate
-            const bf16x8 kf = *reinterpret_cast<const bf16x8*>(sk + att_swz(kb2 * 32 + l32, kk * 2 + g));
-            sacc[kb2] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[kk], sacc[kb2], 0, 0, 0);
-        }
-    if (MASK) {  // keys past the end (last tile only)
+    for (int qb = 0; qb < QB; ++qb)
 #pragma unroll
         for (int kb2 = 0; kb2 < 2; ++kb2)
 #pragma unroll
-            for (int r = 0; r < 16; ++r) {
-                const int key = key0 + kb2 * 32 + (r >> 2) * 8 + g * 4 + (r & 3);
-                if (key >= N) sacc[kb2][r] = -INFINITY;
-            }
-    }
-    float mx = fmaxf(sacc[0][0], sacc[1][0]);
+            for (int r = 0; r < 16; ++r) sacc[qb][kb2][r] = 0.f;
 #pragma unroll
-    for (int r = 1; r < 16; ++r) mx = fmaxf(fmaxf(mx, sacc[0][r]), sacc[1][r]);
-    mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
-    const float m_new = fmaxf(m_run, mx);  // finite: every tile holds at least one real key
-    const float alpha = __builtin_amdgcn_exp2f((m_run - m_new) * scale_log2e);
-    const float mb = m_new * scale_log2e;
-    m_run = m_new;
+    for (int kk = 0; kk < 4; ++kk)
 #pragma unroll
-    for (int r = 0; r < 16; ++r) {
-        sacc[0][r] = __builtin_amdgcn_exp2f(fmaf(sacc[0][r], scale_log2e, -mb));
-        sacc[1][r] = __builtin_amdgcn_exp2f(fmaf(sacc[1][r], scale_log2e, -mb));
-    }
-    if (__ballot(alpha != 1.0f)) {  // the running maximum moved for some row of this wave
+        for (int kb2 = 0; kb2 < 2; ++kb2) {  // independent accumulator chains alternate
+            const bf16x8 kf = *reinterpret_cast<const bf16x8*>(sk + att_swz(kb2 * 32 + l32, kk * 2 + g));
 #pragma unroll
-        for (int i = 0; i < 2; ++i)
+            for (int qb = 0; qb < QB; ++qb)
+                sacc[qb][kb2] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[qb][kk], sacc[qb][kb2], 0, 0, 0);
+        }
+    float alpha[QB];
 #pragma unroll
-            for (int r = 0; r < 16; ++r) oacc[i][r] *= alpha;
+    for (int qb = 0; qb < QB; ++qb) {
+        if (MASK) {  // keys past the end (last tile only)
+#pragma unroll
+            for (int kb2 = 0; kb2 < 2; ++kb2)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) {
+                    const int key = key0 + kb2 * 32 + (r >> 2) * 8 + g * 4 + (r & 3);
+                    if (key >= N) sacc[qb][kb2][r] = -INFINITY;
+                }
+        }
+        float mx = fmaxf(sacc[qb][0][0], sacc[qb][1][0]);
+#pragma unroll
+        for (int r = 1; r < 16; ++r) mx = fmaxf(fmaxf(mx, sacc[qb][0][r]), sacc[qb][1][r]);
+        mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
+        const float m_new = fmaxf(m_run[qb], mx);  // finite: every tile holds at least one real key
+        alpha[qb] = __builtin_amdgcn_exp2f((m_run[qb] - m_new) * scale_log2e);
+        const float mb = m_new * scale_log2e;
+        m_run[qb] = m_new;
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+            sacc[qb][0][r] = __builtin_amdgcn_exp2f(fmaf(sacc[qb][0][r], scale_log2e, -mb));
+            sacc[qb][1][r] = __builtin_amdgcn_exp2f(fmaf(sacc[qb][1][r], scale_log2e, -mb));
+        }
+        if (__ballot(alpha[qb] != 1.0f)) {  // the running maximum moved for some row of this block
+#pragma unroll
+            for (int i = 0; i < 2; ++i)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) oacc[qb][i][r] *= alpha[qb];
+        }
     }
     // P goes to bf16 once; the row sum is taken over the same rounded values (v_dot2 with ones)
-    float psum = 0.f;
+    float psum[QB];
+#pragma unroll
+    for (int qb = 0; qb < QB; ++qb) psum[qb] = 0.f;
     const bf16x2 ones = __builtin_bit_cast(bf16x2, 0x3f803f80u);
 #pragma unroll
     for (int t = 0; t < 4; ++t) {
         const int kb2 = t >> 1, r0 = (t & 1) * 8;
-        union { uint32_t u[4]; bf16x8 v; } pf;
+        union { uint32_t u[4]; bf16x8 v; } pf[QB];
 #pragma unroll
-        for (int e = 0; e < 4; ++e) {
-            pf.u[e] = pack2bf(sacc[kb2][r0 + 2 * e], sacc[kb2][r0 + 2 * e + 1]);
-            psum = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, pf.u[e]), ones, psum, false);
-        }
+        for (int qb = 0; qb < QB; ++qb)
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                pf[qb].u[e] = pack2bf(sacc[qb][kb2][r0 + 2 * e], sacc[qb][kb2][r0 + 2 * e + 1]);
+                psum[qb] = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, pf[qb].u[e]), ones, psum[qb], false);
+            }
 #pragma unroll
         for (int db = 0; db < 2; ++db) {
             const bf16x8 vf = *reinterpret_cast<const bf16x8*>(svt + att_swz(db * 32 + l32, 2 * t + g));
-            oacc[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, pf.v, oacc[db], 0, 0, 0);
+#pragma unroll
+            for (int qb = 0; qb < QB; ++qb)
+                oacc[qb][db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, pf[qb].v, oacc[qb][db], 0, 0, 0);
         }
     }
-    l_run = l_run * alpha + psum;
+#pragma unroll
+    for (int qb = 0; qb < QB; ++qb) l_run[qb] = l_run[qb] * alpha[qb] + psum[qb];
 }
 
-// Long sequences: workgroup = 256 query rows (8 waves) of one (image, head).  K tiles stream
+// Long sequences: workgroup = 256 * QB query rows (8 waves, QB blocks of 32 rows each) of one
+// (image, head).  QB = 2 halves the LDS reads and the barriers per unit of work; which one is
+// launched depends on how the row count fills the workgroups.  K tiles stream
 // global -> LDS directly (buffer_load ... lds, rows past N read as zero through the buffer
 // resource); V tiles go through registers because they are transposed on the way in.  Two
 // stages each; the copies of tile t+1 are issued before the MFMAs of tile t, one barrier per tile.
+template <int QB>
 __global__ __launch_bounds__(512, 2) void attention_bf16_kernel(
     const bf16raw* __restrict__ q, const bf16raw* __restrict__ k, const bf16raw* __restrict__ v,
     bf16raw* __restrict__ o, int N, int64_t sb, int64_t sn, int64_t sh, int64_t osb, int64_t osn,
@@ -121,18 +141,19 @@ __global__ __launch_bounds__(512, 2) void attention_bf16_kernel(
     const int head = xcd + 8 * (local / q_tiles);
     if (head >= BH) return;  // whole workgroup, before any barrier
     const int b = head / H, h = head - b * H;
-    const int q0 = (local % q_tiles) * ATT_BM + wave * 32;
+    const int q0 = (local % q_tiles) * (ATT_BM * QB) + wave * (32 * QB);
     const int64_t base = (int64_t)b * sb + (int64_t)h * sh;
     const bf16raw* vb = v + base;
 
-    // Q fragments: B operand, column = query row q0 + l32, k-slots = 8 channels 16*kk + 8*g ..
-    bf16x8 qf[4];
-    {
-        int qr = q0 + l32;
+    // Q fragments: B operand, column = query row q0 + 32 qb + l32, k-slots = 8 channels 16*kk + 8*g ..
+    bf16x8 qf[QB][4];
+#pragma unroll
+    for (int qb = 0; qb < QB; ++qb) {
+        int qr = q0 + qb * 32 + l32;
         qr = qr < N ? qr : N - 1;  // rows past the end are computed on a copy and never stored
         const bf16raw* qp = q + base + (int64_t)qr * sn;
 #pragma unroll
-        for (int kk = 0; kk < 4; ++kk) qf[kk] = *reinterpret_cast<const bf16x8*>(qp + kk * 16 + g * 8);
+        for (int kk = 0; kk < 4; ++kk) qf[qb][kk] = *reinterpret_cast<const bf16x8*>(qp + kk * 16 + g * 8);
     }
 
     // K copies: wave w fills LDS rows 8w .. 8w+7 of the tile (lane l: row l/8, slot l%8 holds
@@ -175,19 +196,24 @@ __global__ __launch_bounds__(512, 2) void attention_bf16_kernel(
 #define ATT_STEP(SKc, SVc, SKn, SVn, kt_, MASK_)                                                              \
     {                                                                                                    \
         ATT_LOAD_NEXT(SKn, (kt_) + 1)                                                                    \
-        att_tile<MASK_>(SKc, SVc, qf, oacc, m_run, l_run, (kt_) * ATT_BN, N, scale_log2e, l32, g);       \
+        att_tile<MASK_, QB>(SKc, SVc, qf, oacc, m_run, l_run, (kt_) * ATT_BN, N, scale_log2e, l32, g);   \
         ATT_STORE_V(SVn)                                                                                 \
         __builtin_amdgcn_s_waitcnt(0x0F70); /* this wave's K copy has landed */                          \
         __syncthreads();                                                                                 \
     }
 
-    f32x16 oacc[2];
+    f32x16 oacc[QB][2];
+    float m_run[QB];  // running max of the raw logits of this lane's query rows
+    float l_run[QB];  // this lane's share of the running row sums
 #pragma unroll
-    for (int i = 0; i < 2; ++i)
+    for (int qb = 0; qb < QB; ++qb) {
 #pragma unroll
-        for (int r = 0; r < 16; ++r) oacc[i][r] = 0.f;
-    float m_run = -INFINITY;  // running max of the raw logits of this lane's query row
-    float l_run = 0.f;        // this lane's share of the running row sum
+        for (int i = 0; i < 2; ++i)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) oacc[qb][i][r] = 0.f;
+        m_run[qb] = -INFINITY;
+        l_run[qb] = 0.f;
+    }
 
     const int KT = (N + ATT_BN - 1) / ATT_BN;
     ATT_LOAD_NEXT(sk0, 0)
@@ -208,21 +234,178 @@ __global__ __launch_bounds__(512, 2) void attention_bf16_kernel(
 #undef ATT_STORE_V
 #undef ATT_STEP
 
-    // ---- normalise and store: lane holds O[q][db*32 + 8j + 4g + i] in oacc[db][4j + i]
-    const float l_tot = l_run + __shfl_xor(l_run, 32, 64);
-    const float inv = 1.0f / l_tot;
-    const int qr = q0 + l32;
-    if (qr < N) {
-        bf16raw* op = o + (int64_t)b * osb + (int64_t)qr * osn + (int64_t)h * osh;
+    // ---- normalise and store: lane holds O[q][db*32 + 8j + 4g + i] in oacc[qb][db][4j + i]
+#pragma unroll
+    for (int qb = 0; qb < QB; ++qb) {
+        const float l_tot = l_run[qb] + __shfl_xor(l_run[qb], 32, 64);
+        const float inv = 1.0f / l_tot;
+        const int qr = q0 + qb * 32 + l32;
+        if (qr < N) {
+            bf16raw* op = o + (int64_t)b * osb + (int64_t)qr * osn + (int64_t)h * osh;
+#pragma unroll
+            for (int db = 0; db < 2; ++db)
+#pragma unroll
+                for (int j = 0; j < 4; ++j) {
+                    uint2 w;
+                    w.x = pack2bf(oacc[qb][db][4 * j] * inv, oacc[qb][db][4 * j + 1] * inv);
+                    w.y = pack2bf(oacc[qb][db][4 * j + 2] * inv, oacc[qb][db][4 * j + 3] * inv);
+                    *reinterpret_cast<uint2*>(op + db * 32 + j * 8 + g * 4) = w;
+                }
+        }
+    }
+}
+
+// ---------------------------------------------------------------------------
+// Last rows of a long sequence.  When N leaves a few rows (at most 64) beyond the last full
+// query tile, a whole workgroup of the kernel above would stream every K/V tile for them with
+// one or two of its eight waves working.  Here one workgroup per (image, head) takes those rows
+// and its eight waves split the KEY tiles instead (wave w: tiles w, w + 8, ...), each with its
+// own K / V^T tile in LDS and no workgroup barrier inside the loop; the eight partial results
+// (running maximum, row sum, unnormalised output) are merged through LDS in wave order, so the
+// result does not depend on timing.
+// ---------------------------------------------------------------------------
+constexpr int ATT_TAIL_ROWS = 64;
+
+__global__ __launch_bounds__(512, 2) void attention_bf16_tail_kernel(
+    const bf16raw* __restrict__ q, const bf16raw* __restrict__ k, const bf16raw* __restrict__ v,
+    bf16raw* __restrict__ o, int N, int64_t sb, int64_t sn, int64_t sh, int64_t osb, int64_t osn,
+    int64_t osh, float scale_log2e, int H, int q_begin) {
+    // per wave: K tile (8 KB) + V^T tile (8 KB); after the loop the same 16 KB hold the wave's
+    // output partial [2 blocks][32 rows][64 channels] fp32
+    __shared__ __attribute__((aligned(1024))) unsigned char s_tiles[8][16384];
+    __shared__ float s_m[8][2][32];
+    __shared__ float s_l[8][2][32];
+
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int l32 = lane & 31, g = lane >> 5;
+    const int b = blockIdx.x / H, h = blockIdx.x - b * H;
+    const int64_t base = (int64_t)b * sb + (int64_t)h * sh;
+    const bf16raw* vb = v + base;
+    unsigned char* sk = s_tiles[wave];
+    unsigned char* svt = sk + ATT_BN * 128;
+
+    bf16x8 qf[2][1][4];
+#pragma unroll
+    for (int qb = 0; qb < 2; ++qb) {
+        int qr = q_begin + qb * 32 + l32;
+        qr = qr < N ? qr : N - 1;  // rows past the end are computed on a copy and never stored
+        const bf16raw* qp = q + base + (int64_t)qr * sn;
+#pragma unroll
+        for (int kk = 0; kk < 4; ++kk) qf[qb][0][kk] = *reinterpret_cast<const bf16x8*>(qp + kk * 16 + g * 8);
+    }
+    const int64_t k_bytes = ((int64_t)(N - 1) * sn + DH) * 2;
+    const __amdgpu_buffer_rsrc_t rs_k = __builtin_amdgcn_make_buffer_rsrc(
+        const_cast<bf16raw*>(k + base), 0, (int)(k_bytes < 0xffffffffll ? k_bytes : 0xffffffffll), 0x00020000);
+    const int k_lr = lane >> 3;
+    const int k_tile_bytes = (int)(ATT_BN * sn * 2);
+
+    f32x16 oacc[2][1][2];
+    float m_run[2][1], l_run[2][1];
+#pragma unroll
+    for (int qb = 0; qb < 2; ++qb) {
+#pragma unroll
+        for (int i = 0; i < 2; ++i)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) oacc[qb][0][i][r] = 0.f;
+        m_run[qb][0] = -INFINITY;
+        l_run[qb][0] = 0.f;
+    }
+
+    const int KT = (N + ATT_BN - 1) / ATT_BN;
+    for (int kt = wave; kt < KT; kt += 8) {
+        // K tile: copy i fills rows 8i .. 8i+7 (lane l: row l/8, slot l%8 holds chunk (l%8) ^ f(row))
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+            const int voff = (int)(((int64_t)(i * 8 + k_lr) * sn + (((lane & 7) ^ k_lr ^ i) << 3)) * 2);
+            __builtin_amdgcn_raw_ptr_buffer_load_lds(rs_k, (att_lds_ptr)(sk + i * 1024), 16, voff, kt * k_tile_bytes, 0, 0);
+        }
+        // V^T tile: pass i plays thread 64 i + lane of the 512-thread staging pattern above; all
+        // loads are issued before the first transposing write
+        uint2 vr0[8], vr1[8];
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+            const int t = i * 64 + lane;
+            const int v_dc = t & 15, v_pos = 2 * (t >> 4);
+            const int v_key = (v_pos & ~15) | (((v_pos >> 2) & 1) << 3) | (((v_pos >> 3) & 1) << 2) | (v_pos & 3);
+            const int kr = kt * ATT_BN + v_key;
+            vr0[i] = make_uint2(0u, 0u);  // keys past the end contribute exact zeros
+            vr1[i] = make_uint2(0u, 0u);
+            if (kr < N) vr0[i] = *reinterpret_cast<const uint2*>(vb + (int64_t)kr * sn + v_dc * 4);
+            if (kr + 1 < N) vr1[i] = *reinterpret_cast<const uint2*>(vb + (int64_t)(kr + 1) * sn + v_dc * 4);
+        }
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+            const int t = i * 64 + lane;
+            const int v_dc = t & 15, v_pos = 2 * (t >> 4);
+            const uint32_t w0[2] = {vr0[i].x, vr0[i].y}, w1[2] = {vr1[i].x, vr1[i].y};
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                const uint32_t lo = (e & 1) ? (w0[e >> 1] >> 16) : (w0[e >> 1] & 0xffffu);
+                const uint32_t hi = (e & 1) ? (w1[e >> 1] & 0xffff0000u) : (w1[e >> 1] << 16);
+                const int d = v_dc * 4 + e;
+                *reinterpret_cast<uint32_t*>(svt + att_swz(d, v_pos >> 3) + (v_pos & 7) * 2) = lo | hi;
+            }
+        }
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");  // this wave's K copies have landed
+        // one block of 32 rows at a time: fewer live registers than both at once, and LDS
+        // bandwidth is not what limits this kernel
+#pragma unroll
+        for (int qb = 0; qb < 2; ++qb) {
+            if (kt == KT - 1 && (N & (ATT_BN - 1)))
+                att_tile<true, 1>(sk, svt, qf[qb], oacc[qb], m_run[qb], l_run[qb], kt * ATT_BN, N, scale_log2e, l32, g);
+            else
+                att_tile<false, 1>(sk, svt, qf[qb], oacc[qb], m_run[qb], l_run[qb], kt * ATT_BN, N, scale_log2e, l32, g);
+        }
+    }
+
+    // ---- merge the eight partials
+#pragma unroll
+    for (int qb = 0; qb < 2; ++qb) {
+        const float l_tot = l_run[qb][0] + __shfl_xor(l_run[qb][0], 32, 64);
+        if (g == 0) {
+            s_m[wave][qb][l32] = m_run[qb][0];
+            s_l[wave][qb][l32] = l_tot;
+        }
+    }
+    __syncthreads();  // every wave has left its tiles: the partials may overwrite them
+    float* part = reinterpret_cast<float*>(s_tiles[wave]);
+#pragma unroll
+    for (int qb = 0; qb < 2; ++qb) {
+        float m_tot = s_m[0][qb][l32];
+#pragma unroll
+        for (int w = 1; w < 8; ++w) m_tot = fmaxf(m_tot, s_m[w][qb][l32]);
+        float L = 0.f;
+#pragma unroll
+        for (int w = 0; w < 8; ++w)
+            L += s_l[w][qb][l32] * __builtin_amdgcn_exp2f((s_m[w][qb][l32] - m_tot) * scale_log2e);
+        const float f = __builtin_amdgcn_exp2f((m_run[qb][0] - m_tot) * scale_log2e) / L;  // 0 for a wave without tiles
 #pragma unroll
         for (int db = 0; db < 2; ++db)
 #pragma unroll
             for (int j = 0; j < 4; ++j) {
-                uint2 w;
-                w.x = pack2bf(oacc[db][4 * j] * inv, oacc[db][4 * j + 1] * inv);
-                w.y = pack2bf(oacc[db][4 * j + 2] * inv, oacc[db][4 * j + 3] * inv);
-                *reinterpret_cast<uint2*>(op + db * 32 + j * 8 + g * 4) = w;
+                const int slot = db * 8 + 2 * j + g;  // 4 channels db*32 + 8j + 4g ..
+                const f32x4 val = {oacc[qb][0][db][4 * j] * f, oacc[qb][0][db][4 * j + 1] * f,
+                                   oacc[qb][0][db][4 * j + 2] * f, oacc[qb][0][db][4 * j + 3] * f};
+                *reinterpret_cast<f32x4*>(part + (qb * 32 + l32) * 64 + ((slot ^ (l32 & 15)) << 2)) = val;
             }
+    }
+    __syncthreads();
+    {
+        const int r = tid >> 3, c8 = tid & 7;  // row of the 64, channels 8 c8 .. 8 c8 + 7
+        float acc[8];
+#pragma unroll
+        for (int e = 0; e < 8; ++e) acc[e] = 0.f;
+#pragma unroll
+        for (int w = 0; w < 8; ++w) {
+            const float* pw = reinterpret_cast<const float*>(s_tiles[w]) + r * 64;
+            const f32x4 lo = *reinterpret_cast<const f32x4*>(pw + (((2 * c8) ^ (r & 15)) << 2));
+            const f32x4 hi = *reinterpret_cast<const f32x4*>(pw + (((2 * c8 + 1) ^ (r & 15)) << 2));
+#pragma unroll
+            for (int e = 0; e < 4; ++e) { acc[e] += lo[e]; acc[4 + e] += hi[e]; }
+        }
+        const int qr = q_begin + r;
+        if (qr < N) Elem<bf16raw>::store8(o + (int64_t)b * osb + (int64_t)qr * osn + (int64_t)h * osh + c8 * 8, acc);
     }
 }
 
@@ -481,11 +664,41 @@ hipError_t launch_attention(rs_dtype dt, const void* q, const void* k, const voi
                            (const bf16raw*)k, (const bf16raw*)v, (bf16raw*)o, N, sb, sn, sh, osb, osn, osh,
                            scale_log2e);
     } else if (dt == RS_BF16) {
-        const int q_tiles = (N + ATT_BM - 1) / ATT_BM, BH = B * H;
+        // Rows per workgroup (256 or 512) and whether the rows beyond the last full query tile go
+        // to the tail kernel: the combination with the least estimated time.  One workgroup per CU;
+        // a 512-row workgroup costs ~1.6x a 256-row one (half the barriers and LDS reads per row);
+        // the tail kernel costs about a third of a 256-row workgroup.
+        const int BH = B * H;
+        int best_qb = 1, best_tail = 0;
+        float best_cost = 1e30f;
+        for (int qb = 1; qb <= 2; ++qb)
+            for (int tail = 0; tail <= 1; ++tail) {
+                const int bm = ATT_BM * qb, rem = N % bm;
+                if (tail && !(rem > 0 && rem <= ATT_TAIL_ROWS && N > bm)) continue;
+                const int tiles = tail ? N / bm : (N + bm - 1) / bm;
+                const float rounds = (float)(((int64_t)BH * tiles + 255) / 256);
+                float cost = rounds * (qb == 2 ? 1.6f : 1.0f);
+                if (tail) cost += 0.35f * (float)((BH + 255) / 256);
+                if (cost < best_cost) { best_cost = cost; best_qb = qb; best_tail = tail; }
+            }
+#ifdef RS_ATT_FORCE_QB
+        best_qb = RS_ATT_FORCE_QB; best_tail = 0;
+#endif
+        const int bm = ATT_BM * best_qb;
+        const int q_tiles = best_tail ? N / bm : (N + bm - 1) / bm;
         dim3 grid(8 * ((BH + 7) / 8) * q_tiles);
-        hipLaunchKernelGGL(attention_bf16_kernel, grid, dim3(512), 0, s, (const bf16raw*)q,
-                           (const bf16raw*)k, (const bf16raw*)v, (bf16raw*)o, N, sb, sn, sh, osb, osn,
-                           osh, scale_log2e, H, BH, q_tiles);
+        if (best_qb == 2)
+            hipLaunchKernelGGL(attention_bf16_kernel<2>, grid, dim3(512), 0, s, (const bf16raw*)q,
+                               (const bf16raw*)k, (const bf16raw*)v, (bf16raw*)o, N, sb, sn, sh, osb, osn,
+                               osh, scale_log2e, H, BH, q_tiles);
+        else
+            hipLaunchKernelGGL(attention_bf16_kernel<1>, grid, dim3(512), 0, s, (const bf16raw*)q,
+                               (const bf16raw*)k, (const bf16raw*)v, (bf16raw*)o, N, sb, sn, sh, osb, osn,
+                               osh, scale_log2e, H, BH, q_tiles);
+        if (best_tail)
+            hipLaunchKernelGGL(attention_bf16_tail_kernel, dim3(BH), dim3(512), 0, s, (const bf16raw*)q,
+                               (const bf16raw*)k, (const bf16raw*)v, (bf16raw*)o, N, sb, sn, sh, osb, osn,
+                               osh, scale_log2e, H, q_tiles * bm);
     } else {
         dim3 grid((N + 63) / 64, H, B);
         hipLaunchKernelGGL(attention_f32_kernel, grid, dim3(64), 0, s, (const float*)q,

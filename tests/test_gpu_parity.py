@@ -45,6 +45,30 @@ def test_attention_packed_qkv(dtype, B, N, H):
     assert err < TOL[dtype]
 
 
+# (B, N, H) chosen so that the launcher takes each of its long-sequence plans: 256-row workgroups
+# plus the tail kernel for the one row left over (128 heads x 513); 512-row workgroups (96 x 1024);
+# 512-row workgroups plus the tail kernel for 36 rows, with a padded last key tile (96 x 1060).
+@pytest.mark.parametrize("B,N,H", [(8, 513, 16), (8, 1024, 12), (8, 1060, 12)])
+def test_attention_long_sequence_plans(B, N, H):
+    _say("attention plans", B, N, H)
+    qkv = host_round(si.generic(7, 1, (B, N, 3, H, 64)), "bf16")
+    ref = oracle.attention(qkv[:, :, 0], qkv[:, :, 1], qkv[:, :, 2], 0.125)
+    d = to_dev(qkv, "bf16")
+    o = torch.full((B, N, H, 64), float("nan"), device="cuda", dtype=torch.bfloat16)
+    rs.rs_attention_fwd(d[:, :, 0], d[:, :, 1], d[:, :, 2], o, 0.125)
+    torch.cuda.synchronize()
+    got = to_host(o)
+    assert np.isfinite(got).all()
+    err = norm_err(got, ref)
+    err_tail = norm_err(got[:, -40:], ref[:, -40:])
+    _say("  err %.3e, last 40 rows %.3e" % (err, err_tail))
+    assert err < TOL["bf16"] and err_tail < TOL["bf16"]
+    again = torch.empty_like(o)
+    rs.rs_attention_fwd(d[:, :, 0], d[:, :, 1], d[:, :, 2], again, 0.125)
+    torch.cuda.synchronize()
+    assert torch.equal(o.view(torch.int16), again.view(torch.int16))  # merge order is fixed
+
+
 @pytest.mark.parametrize("dtype", ["bf16", "f32"])
 def test_attention_large_logits_and_separate_tensors(dtype):
     B, N, H = 1, 130, 2
