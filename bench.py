@@ -40,6 +40,9 @@ def parse():
     ap.add_argument("--cpu-sample", type=int, default=0, help="images for the CPU baseline (0 = auto)")
     ap.add_argument("--stress", action="store_true",
                     help="also time rs_shift_topk alone on an HBM-resident shape (B=4096, N=197, D=768)")
+    ap.add_argument("--graph", action="store_true",
+                    help="capture one step into a HIP graph and time its replays (for the small, launch-bound "
+                         "workloads; the per-kernel replay stays eager)")
     ap.add_argument("--calib-copy-mb", type=int, default=0,
                     help="after the run, copy this many MiB device-to-device three times: a kernel of known "
                          "traffic to scale rocprofv3 FETCH_SIZE / WRITE_SIZE readings with")
@@ -99,9 +102,9 @@ def main():
     ws = torch.empty(max(rs.rs_block_workspace_size(c) for c in cfgs), dtype=torch.uint8, device=dev)
     bufs = [torch.empty((B, N, D), device=dev, dtype=tdt) for _ in range(2)]
     kept = torch.empty((B, N), device=dev, dtype=torch.int32)
-    stream = torch.cuda.current_stream()
 
     def step():
+        stream = torch.cuda.current_stream()   # the capture stream while a graph is recorded
         src = x0
         for l in range(L):
             dst = bufs[l & 1]
@@ -109,13 +112,27 @@ def main():
             src = dst
         return src
 
+    run = step
+    if a.graph:
+        # the library neither allocates nor synchronises, so a whole step records as is
+        side = torch.cuda.Stream()
+        side.wait_stream(torch.cuda.current_stream())
+        with torch.cuda.stream(side):
+            step()
+        torch.cuda.current_stream().wait_stream(side)
+        torch.cuda.synchronize()
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph):
+            step()
+        run = graph.replay
+
     torch.cuda.synchronize()
     for _ in range(a.warmup):
-        step()
+        run()
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     for _ in range(a.steps):
-        step()
+        run()
     torch.cuda.synchronize()
     dt = time.perf_counter() - t0
     ms_per_step = dt / a.steps * 1e3
@@ -199,6 +216,7 @@ def main():
         "roofline": roofline,
         "kernels": kernels,
         "instrumented_ms_per_step": round(instr_ms_per_step, 4),
+        "launch": "hip graph replay" if a.graph else "eager",
     }
 
     # ---- optional: the prune pass alone on an HBM-resident shape ----

@@ -325,3 +325,58 @@ def test_multi_block_teacher_forced():
         assert norm_err(to_host(y), oracle.gather(ref["xhat"], kept_h)) < TOL[dtype]
         _say("  block %d: kept exact on %.0f%% of images" % (blk + 1, 100 * exact))
         dx = y
+
+
+def test_block_stack_replays_from_a_hip_graph():
+    """Three blocks with pruning recorded into one HIP graph (the library neither allocates nor
+    synchronises); every replay, with eager work and synchronisations in between, must equal
+    the eager result bit for bit."""
+    B, N, D, H, Dm = 4, 197, 192, 3, 768
+    sched = rs.keep_counts(N, 1, 3, dict(kind="drop_pct", pct=25, after=[1, 2]))
+    x0 = to_dev(host_round(si.tokens(9, B, N, D, 0.3), "bf16"), "bf16")
+    ws_list, cfgs, keep = [], [], []
+    for l, (n_in, n_keep) in enumerate(sched):
+        w = {k: to_dev(host_round(v, "bf16"), "bf16") for k, v in si.block_weights(9, l, D, Dm, 0.05).items()}
+        cfg = rs.make_cfg(B, n_in, D, H, Dm, 1, n_keep, torch.bfloat16)
+        packed = torch.empty(rs.rs_packed_weights_size(cfg), dtype=torch.uint8, device="cuda")
+        rs.rs_pack_weights(cfg, rs.make_weights(w), packed)
+        keep.append((w, packed))
+        ws_list.append(rs.make_weights(w, packed))
+        cfgs.append(cfg)
+    ws = torch.empty(max(rs.rs_block_workspace_size(c) for c in cfgs), dtype=torch.uint8, device="cuda")
+    bufs = [torch.zeros((B, N, D), device="cuda", dtype=torch.bfloat16) for _ in range(2)]
+    kept = torch.zeros((B, N), device="cuda", dtype=torch.int32)
+
+    def step():
+        stream = torch.cuda.current_stream()
+        src = x0
+        for l in range(3):
+            rs.rs_block_fwd(cfgs[l], ws_list[l], src, bufs[l & 1], kept, None, ws, stream)
+            src = bufs[l & 1]
+        return src
+
+    K_last = 1 + sched[-1][1]
+    step()
+    torch.cuda.synchronize()
+    n_y, n_k = B * K_last * D, B * K_last     # y and kept_idx are compact [B, K, D] / [B, K] at the buffer start
+    want = step().view(-1)[:n_y].clone()
+    want_kept = kept.view(-1)[:n_k].clone()
+    torch.cuda.synchronize()
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        step()
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        out = step()
+    for rep in range(4):
+        for b_ in bufs:
+            b_.fill_(float(rep))      # eager work between replays; stale data must not survive
+        kept.zero_()
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(out.view(-1)[:n_y].view(torch.int16), want.view(torch.int16)), rep
+        assert torch.equal(kept.view(-1)[:n_k], want_kept), rep
