@@ -31,15 +31,21 @@ __device__ __forceinline__ int att_swz(int r, int c) { return r * 128 + (((c ^ r
 
 typedef __attribute__((address_space(3))) void* att_lds_ptr;
 
+// 16-byte chunk `chunk` (0..31) of the 512-byte row of channel `d` in a resident V^T array of
+// 256 key positions (short-sequence kernel).
+__device__ __forceinline__ int vt_off(int d, int chunk) { return d * 512 + ((chunk ^ ((d ^ (d >> 3)) & 15)) << 4); }
+
 // QB query-row blocks of 32 rows against one resident tile of 64 keys: S^T = K Q^T, online
 // softmax in registers (one lane = one query row per block, half of the tile's keys),
 // O^T += V^T P^T.  Every K and V^T fragment read from LDS serves all QB blocks.
-// `sk`: K tile [64 keys][128 B] swizzled; `svt`: V^T tile [64 channels][64 key positions].
-template <bool MASK, int QB>
+// `sk`: K tile [64 keys][128 B] swizzled; `svt`: V^T tile [64 channels][64 key positions], or
+// (RESIDENT) the whole head's V^T [64 channels][256 key positions] with `vt_tile` = index of the
+// 64-key tile inside it.
+template <bool MASK, int QB, bool RESIDENT = false>
 __device__ __forceinline__ void att_tile(const unsigned char* sk, const unsigned char* svt,
                                          const bf16x8 (&qf)[QB][4], f32x16 (&oacc)[QB][2],
                                          float (&m_run)[QB], float (&l_run)[QB], int key0, int N,
-                                         float scale_log2e, int l32, int g) {
+                                         float scale_log2e, int l32, int g, int vt_tile = 0) {
     f32x16 sacc[QB][2];
 #pragma unroll
     for (int qb = 0; qb < QB; ++qb)
@@ -82,10 +88,16 @@ __device__ __forceinline__ void att_tile(const unsigned char* sk, const unsigned
             sacc[qb][1][r] = __builtin_amdgcn_exp2f(fmaf(sacc[qb][1][r], scale_log2e, -mb));
         }
         if (__ballot(alpha[qb] != 1.0f)) {  // the running maximum moved for some row of this block
+            // in-place multiplies: with plain C++ the compiler renames the 32 accumulators on this
+            // rarely taken path and pays 32 register copies on EVERY tile to merge the two paths
 #pragma unroll
             for (int i = 0; i < 2; ++i)
 #pragma unroll
-                for (int r = 0; r < 16; ++r) oacc[qb][i][r] *= alpha[qb];
+                for (int r = 0; r < 16; ++r) {
+                    float t = oacc[qb][i][r];
+                    asm volatile("v_mul_f32 %0, %0, %1" : "+v"(t) : "v"(alpha[qb]));
+                    oacc[qb][i][r] = t;
+                }
         }
     }
     // P goes to bf16 once; the row sum is taken over the same rounded values (v_dot2 with ones)
@@ -106,7 +118,8 @@ __device__ __forceinline__ void att_tile(const unsigned char* sk, const unsigned
             }
 #pragma unroll
         for (int db = 0; db < 2; ++db) {
-            const bf16x8 vf = *reinterpret_cast<const bf16x8*>(svt + att_swz(db * 32 + l32, 2 * t + g));
+            const bf16x8 vf = *reinterpret_cast<const bf16x8*>(
+                svt + (RESIDENT ? vt_off(db * 32 + l32, 2 * (vt_tile * 4 + t) + g) : att_swz(db * 32 + l32, 2 * t + g)));
 #pragma unroll
             for (int qb = 0; qb < QB; ++qb)
                 oacc[qb][db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, pf[qb].v, oacc[qb][db], 0, 0, 0);
@@ -422,8 +435,6 @@ __global__ __launch_bounds__(512, 2) void attention_bf16_tail_kernel(
 // ---------------------------------------------------------------------------
 constexpr int SM_MAXN = 256;
 
-__device__ __forceinline__ int vt_off(int d, int chunk) { return d * 512 + ((chunk ^ ((d ^ (d >> 3)) & 15)) << 4); }
-
 __global__ __launch_bounds__(512) void attention_bf16_small_kernel(
     const bf16raw* __restrict__ q, const bf16raw* __restrict__ k, const bf16raw* __restrict__ v,
     bf16raw* __restrict__ o, int N, int64_t sb, int64_t sn, int64_t sh, int64_t osb, int64_t osn,
@@ -440,117 +451,81 @@ __global__ __launch_bounds__(512) void attention_bf16_small_kernel(
     const int KT = (N + ATT_BN - 1) / ATT_BN;   // key tiles of 64
     const int NP = KT * ATT_BN;                 // keys including the padding of the last tile
 
-    // ---- K -> LDS: 16-byte chunk (tid & 7) of key rows (tid >> 3) + 64 i
-    {
-        const int ld_chunk = tid & 7, ld_row = tid >> 3;
-        for (int r = ld_row; r < NP; r += 64) {
-            const int kr = r < N ? r : N - 1;  // padded keys are masked to -inf below
-            const uint4 t = *reinterpret_cast<const uint4*>(kb + (int64_t)kr * sn + ld_chunk * 8);
-            *reinterpret_cast<uint4*>(&s_k[att_swz(r, ld_chunk)]) = t;
-        }
-    }
-    // ---- V -> LDS transposed.  Thread: channel chunk (tid & 7), key positions 2a, 2a+1 with
-    //      a = (tid >> 3) + 64 i; position p = 16T + 8g' + 4u + i  <->  key 16T + 8u + 4g' + i
-    {
-        const int dc = tid & 7;
-        for (int a2 = tid >> 3; 2 * a2 < NP; a2 += 64) {
-            const int vpos = 2 * a2;
-            const int vkey = (vpos & ~15) | (((vpos >> 2) & 1) << 3) | (((vpos >> 3) & 1) << 2) | (vpos & 3);
-            uint4 r0 = make_uint4(0u, 0u, 0u, 0u), r1 = r0;  // keys past the end contribute exact zeros
-            if (vkey < N) r0 = *reinterpret_cast<const uint4*>(vb + (int64_t)vkey * sn + dc * 8);
-            if (vkey + 1 < N) r1 = *reinterpret_cast<const uint4*>(vb + (int64_t)(vkey + 1) * sn + dc * 8);
-            const uint32_t w0[4] = {r0.x, r0.y, r0.z, r0.w};
-            const uint32_t w1[4] = {r1.x, r1.y, r1.z, r1.w};
+    // All global loads of the workgroup's share of K, V and Q are issued first and written to LDS
+    // afterwards: one memory latency per workgroup instead of one per loop iteration.
+    // K: 16-byte chunk (tid & 7) of key rows (tid >> 3) + 64 i.  V: channel chunk (tid & 7), key
+    // positions 2a, 2a+1 with a = (tid >> 3) + 64 i; position p = 16T + 8g' + 4u + i  <->  key
+    // 16T + 8u + 4g' + i.
+    const int ld_chunk = tid & 7, ld_row = tid >> 3;
+    uint4 k_reg[SM_MAXN / 64];
 #pragma unroll
-            for (int e = 0; e < 8; ++e) {
-                const uint32_t lo = (e & 1) ? (w0[e >> 1] >> 16) : (w0[e >> 1] & 0xffffu);
-                const uint32_t hi = (e & 1) ? (w1[e >> 1] & 0xffff0000u) : (w1[e >> 1] << 16);
-                const int d = dc * 8 + e;
-                *reinterpret_cast<uint32_t*>(&s_vt[vt_off(d, vpos >> 3) + (vpos & 7) * 2]) = lo | hi;
-            }
-        }
+    for (int i = 0; i < SM_MAXN / 64; ++i) {
+        const int r = ld_row + 64 * i;
+        const int kr = r < N ? r : N - 1;  // padded keys are masked to -inf in the last tile
+        k_reg[i] = make_uint4(0u, 0u, 0u, 0u);
+        if (r < NP) k_reg[i] = *reinterpret_cast<const uint4*>(kb + (int64_t)kr * sn + ld_chunk * 8);
+    }
+    uint4 v_reg0[SM_MAXN / 128], v_reg1[SM_MAXN / 128];
+    int v_posn[SM_MAXN / 128];
+#pragma unroll
+    for (int i = 0; i < SM_MAXN / 128; ++i) {
+        const int vpos = 2 * (ld_row + 64 * i);
+        const int vkey = (vpos & ~15) | (((vpos >> 2) & 1) << 3) | (((vpos >> 3) & 1) << 2) | (vpos & 3);
+        v_posn[i] = vpos;
+        v_reg0[i] = make_uint4(0u, 0u, 0u, 0u);  // keys past the end contribute exact zeros
+        v_reg1[i] = make_uint4(0u, 0u, 0u, 0u);
+        if (vkey < N) v_reg0[i] = *reinterpret_cast<const uint4*>(vb + (int64_t)vkey * sn + ld_chunk * 8);
+        if (vkey + 1 < N) v_reg1[i] = *reinterpret_cast<const uint4*>(vb + (int64_t)(vkey + 1) * sn + ld_chunk * 8);
     }
     const int q0 = wave * 32;
     // Q fragments (B operand): column = query row q0 + l32, k-slots = channels 16 kk + 8 g ..
-    bf16x8 qf[4];
+    bf16x8 qf[1][4];
     {
         int qr = q0 + l32;
         qr = qr < N ? qr : N - 1;
         const bf16raw* qp = q + base + (int64_t)qr * sn;
 #pragma unroll
-        for (int kk = 0; kk < 4; ++kk) qf[kk] = *reinterpret_cast<const bf16x8*>(qp + kk * 16 + g * 8);
+        for (int kk = 0; kk < 4; ++kk) qf[0][kk] = *reinterpret_cast<const bf16x8*>(qp + kk * 16 + g * 8);
+    }
+#pragma unroll
+    for (int i = 0; i < SM_MAXN / 64; ++i) {
+        const int r = ld_row + 64 * i;
+        if (r < NP) *reinterpret_cast<uint4*>(&s_k[att_swz(r, ld_chunk)]) = k_reg[i];
+    }
+#pragma unroll
+    for (int i = 0; i < SM_MAXN / 128; ++i) {
+        const int vpos = v_posn[i];
+        if (vpos < NP) {
+            const uint32_t w0[4] = {v_reg0[i].x, v_reg0[i].y, v_reg0[i].z, v_reg0[i].w};
+            const uint32_t w1[4] = {v_reg1[i].x, v_reg1[i].y, v_reg1[i].z, v_reg1[i].w};
+#pragma unroll
+            for (int e = 0; e < 8; ++e) {
+                const uint32_t lo = (e & 1) ? (w0[e >> 1] >> 16) : (w0[e >> 1] & 0xffffu);
+                const uint32_t hi = (e & 1) ? (w1[e >> 1] & 0xffff0000u) : (w1[e >> 1] << 16);
+                const int d = ld_chunk * 8 + e;
+                *reinterpret_cast<uint32_t*>(&s_vt[vt_off(d, vpos >> 3) + (vpos & 7) * 2]) = lo | hi;
+            }
+        }
     }
     __syncthreads();
     if (q0 >= N) return;  // whole-wave exit after the only barrier
 
-    f32x16 oacc[2];
+    f32x16 oacc[1][2];
 #pragma unroll
     for (int i = 0; i < 2; ++i)
 #pragma unroll
-        for (int r = 0; r < 16; ++r) oacc[i][r] = 0.f;
-    float m_run = -INFINITY, l_run = 0.f;
+        for (int r = 0; r < 16; ++r) oacc[0][i][r] = 0.f;
+    float m_run[1] = {-INFINITY}, l_run[1] = {0.f};
 
-    for (int kt = 0; kt < KT; ++kt) {
-        f32x16 sacc[2];
-#pragma unroll
-        for (int kb2 = 0; kb2 < 2; ++kb2) {
-#pragma unroll
-            for (int r = 0; r < 16; ++r) sacc[kb2][r] = 0.f;
-#pragma unroll
-            for (int kk = 0; kk < 4; ++kk) {
-                bf16x8 kf = *reinterpret_cast<const bf16x8*>(&s_k[att_swz(kt * 64 + kb2 * 32 + l32, kk * 2 + g)]);
-                sacc[kb2] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[kk], sacc[kb2], 0, 0, 0);
-            }
-        }
-        if ((kt + 1) * ATT_BN > N) {
-#pragma unroll
-            for (int kb2 = 0; kb2 < 2; ++kb2)
-#pragma unroll
-                for (int r = 0; r < 16; ++r) {
-                    const int key = kt * ATT_BN + kb2 * 32 + (r >> 2) * 8 + g * 4 + (r & 3);
-                    if (key >= N) sacc[kb2][r] = -INFINITY;
-                }
-        }
-        float mx = sacc[0][0];
-#pragma unroll
-        for (int kb2 = 0; kb2 < 2; ++kb2)
-#pragma unroll
-            for (int r = 0; r < 16; ++r) mx = fmaxf(mx, sacc[kb2][r]);
-        mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
-        const float m_new = fmaxf(m_run, mx);
-        const float alpha = exp2f((m_run - m_new) * scale_log2e);
-        const float mb = m_new * scale_log2e;
-        m_run = m_new;
-        float psum = 0.f;
-#pragma unroll
-        for (int kb2 = 0; kb2 < 2; ++kb2)
-#pragma unroll
-            for (int r = 0; r < 16; ++r) {
-                const float p = __builtin_amdgcn_exp2f(fmaf(sacc[kb2][r], scale_log2e, -mb));
-                sacc[kb2][r] = p;
-                psum += p;
-            }
-        l_run = l_run * alpha + psum;
-        if (__ballot(alpha != 1.0f)) {  // the running maximum moved for some row of this wave
-#pragma unroll
-            for (int i = 0; i < 2; ++i)
-#pragma unroll
-                for (int r = 0; r < 16; ++r) oacc[i][r] *= alpha;
-        }
-#pragma unroll
-        for (int t = 0; t < 4; ++t) {
-            const int kb2 = t >> 1, r0 = (t & 1) * 8;
-            union { uint32_t u[4]; bf16x8 v; } pf;
-#pragma unroll
-            for (int e = 0; e < 4; ++e) pf.u[e] = pack2bf(sacc[kb2][r0 + 2 * e], sacc[kb2][r0 + 2 * e + 1]);
-#pragma unroll
-            for (int db = 0; db < 2; ++db) {
-                bf16x8 vf = *reinterpret_cast<const bf16x8*>(&s_vt[vt_off(db * 32 + l32, 2 * (kt * 4 + t) + g)]);
-                oacc[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, pf.v, oacc[db], 0, 0, 0);
-            }
-        }
-    }
-    const float l_tot = l_run + __shfl_xor(l_run, 32, 64);
+    const int KF = N / ATT_BN;  // tiles without padding keys: no masking work in the loop
+    for (int kt = 0; kt < KF; ++kt)
+        att_tile<false, 1, true>(s_k + kt * (ATT_BN * 128), s_vt, qf, oacc, m_run, l_run, kt * ATT_BN, N, scale_log2e,
+                                 l32, g, kt);
+    if (KF < KT)
+        att_tile<true, 1, true>(s_k + KF * (ATT_BN * 128), s_vt, qf, oacc, m_run, l_run, KF * ATT_BN, N, scale_log2e,
+                                l32, g, KF);
+
+    const float l_tot = l_run[0] + __shfl_xor(l_run[0], 32, 64);
     const float inv = 1.0f / l_tot;
     const int qr = q0 + l32;
     if (qr < N) {
@@ -560,8 +535,8 @@ __global__ __launch_bounds__(512) void attention_bf16_small_kernel(
 #pragma unroll
             for (int j = 0; j < 4; ++j) {
                 uint2 w;
-                w.x = pack2bf(oacc[db][4 * j] * inv, oacc[db][4 * j + 1] * inv);
-                w.y = pack2bf(oacc[db][4 * j + 2] * inv, oacc[db][4 * j + 3] * inv);
+                w.x = pack2bf(oacc[0][db][4 * j] * inv, oacc[0][db][4 * j + 1] * inv);
+                w.y = pack2bf(oacc[0][db][4 * j + 2] * inv, oacc[0][db][4 * j + 3] * inv);
                 *reinterpret_cast<uint2*>(op + db * 32 + j * 8 + g * 4) = w;
             }
     }
