@@ -148,6 +148,51 @@ def shift_topk(f_out, f_in, src, n_prefix, n_keep, dist=DIST_L2):
     return s, kept, gather(f_in if src is None else src, kept)
 
 
+def grid_line_scores(scores):
+    """Line-wise scores of a 2-D token grid (Sec. 4.2, "CNN and SSM", variant (ii)): the shift
+    averaged along each row and along each column.  scores [B, H, W] -> ([B, H], [B, W]).
+    Plain sequential sums in index order."""
+    s = _d(scores)
+    B, H, W = s.shape
+    rows = np.zeros((B, H), np.float64)
+    cols = np.zeros((B, W), np.float64)
+    for w in range(W):
+        rows += s[:, :, w]
+    for h in range(H):
+        cols += s[:, h, :]
+    return rows / W, cols / H
+
+
+def grid_line_prune(f_out, f_in, src, keep_rows, keep_cols, dist=DIST_L2):
+    """Line-wise pruning of a [B, H, W, C] grid: per-position shift D(f_out, f_in) over the
+    channels, averaged per row and per column; the keep_rows rows and keep_cols columns with
+    the highest averages survive (ties: lower index; survivors in ascending order), and `src`
+    (f_out when None: the stage output is what gets pruned) is cut down to them.
+
+    Returns scores [B,H,W], row_scores [B,H], col_scores [B,W], kept_rows [B,keep_rows],
+    kept_cols [B,keep_cols], gathered [B,keep_rows,keep_cols,C]."""
+    a, b = _d(f_out), _d(f_in)
+    B, H, W, C = a.shape
+    s = shift_scores(a, b, dist)
+    rs_, cs_ = grid_line_scores(s)
+    kr = topk(rs_, 0, keep_rows)
+    kc = topk(cs_, 0, keep_cols)
+    g = grid_gather(a if src is None else src, kr, kc)
+    return s, rs_, cs_, kr, kc, g
+
+
+def grid_gather(src, kept_rows, kept_cols):
+    """src [B, H, W, C] -> [B, R, Q, C] with out[b, i, j] = src[b, kept_rows[b, i], kept_cols[b, j]]."""
+    src = _d(src)
+    B = src.shape[0]
+    out = np.empty((B, kept_rows.shape[1], kept_cols.shape[1], src.shape[3]), np.float64)
+    for b_ in range(B):
+        for i, r in enumerate(kept_rows[b_]):
+            for j, c in enumerate(kept_cols[b_]):
+                out[b_, i, j] = src[b_, r, c]
+    return out
+
+
 def block(x, w, H, ln_eps=1e-6, attn_scale=None, dist=DIST_L2, op=OP_MLP):
     """One encoder block on x [B, N, D] with weight dict `w` (missing/None bias = 0).
 

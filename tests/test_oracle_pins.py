@@ -429,3 +429,47 @@ def test_shift_topk_composition_drops_lowest_shift():
     np.testing.assert_array_equal(y[0], x[0, [0, 2, 4, 5, 7]])
     s, kept, y = oracle.shift_topk(f, x, f, 1, 4)
     np.testing.assert_array_equal(y[0], f[0, [0, 2, 4, 5, 7]])
+
+
+# ----------------------------------------------------------------------------
+# Line-wise pruning of a 2-D grid (Sec. 4.2, "CNN and SSM", variant (ii))
+# ----------------------------------------------------------------------------
+def test_grid_line_prune_closed_forms():
+    B, H, W, C = 2, 5, 4, 8
+    f_in = RNG.standard_normal((B, H, W, C))
+    # the shift depends on the row only: row h moves by amp[h] along one channel
+    amp = np.array([0.5, 3.0, 1.0, 2.0, 0.25])
+    f_out = f_in.copy()
+    f_out[..., 0] += amp[None, :, None]
+    s, rs_, cs_, kr, kc, g = oracle.grid_line_prune(f_out, f_in, None, 3, 2)
+    np.testing.assert_allclose(s, np.broadcast_to(amp[None, :, None], (B, H, W)), rtol=1e-12)
+    np.testing.assert_allclose(rs_, np.broadcast_to(amp, (B, H)), rtol=1e-12)
+    np.testing.assert_allclose(cs_, np.full((B, W), amp.mean()), rtol=1e-12)
+    np.testing.assert_array_equal(kr, np.tile([1, 2, 3], (B, 1)))     # the three largest rows, ascending
+    np.testing.assert_array_equal(kc, np.tile([0, 1], (B, 1)))        # all columns tie: lowest indices
+    np.testing.assert_array_equal(g, f_out[:, [1, 2, 3]][:, :, [0, 1]])
+    # keep everything: identity
+    s, rs_, cs_, kr, kc, g = oracle.grid_line_prune(f_out, f_in, f_in, H, W)
+    np.testing.assert_array_equal(g, f_in)
+
+
+def test_grid_line_prune_against_numpy_sort():
+    B, H, W, C = 3, 7, 6, 16
+    f_in = RNG.standard_normal((B, H, W, C))
+    f_out = f_in + RNG.standard_normal((B, H, W, C)) * np.exp(RNG.standard_normal((B, H, W, 1)))
+    src = RNG.standard_normal((B, H, W, C))
+    for dist in (0, 1, 2):
+        s, rs_, cs_, kr, kc, g = oracle.grid_line_prune(f_out, f_in, src, 4, 3, dist)
+        if dist == 0:
+            want = np.linalg.norm(f_out - f_in, axis=-1)
+        elif dist == 1:
+            want = np.abs(f_out - f_in).sum(-1)
+        else:
+            want = 1 - (f_out * f_in).sum(-1) / (np.linalg.norm(f_out, axis=-1) * np.linalg.norm(f_in, axis=-1))
+        np.testing.assert_allclose(s, want, rtol=1e-10)
+        np.testing.assert_allclose(rs_, want.mean(axis=2), rtol=1e-12)
+        np.testing.assert_allclose(cs_, want.mean(axis=1), rtol=1e-12)
+        for b in range(B):
+            np.testing.assert_array_equal(kr[b], np.sort(np.argsort(-want.mean(axis=2)[b], kind="stable")[:4]))
+            np.testing.assert_array_equal(kc[b], np.sort(np.argsort(-want.mean(axis=1)[b], kind="stable")[:3]))
+            np.testing.assert_array_equal(g[b], src[b][kr[b]][:, kc[b]])
