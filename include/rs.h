@@ -170,6 +170,27 @@ RS_API rs_status rs_pack_weights(const rs_block_cfg *cfg, const rs_block_weights
                           void *packed_out, void *hip_stream);
 
 /*
+ * Line-wise pruning of a 2-D token grid (Sec. 4.2, "CNN and SSM", variant (ii)): for feature maps
+ * without a token sequence the shift s[b,h,w] = D(f_out[b,h,w,:], f_in[b,h,w,:]) (Eq. (4)) is
+ * averaged along every row and every column, and whole lines with the lowest averages are
+ * removed so that the grid stays rectangular.
+ *   f_out, f_in : [B, H, W, C] channel-last, same shape (which two maps of a stage to compare
+ *                 is the caller's choice: the paper compares a stage's input and output).
+ *   src         : [B, H, W, C] map to cut down, NULL = f_out (the stage output).
+ *   keep_rows, keep_cols : lines kept per image (ties: lower index kept; order ascending).
+ *   scores [B,H,W], row_scores [B,H], col_scores [B,W] : fp32 outputs, all required.
+ *   kept_rows [B, keep_rows], kept_cols [B, keep_cols] : int32 outputs.
+ *   gathered [B, keep_rows, keep_cols, C] or NULL; must not alias src.
+ * C % 8 == 0.  No workspace.  Deterministic.  The token-wise variant (i) of the same passage
+ * is not built.
+ */
+RS_API rs_status rs_grid_line_prune(const void *f_out, const void *f_in, const void *src, int32_t B,
+                                    int32_t H, int32_t W, int32_t C, int32_t keep_rows,
+                                    int32_t keep_cols, rs_dist dist, rs_dtype dtype, float *scores,
+                                    float *row_scores, float *col_scores, int32_t *kept_rows,
+                                    int32_t *kept_cols, void *gathered, void *hip_stream);
+
+/*
  * One linear layer of the block with its fused elementwise tail (the four contractions of
  * Eqs. (5),(6): QKV, output projection, fc1, fc2; the O(N C^2) term of Sec. 3.1):
  *     out = epilogue(a @ W + bias)

@@ -153,4 +153,11 @@ hipError_t launch_select(const float* scores, int32_t* kept_idx, int B, int N, i
 hipError_t launch_gather(rs_dtype dt, const void* src, const int32_t* kept_idx, void* out, int B,
                          int N, int K, int D, hipStream_t s);
 
+// 2-D grid: row_scores[b, h] = mean_w scores[b, h, w], col_scores[b, w] = mean_h scores[b, h, w]
+hipError_t launch_grid_line_scores(const float* scores, float* row_scores, float* col_scores, int B, int H,
+                                   int W, hipStream_t s);
+// out[b, i, j, :] = src[b, kept_rows[b, i], kept_cols[b, j], :]   (src [B, H, W, C], out [B, R, Q, C])
+hipError_t launch_grid_gather(rs_dtype dt, const void* src, const int32_t* kept_rows, const int32_t* kept_cols,
+                              void* out, int B, int H, int W, int R, int Q, int C, hipStream_t s);
+
 }  // namespace rs

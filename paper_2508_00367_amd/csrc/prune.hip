@@ -234,4 +234,60 @@ hipError_t launch_gather(rs_dtype dt, const void* src, const int32_t* kept_idx, 
     return hipGetLastError();
 }
 
+// ---------------------------------------------------------------------------
+// Line-wise pruning of a 2-D token grid (Sec. 4.2, "CNN and SSM", variant (ii)).
+// Line scores: the per-position shift averaged along each row and along each column; one
+// workgroup per image, thread h sums row h over w in index order and thread w sums column w
+// over h in index order (fixed order: bit-reproducible).  The rows and columns to keep are then
+// picked by select_kernel, and the grid gather copies the surviving positions.
+// ---------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void grid_line_scores_kernel(const float* __restrict__ scores,
+                                                               float* __restrict__ row_scores,
+                                                               float* __restrict__ col_scores, int H, int W) {
+    const float* s = scores + (int64_t)blockIdx.x * H * W;
+    for (int h = threadIdx.x; h < H; h += 256) {
+        float a = 0.f;
+        for (int w = 0; w < W; ++w) a += s[h * W + w];
+        row_scores[(int64_t)blockIdx.x * H + h] = a / (float)W;
+    }
+    for (int w = threadIdx.x; w < W; w += 256) {
+        float a = 0.f;
+        for (int h = 0; h < H; ++h) a += s[h * W + w];
+        col_scores[(int64_t)blockIdx.x * W + w] = a / (float)H;
+    }
+}
+
+hipError_t launch_grid_line_scores(const float* scores, float* row_scores, float* col_scores, int B, int H,
+                                   int W, hipStream_t s) {
+    if (B == 0) return hipSuccess;
+    hipLaunchKernelGGL(grid_line_scores_kernel, dim3(B), dim3(256), 0, s, scores, row_scores, col_scores, H, W);
+    return hipGetLastError();
+}
+
+// out[b, i, j, :] = src[b, kept_rows[b, i], kept_cols[b, j], :]; one wavefront per output position
+__global__ __launch_bounds__(256) void grid_gather_kernel(const uint4* __restrict__ src,
+                                                          const int32_t* __restrict__ kept_rows,
+                                                          const int32_t* __restrict__ kept_cols,
+                                                          uint4* __restrict__ out, int64_t positions, int H, int W,
+                                                          int R, int Q, int vec) {
+    const int lane = threadIdx.x & 63;
+    const int64_t p = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
+    if (p >= positions) return;
+    const int64_t b = p / ((int64_t)R * Q);
+    const int ij = (int)(p - b * R * Q);
+    const int i = ij / Q, j = ij - i * Q;
+    const int64_t sp = (b * H + kept_rows[b * R + i]) * W + kept_cols[b * Q + j];
+    for (int c = lane; c < vec; c += 64) out[p * vec + c] = src[sp * vec + c];
+}
+
+hipError_t launch_grid_gather(rs_dtype dt, const void* src, const int32_t* kept_rows, const int32_t* kept_cols,
+                              void* out, int B, int H, int W, int R, int Q, int C, hipStream_t s) {
+    const int64_t positions = (int64_t)B * R * Q;
+    if (positions == 0) return hipSuccess;
+    const int vec = (int)((size_t)C * elem_size(dt) / 16);
+    hipLaunchKernelGGL(grid_gather_kernel, dim3((unsigned)((positions + 3) / 4)), dim3(256), 0, s, (const uint4*)src,
+                       kept_rows, kept_cols, (uint4*)out, positions, H, W, R, Q, vec);
+    return hipGetLastError();
+}
+
 }  // namespace rs

@@ -380,3 +380,39 @@ def test_block_stack_replays_from_a_hip_graph():
         torch.cuda.synchronize()
         assert torch.equal(out.view(-1)[:n_y].view(torch.int16), want.view(torch.int16)), rep
         assert torch.equal(kept.view(-1)[:n_k], want_kept), rep
+
+
+# ----------------------------------------------------------------------------
+# line-wise pruning of a 2-D grid
+# ----------------------------------------------------------------------------
+GRID_CASES = [  # B, H, W, C, keep_rows, keep_cols  (ResNet stage shapes: 56x56x64 -> 48x48, 28x28x128 -> 24x24)
+    (2, 56, 56, 64, 48, 48), (3, 28, 28, 128, 24, 24), (1, 7, 5, 8, 7, 5), (2, 9, 300, 16, 0, 3), (1, 1, 1, 2048, 1, 1)]
+
+
+@pytest.mark.parametrize("dtype", ["bf16", "f32"])
+@pytest.mark.parametrize("dist", [rs.RS_DIST_L2, rs.RS_DIST_COS])
+@pytest.mark.parametrize("B,H,W,C,R,Q", GRID_CASES)
+def test_grid_line_prune(dtype, dist, B, H, W, C, R, Q):
+    _say("grid", dtype, dist, B, H, W, C, R, Q)
+    f_in = host_round(si.generic(11, 1, (B, H, W, C)), dtype)
+    f_out = host_round(f_in + si.generic(11, 2, (B, H, W, C), std=0.3) * np.exp(si.generic(11, 3, (B, H, W, 1), std=0.7)), dtype)
+    src = host_round(si.generic(11, 4, (B, H, W, C)), dtype)
+    s_ref, r_ref, c_ref, kr_ref, kc_ref, g_ref = oracle.grid_line_prune(f_out, f_in, src, R, Q, dist)
+    d_out, d_in, d_src = (to_dev(t, dtype) for t in (f_out, f_in, src))
+    scores = torch.full((B, H, W), float("nan"), device="cuda", dtype=torch.float32)
+    rsc = torch.full((B, H), float("nan"), device="cuda", dtype=torch.float32)
+    csc = torch.full((B, W), float("nan"), device="cuda", dtype=torch.float32)
+    kr = torch.full((B, R), -1, device="cuda", dtype=torch.int32)
+    kc = torch.full((B, Q), -1, device="cuda", dtype=torch.int32)
+    g = torch.full((B, R, Q, C), float("nan"), device="cuda", dtype=d_in.dtype)
+    rs.rs_grid_line_prune(d_out, d_in, d_src, R, Q, scores, rsc, csc, kr, kc, g, dist=dist)
+    torch.cuda.synchronize()
+    s, r_, c_ = to_host(scores), to_host(rsc), to_host(csc)
+    assert norm_err(s, s_ref) < 1e-5 and norm_err(r_, r_ref) < 1e-5 and norm_err(c_, c_ref) < 1e-5
+    kr_h, kc_h = kr.cpu().numpy(), kc.cpu().numpy()
+    # selection is exact on the GPU's own line scores, and admissible against the checker's
+    np.testing.assert_array_equal(kr_h, oracle.topk(r_, 0, R))
+    np.testing.assert_array_equal(kc_h, oracle.topk(c_, 0, Q))
+    check_kept_admissible(kr_h, r_, r_ref, 0, R)
+    check_kept_admissible(kc_h, c_, c_ref, 0, Q)
+    np.testing.assert_array_equal(to_host(g), oracle.grid_gather(src, kr_h, kc_h))
