@@ -98,8 +98,13 @@ __global__ __launch_bounds__(WGM* WGN * 64, WGM* WGN / 4) void gemm_bf16_kernel(
     static_assert(NSTAGE >= 2 && NSTAGE <= 4, "2 to 4 stages");
     static_assert((NSTAGE - 2) * LPW <= 63, "vmcnt range");
 
+    // Epilogue staging: 32 fp32 rows of the wave tile + the wave's row statistics per wave.  It lives
+    // in the array of stage 1, which is made large enough for all waves: stage 0 receives the next
+    // tile's first K slice meanwhile, and being a different array the compiler knows that the
+    // epilogue's LDS traffic need not wait for those copies.
+    constexpr int EPW = (32 * (WN * 4 + 16) + WM * 8 + 255) / 256 * 256;  // bytes per wave
     __shared__ __attribute__((aligned(1024))) unsigned char stage0[STAGE];
-    __shared__ __attribute__((aligned(1024))) unsigned char stage1[STAGE];
+    __shared__ __attribute__((aligned(1024))) unsigned char stage1[STAGE > NW * EPW ? STAGE : NW * EPW];
     __shared__ __attribute__((aligned(1024))) unsigned char stage2[NSTAGE > 2 ? STAGE : 16];
     __shared__ __attribute__((aligned(1024))) unsigned char stage3[NSTAGE > 3 ? STAGE : 16];
 
@@ -108,23 +113,30 @@ __global__ __launch_bounds__(WGM* WGN * 64, WGM* WGN / 4) void gemm_bf16_kernel(
     // grid in groups of `gm` row panels, n-major inside a group (m fastest): the ~32 tiles an XCD
     // runs at a time then share gm activation panels, which stay in its L2 while the weight
     // panels stream past, instead of re-reading the whole weight matrix for every row panel.
+    //
+    // Persistent workgroups: the grid is one workgroup per CU; workgroup (x, j) of XCD x walks
+    // positions j, j + per_xcd, ... of that XCD's range, so the tiles an XCD runs at a time are the
+    // same as with one workgroup per tile, but the first K slice of the next tile is fetched while
+    // the epilogue of the current one runs.
     const int nblk = tiles_m * tiles_n;
-    int bid = blockIdx.x;
-    {
-        const int x = bid & 7, j = bid >> 3;
-        const int q = nblk >> 3, r = nblk & 7;  // XCD x owns q (+1 if x < r) tiles
-        bid = x * q + (x < r ? x : r) + j;
+    const int xcd = blockIdx.x & 7, per_xcd = gridDim.x >> 3;
+    const int xq = nblk >> 3, xr = nblk & 7;  // XCD x owns xq (+1 if x < xr) tiles
+    const int x_cnt = xq + (xcd < xr ? 1 : 0), x_start = xcd * xq + (xcd < xr ? xcd : xr);
+    int seq = blockIdx.x >> 3;
+    if (seq >= x_cnt) return;  // whole workgroup, before any barrier
+#define RS_GEMM_DECODE(seq_, m0_, n0_)                                                                    \
+    {                                                                                                     \
+        const int bid_ = x_start + (seq_);                                                                \
+        const int per_group_ = gm * tiles_n;                                                              \
+        const int grp_ = bid_ / per_group_, rem_ = bid_ - grp_ * per_group_;                              \
+        const int first_m_ = grp_ * gm;                                                                   \
+        const int gsz_ = min(tiles_m - first_m_, gm);                                                     \
+        const int tn_ = rem_ / gsz_;                                                                      \
+        (n0_) = tn_ * BN;                                                                                 \
+        (m0_) = (first_m_ + rem_ - tn_ * gsz_) * BM;                                                      \
     }
-    int tile_m, tile_n;
-    {
-        const int per_group = gm * tiles_n;
-        const int grp = bid / per_group, rem = bid - grp * per_group;
-        const int first_m = grp * gm;
-        const int gsz = min(tiles_m - first_m, gm);
-        tile_n = rem / gsz;
-        tile_m = first_m + rem - tile_n * gsz;
-    }
-    const int m0 = tile_m * BM, n0 = tile_n * BN;
+    int m0, n0;
+    RS_GEMM_DECODE(seq, m0, n0)
 
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);  // wave-uniform: LDS copy targets go to M0
@@ -141,8 +153,8 @@ __global__ __launch_bounds__(WGM* WGN * 64, WGM* WGN / 4) void gemm_bf16_kernel(
     //    64-byte rows (BK 32): f(r) = (r >> 2) & 3         (r & 3 picks the quarter line)
     // global -> LDS: wave copy i of wave w fills rows (NW*i + w)*RPI .. +RPI-1 (lane l: row l / SPR,
     // slot l % SPR), so the lane fetches chunk (l % SPR) ^ f(row).
-    const __amdgpu_buffer_rsrc_t rs_a = make_rsrc(a + (int64_t)m0 * K, (int64_t)(M - m0) * K * 2);
-    const __amdgpu_buffer_rsrc_t rs_w = make_rsrc(wt + (int64_t)n0 * K, (int64_t)(N - n0) * K * 2);
+    __amdgpu_buffer_rsrc_t rs_a = make_rsrc(a + (int64_t)m0 * K, (int64_t)(M - m0) * K * 2);
+    __amdgpu_buffer_rsrc_t rs_w = make_rsrc(wt + (int64_t)n0 * K, (int64_t)(N - n0) * K * 2);
     const int ld_r = lane / SPR, ld_p = lane % SPR;
     int voff_e, voff_o;  // lane byte offset for even / odd copy index i
     if (SPR == 8) {  // row >> 3 = NW*i + w
@@ -152,44 +164,6 @@ __global__ __launch_bounds__(WGM* WGN * 64, WGM* WGN / 4) void gemm_bf16_kernel(
         voff_e = voff_o = ((wave * RPI + ld_r) * K + ((ld_p ^ ((ld_r >> 2) & 3)) << 3)) * 2;
     }
     const int pass_bytes = NW * RPI * K * 2;
-
-    // LayerNorm-folded epilogues: fetch the (mean, rstd) of this wave's WM rows now (lane l: rows
-    // l, l + 64, ...), so that the loads are long done when the epilogue wants them
-    constexpr bool LN_EPI = EPI == EPI_LN_BIAS || EPI == EPI_LN_BIAS_GELU;
-    float2 row_st[LN_EPI ? WM / 64 : 1];
-    if (LN_EPI) {
-#pragma unroll
-        for (int h = 0; h < WM / 64; ++h) {
-            const int m = m0 + wm * WM + h * 64 + lane;
-            row_st[h] = m < M ? reinterpret_cast<const float2*>(ln.stats)[m] : make_float2(0.f, 0.f);
-        }
-    }
-
-    // Likewise the per-column epilogue vectors of the lane's 8 output features (on the way out a
-    // row of the wave tile is covered by WN / 8 lanes, 8 consecutive features each).
-    const int ep_oc = (lane % (WN / 8)) * 8;
-    const int ep_n = n0 + wn * WN + ep_oc;
-    const bool ep_n_ok = ep_n < N;  // N % 8 == 0
-    uint4 bias_raw = make_uint4(0u, 0u, 0u, 0u);
-    float ln_bv[LN_EPI ? 8 : 1], ln_cs[LN_EPI ? 8 : 1];
-    if (LN_EPI) {
-#pragma unroll
-        for (int e = 0; e < 8; ++e) { ln_bv[e] = 0.f; ln_cs[e] = 0.f; }
-        if (ep_n_ok) {
-            Elem<float>::load8(ln.bias + ep_n, reinterpret_cast<float(&)[8]>(ln_bv));
-            Elem<float>::load8(ln.colsum + ep_n, reinterpret_cast<float(&)[8]>(ln_cs));
-        }
-    } else if (bias && ep_n_ok) {
-        bias_raw = *reinterpret_cast<const uint4*>(bias + ep_n);
-    }
-
-    f32x16 acc[TN][TM];
-#pragma unroll
-    for (int i = 0; i < TN; ++i)
-#pragma unroll
-        for (int j = 0; j < TM; ++j)
-#pragma unroll
-            for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
 
     const int S = K / BK;                                   // real slices
     const int S_pad = (S + NSTAGE - 1) / NSTAGE * NSTAGE;   // loop trip count (zero slices at the end)
@@ -257,10 +231,52 @@ __global__ __launch_bounds__(WGM* WGN * 64, WGM* WGN / 4) void gemm_bf16_kernel(
         RS_GEMM_INTERLEAVE(1)                                                                             \
     }
 
-    // prologue: slice 0 lands, slice 1 is on its way, the first fragments are in registers
     static_assert(NSTAGE == 2 && KK == 4, "the slice schedule below is written for two stages of 64-wide slices");
+    RS_GEMM_DMA(stage0, 0)  // first K slice of the first tile
+
+    for (;;) {  // one tile per iteration
+    // LayerNorm-folded epilogues: fetch the (mean, rstd) of this wave's WM rows now (lane l: rows
+    // l, l + 64, ...), so that the loads are long done when the epilogue wants them
+    constexpr bool LN_EPI = EPI == EPI_LN_BIAS || EPI == EPI_LN_BIAS_GELU;
+    float2 row_st[LN_EPI ? WM / 64 : 1];
+    if (LN_EPI) {
+#pragma unroll
+        for (int h = 0; h < WM / 64; ++h) {
+            const int m = m0 + wm * WM + h * 64 + lane;
+            row_st[h] = m < M ? reinterpret_cast<const float2*>(ln.stats)[m] : make_float2(0.f, 0.f);
+        }
+    }
+
+    // Likewise the per-column epilogue vectors of the lane's 8 output features (on the way out a
+    // row of the wave tile is covered by WN / 8 lanes, 8 consecutive features each).
+    const int ep_oc = (lane % (WN / 8)) * 8;
+    const int ep_n = n0 + wn * WN + ep_oc;
+    const bool ep_n_ok = ep_n < N;  // N % 8 == 0
+    uint4 bias_raw = make_uint4(0u, 0u, 0u, 0u);
+    float ln_bv[LN_EPI ? 8 : 1], ln_cs[LN_EPI ? 8 : 1];
+    if (LN_EPI) {
+#pragma unroll
+        for (int e = 0; e < 8; ++e) { ln_bv[e] = 0.f; ln_cs[e] = 0.f; }
+        if (ep_n_ok) {
+            Elem<float>::load8(ln.bias + ep_n, reinterpret_cast<float(&)[8]>(ln_bv));
+            Elem<float>::load8(ln.colsum + ep_n, reinterpret_cast<float(&)[8]>(ln_cs));
+        }
+    } else if (bias && ep_n_ok) {
+        bias_raw = *reinterpret_cast<const uint4*>(bias + ep_n);
+    }
+
+    f32x16 acc[TN][TM];
+#pragma unroll
+    for (int i = 0; i < TN; ++i)
+#pragma unroll
+        for (int j = 0; j < TM; ++j)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
+
+    // slice 0 has been requested (before the loop, or under the previous tile's epilogue); when it
+    // has landed and every wave is past that epilogue, slice 1 goes on its way and the first
+    // fragments into registers
     Frags<TN, TM> f0, f1;
-    RS_GEMM_DMA(stage0, 0)
     __builtin_amdgcn_s_waitcnt(vmcnt_imm(0));
     __syncthreads();
     RS_GEMM_DMA(stage1, 1)
@@ -271,11 +287,21 @@ __global__ __launch_bounds__(WGM* WGN * 64, WGM* WGN / 4) void gemm_bf16_kernel(
         RS_GEMM_SLICE(stage1, stage0, t + 1)
     }
     __builtin_amdgcn_s_waitcnt(vmcnt_imm(0));  // the trailing (empty) copies too: the stages get reused
-#undef RS_GEMM_DMA
-#undef RS_GEMM_LOAD_FRAGS
-#undef RS_GEMM_MFMA
-#undef RS_GEMM_INTERLEAVE
-#undef RS_GEMM_SLICE
+    __syncthreads();  // every wave is done with the K-loop stages
+
+
+    // next tile: its first K slice streams into stage0 while the epilogue runs (past the last tile
+    // the copies are aimed outside the resource and deliver zeros nobody reads).  The copies are
+    // issued inside the epilogue, right after its first residual loads: loads return in order,
+    // and those must not queue up behind 64 KB of copies.
+    const int m0_cur = m0, n0_cur = n0;
+    seq += per_xcd;
+    const bool more = seq < x_cnt;
+    if (more) {
+        RS_GEMM_DECODE(seq, m0, n0)
+        rs_a = make_rsrc(a + (int64_t)m0 * K, (int64_t)(M - m0) * K * 2);
+        rs_w = make_rsrc(wt + (int64_t)n0 * K, (int64_t)(N - n0) * K * 2);
+    }
 
     // ---- epilogue, staged through LDS so that global traffic is row-contiguous.
     // Accumulator layout: lane (l32, g) owns token row l32 of each 32-row group; register
@@ -284,13 +310,12 @@ __global__ __launch_bounds__(WGM* WGN * 64, WGM* WGN / 4) void gemm_bf16_kernel(
     // free), then re-reads it with 16 lanes per row, 8 consecutive features per lane; bias,
     // GELU, residual, the shift partial sums and the bf16 rounding happen on that layout, and
     // every global load/store instruction covers whole 16 * WN / 8-byte row segments.
-    __syncthreads();  // every wave is done with the K-loop stages: reuse them
     {
         constexpr int PITCH = WN * 4 + 16;         // bytes per staged row
         constexpr int LPR = WN / 8;                // lanes per row on the way out (16 for WN = 128)
         constexpr int RPS = 64 / LPR;              // rows per step
-        static_assert(32 * PITCH + WM * 8 <= 2 * STAGE / NW, "epilogue staging does not fit");
-        unsigned char* ep = ((wave & 1) ? stage1 : stage0) + (wave >> 1) * (2 * STAGE / NW);
+        static_assert(32 * PITCH + WM * 8 <= EPW, "epilogue staging does not fit");
+        unsigned char* ep = stage1 + wave * EPW;
         float2* ep_st = reinterpret_cast<float2*>(ep + 32 * PITCH);  // the wave's row statistics
         if (LN_EPI) {
 #pragma unroll
@@ -323,11 +348,12 @@ __global__ __launch_bounds__(WGM* WGN * 64, WGM* WGN / 4) void gemm_bf16_kernel(
             if (RES) {
 #pragma unroll
                 for (int st = 0; st < 32 / RPS; ++st) {
-                    const int m = m0 + wm * WM + j * 32 + st * RPS + orow;
+                    const int m = m0_cur + wm * WM + j * 32 + st * RPS + orow;
                     res_raw[st] = (m < M && n_ok) ? *reinterpret_cast<const uint4*>(res + (int64_t)m * N + n)
                                                   : make_uint4(0u, 0u, 0u, 0u);
                 }
             }
+            if (j == 0) RS_GEMM_DMA(stage0, more ? 0 : S)
 #pragma unroll
             for (int i = 0; i < TN; ++i)
 #pragma unroll
@@ -338,7 +364,7 @@ __global__ __launch_bounds__(WGM* WGN * 64, WGM* WGN / 4) void gemm_bf16_kernel(
 #pragma unroll
             for (int st = 0; st < 32 / RPS; ++st) {
                 const int r = st * RPS + orow;
-                const int m = m0 + wm * WM + j * 32 + r;
+                const int m = m0_cur + wm * WM + j * 32 + r;
                 const bool ok = m < M && n_ok;
                 float v[8];
                 {
@@ -400,7 +426,7 @@ __global__ __launch_bounds__(WGM* WGN * 64, WGM* WGN / 4) void gemm_bf16_kernel(
                         if (DIST == RS_DIST_COS) { p1 += __shfl_xor(p1, off, 64); p2 += __shfl_xor(p2, off, 64); }
                     }
                     if ((lane % LPR) == 0 && m < M) {
-                        const int slot = (n0 + wn * WN) / WN;
+                        const int slot = (n0_cur + wn * WN) / WN;
                         float* dst = partials + ((int64_t)m * slots + slot) * kShiftLanes;
                         dst[0] = p0;
                         if (DIST == RS_DIST_COS) { dst[1] = p1; dst[2] = p2; }
@@ -409,6 +435,14 @@ __global__ __launch_bounds__(WGM* WGN * 64, WGM* WGN / 4) void gemm_bf16_kernel(
             }
         }
     }
+        if (!more) break;
+    }  // tiles
+#undef RS_GEMM_DMA
+#undef RS_GEMM_DECODE
+#undef RS_GEMM_LOAD_FRAGS
+#undef RS_GEMM_MFMA
+#undef RS_GEMM_INTERLEAVE
+#undef RS_GEMM_SLICE
 }
 
 // Tile configuration of the bf16 GEMM: BM, BN, BK, NSTAGE, waves along tokens, waves along features.
@@ -429,8 +463,16 @@ static hipError_t launch_bf16(const void* a, const void* wt, const void* bias, c
     const int tiles_m = (int)((M + C::BM - 1) / C::BM), tiles_n = (N + C::BN - 1) / C::BN;
     const int slots = (tiles_n * C::BN) / C::WN;
     const int gm = 8;  // row panels per tile group: their activations stay in an XCD's L2 during a sweep over n
+    // one workgroup per CU (8 XCDs x CUs / 8), fewer when an XCD's share of the tiles is smaller
+    static const int cus = [] {
+        int dev = 0, n = 0;
+        if (hipGetDevice(&dev) != hipSuccess || hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n < 8) n = 256;
+        return n;
+    }();
+    const int share = (tiles_m * tiles_n + 7) / 8;
+    const int per_xcd = share < cus / 8 ? share : cus / 8;
     hipLaunchKernelGGL((gemm_bf16_kernel<C::BM, C::BN, C::BK, C::NSTAGE, C::WGM, C::WGN, EPI, DIST>),
-                       dim3(tiles_m * tiles_n), dim3(C::WGM * C::WGN * 64), 0, s, (const bf16raw*)a,
+                       dim3(8 * per_xcd), dim3(C::WGM * C::WGN * 64), 0, s, (const bf16raw*)a,
                        (const bf16raw*)wt, (const bf16raw*)bias, (const bf16raw*)res, (bf16raw*)out, partials,
                        (const bf16raw*)ref, post ? 1 : 0, ln, (int)M, N, K, tiles_m, tiles_n, slots, gm);
     return hipGetLastError();
