@@ -111,6 +111,45 @@ def test_fullsize_vit_b_block_sampled_images():
     assert e_y < TOL["bf16"]
 
 
+@pytest.mark.parametrize("name,block,sample", [("video_vit_b16", 2, [0, 7]), ("video_vit_l14", 4, [3]),
+                                               ("umt_b_ret", 1, [19])])
+def test_fullsize_video_block_sampled_clips(name, block, sample):
+    """First pruning block of the video workloads at full size (8 x 1569 x 768 keep half; 4 x 4097
+    x 1024 keep 70 %; 20 x 2352 x 768 without class token keep 80 %): long-sequence attention
+    plans, LayerNorm-folded GEMMs and the prune pass together.  The checker recomputes the
+    sampled clips; invariants cover the rest."""
+    wl = si.WORKLOADS[name]
+    B, N, D, H, Dm, P = wl["B"], wl["N"], wl["D"], wl["H"], wl["Dm"], wl.get("n_prefix", 1)
+    n_keep = rs.keep_counts(N, P, wl["blocks"], wl["prune"])[block - 1][1]
+    assert n_keep < N - P
+    _say("full-size block", name, B, N, D, "keep", n_keep)
+    x = host_round(si.tokens(0, B, N, D, 0.3), "bf16")
+    w = {k: host_round(v, "bf16") for k, v in si.block_weights(0, block - 1, D, Dm).items()}
+    dw = {k: to_dev(v, "bf16") for k, v in w.items()}
+    dx = to_dev(x, "bf16")
+    cfg = rs.make_cfg(B, N, D, H, Dm, P, n_keep, torch.bfloat16)
+    packed = torch.empty(rs.rs_packed_weights_size(cfg), dtype=torch.uint8, device="cuda")
+    rs.rs_pack_weights(cfg, rs.make_weights(dw), packed)
+    ws = torch.empty(rs.rs_block_workspace_size(cfg), dtype=torch.uint8, device="cuda")
+    y = torch.full((B, P + n_keep, D), float("nan"), device="cuda", dtype=torch.bfloat16)
+    kept = torch.full((B, P + n_keep), -1, device="cuda", dtype=torch.int32)
+    scores = torch.empty((B, N), device="cuda", dtype=torch.float32)
+    rs.rs_block_fwd(cfg, rs.make_weights(dw, packed), dx, y, kept, scores, ws)
+    torch.cuda.synchronize()
+    kept_h, s = kept.cpu().numpy(), to_host(scores)
+    assert np.isfinite(to_host(y)).all() and np.isfinite(s).all()
+    assert (np.diff(kept_h, axis=1) > 0).all() and kept_h.max() < N and kept_h.min() >= 0
+    if P:
+        assert (kept_h[:, 0] == 0).all()
+    np.testing.assert_array_equal(kept_h, oracle.topk(s, P, n_keep))   # exact on the GPU's scores
+    ref = oracle.block(x[sample], w, H)
+    e_s = norm_err(s[sample], ref["scores"])
+    exact = check_kept_admissible(kept_h[sample], s[sample], ref["scores"], P, n_keep)
+    e_y = norm_err(to_host(y)[sample], oracle.gather(ref["xhat"], kept_h[sample]))
+    _say("  score err %.3e, y err %.3e, kept exact on %.0f%% of sampled clips" % (e_s, e_y, 100 * exact))
+    assert e_s < TOL["bf16"] and e_y < TOL["bf16"]
+
+
 @pytest.mark.parametrize("B,N,H", [(4, 4097, 16), (8, 1569, 12)])
 def test_fullsize_video_attention_sampled_rows(B, N, H):
     """Joint space-time attention at the video workloads' sizes: the checker recomputes sampled
