@@ -147,6 +147,12 @@ hipError_t launch_shift_scores(rs_dtype dt, rs_dist dist, const void* f_out, con
 hipError_t launch_finalize_scores(rs_dist dist, const float* partials, int slots, float* scores,
                                   int64_t M, hipStream_t s);
 // per image: the n_keep highest scores among tokens >= n_prefix, ascending kept_idx[B, K]
+// the two steps above in one launch (a real selection only: n_keep < N - n_prefix, n_keep > 0;
+// N must pass select_from_partials_fits)
+bool select_from_partials_fits(int N);
+hipError_t launch_select_from_partials(rs_dist dist, const float* partials, int slots, float* scores,
+                                       int32_t* kept_idx, int B, int N, int n_prefix, int n_keep,
+                                       hipStream_t s);
 hipError_t launch_select(const float* scores, int32_t* kept_idx, int B, int N, int n_prefix,
                          int n_keep, hipStream_t s);
 // out[b, j, :] = src[b, kept_idx[b, j], :]

@@ -122,16 +122,39 @@ __device__ __forceinline__ int block_scan_incl(int v, int* s_wave /*[4]*/, int t
     return v + add;
 }
 
-__global__ __launch_bounds__(256) void select_kernel(const float* __restrict__ scores,
+// With `partials` the scores are first formed from the GEMM epilogue's per-row slots (added in
+// slot order, as finalize_scores_kernel does), kept in LDS for the selection and written to
+// `scores`: the block's prune pass needs no separate score launch.  N * 4 bytes of dynamic LDS.
+__global__ __launch_bounds__(256) void select_kernel(float* __restrict__ scores,
                                                      int32_t* __restrict__ kept_idx, int N,
-                                                     int n_prefix, int n_keep) {
+                                                     int n_prefix, int n_keep,
+                                                     const float* __restrict__ partials, int slots, int dist) {
     __shared__ int hist[256];
     __shared__ int s_wave[4];
     __shared__ uint32_t s_prefix;
     __shared__ int s_remaining;
+    extern __shared__ float s_scores[];
     const int tid = threadIdx.x;
     const float* sc = scores + (int64_t)blockIdx.x * N;
     int32_t* out = kept_idx + (int64_t)blockIdx.x * (n_prefix + n_keep);
+    if (partials) {
+        for (int i = tid; i < N; i += 256) {
+            const float* p = partials + ((int64_t)blockIdx.x * N + i) * slots * kShiftLanes;
+            float p0 = 0.f, p1 = 0.f, p2 = 0.f;
+            for (int sl = 0; sl < slots; ++sl) {
+                p0 += p[sl * kShiftLanes];
+                if (dist == RS_DIST_COS) { p1 += p[sl * kShiftLanes + 1]; p2 += p[sl * kShiftLanes + 2]; }
+            }
+            float r;
+            if (dist == RS_DIST_L2) r = sqrtf(p0);
+            else if (dist == RS_DIST_L1) r = p0;
+            else r = 1.0f - p0 / (sqrtf(p1) * sqrtf(p2));
+            s_scores[i] = r;
+            scores[(int64_t)blockIdx.x * N + i] = r;
+        }
+        sc = s_scores;
+        __syncthreads();
+    }
 
     for (int i = tid; i < n_prefix; i += 256) out[i] = i;
     if (n_keep == 0) return;
@@ -201,8 +224,20 @@ hipError_t launch_select(const float* scores, int32_t* kept_idx, int B, int N, i
         const int64_t tot = (int64_t)B * N;
         hipLaunchKernelGGL(iota_kernel, dim3((unsigned)((tot + 255) / 256)), dim3(256), 0, s, kept_idx, B, N);
     } else {
-        hipLaunchKernelGGL(select_kernel, dim3(B), dim3(256), 0, s, scores, kept_idx, N, n_prefix, n_keep);
+        hipLaunchKernelGGL(select_kernel, dim3(B), dim3(256), 0, s, const_cast<float*>(scores), kept_idx, N,
+                           n_prefix, n_keep, (const float*)nullptr, 0, 0);
     }
+    return hipGetLastError();
+}
+
+bool select_from_partials_fits(int N) { return N <= 12288; }  // scores of one image in LDS
+
+hipError_t launch_select_from_partials(rs_dist dist, const float* partials, int slots, float* scores,
+                                       int32_t* kept_idx, int B, int N, int n_prefix, int n_keep,
+                                       hipStream_t s) {
+    if (B == 0) return hipSuccess;
+    hipLaunchKernelGGL(select_kernel, dim3(B), dim3(256), (size_t)N * sizeof(float), s, scores, kept_idx, N,
+                       n_prefix, n_keep, partials, slots, (int)dist);
     return hipGetLastError();
 }
 

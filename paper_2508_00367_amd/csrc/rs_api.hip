@@ -471,6 +471,13 @@ rs_status rs_block_fwd(const rs_block_cfg* cfg, const rs_block_weights* w, const
     const void* ref = c.op == RS_SHIFT_BLOCK ? x : c.op == RS_SHIFT_MLP_NORMED ? (const void*)u : nullptr;
     RS_LAUNCH_K(K_GEMM_FC2, s, launch_gemm(dt, fc2_scores ? EPI_BIAS_RES_SHIFT : EPI_BIAS_RES, c.dist, hid, w2, w->b_fc2, x1,
                           xhat, partials, ref, post, M, D, Dm, s));
+    if (prune && c.n_keep > 0 && select_from_partials_fits(c.N)) {
+        // scores straight from the epilogue's partial sums inside the selection kernel
+        RS_LAUNCH_K(K_SELECT, s, launch_select_from_partials(c.dist, partials, L.slots, sc, kept_idx, c.B, c.N, c.n_prefix,
+                                                           c.n_keep, s));
+        RS_LAUNCH_K(K_GATHER, s, launch_gather(dt, xhat, kept_idx, y, c.B, c.N, K, D, s));
+        return RS_OK;
+    }
     if (want_scores) RS_LAUNCH_K(K_SCORE, s, launch_finalize_scores(c.dist, partials, L.slots, sc, M, s));
     // keep the n_keep highest-shift tokens (plus the prefix) and compact them
     RS_LAUNCH_K(K_SELECT, s, launch_select(sc, kept_idx, c.B, c.N, c.n_prefix, c.n_keep, s));
