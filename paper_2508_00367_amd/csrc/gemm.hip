@@ -95,8 +95,7 @@ __global__ __launch_bounds__(WGM* WGN * 64, WGM* WGN / 4) void gemm_bf16_kernel(
     static_assert(NW == 4 || NW == 8, "4 or 8 waves");
     static_assert(BM % (RPI * NW) == 0 && BN % (RPI * NW) == 0, "tile rows must split evenly over the wave copies");
     static_assert(BK == 32 || BK == 64, "K slice of 32 or 64");
-    static_assert(NSTAGE >= 2 && NSTAGE <= 4, "2 to 4 stages");
-    static_assert((NSTAGE - 2) * LPW <= 63, "vmcnt range");
+    static_assert(NSTAGE == 2, "two stages (deeper rings of narrower slices measured no better)");
 
     // Epilogue staging: 32 fp32 rows of the wave tile + the wave's row statistics per wave.  It lives
     // in the array of stage 1, which is made large enough for all waves: stage 0 receives the next
@@ -105,8 +104,6 @@ __global__ __launch_bounds__(WGM* WGN * 64, WGM* WGN / 4) void gemm_bf16_kernel(
     constexpr int EPW = (32 * (WN * 4 + 16) + WM * 8 + 255) / 256 * 256;  // bytes per wave
     __shared__ __attribute__((aligned(1024))) unsigned char stage0[STAGE];
     __shared__ __attribute__((aligned(1024))) unsigned char stage1[STAGE > NW * EPW ? STAGE : NW * EPW];
-    __shared__ __attribute__((aligned(1024))) unsigned char stage2[NSTAGE > 2 ? STAGE : 16];
-    __shared__ __attribute__((aligned(1024))) unsigned char stage3[NSTAGE > 3 ? STAGE : 16];
 
     // Tile order.  Consecutive workgroup ids go round-robin to the 8 XCDs, each with its own
     // 4 MB L2, so XCD x takes a contiguous range of the tile sequence.  The sequence walks the tile
@@ -462,7 +459,10 @@ static hipError_t launch_bf16(const void* a, const void* wt, const void* bias, c
     using C = GemmCfg;
     const int tiles_m = (int)((M + C::BM - 1) / C::BM), tiles_n = (N + C::BN - 1) / C::BN;
     const int slots = (tiles_n * C::BN) / C::WN;
-    const int gm = 8;  // row panels per tile group: their activations stay in an XCD's L2 during a sweep over n
+#ifndef RS_GEMM_GM
+#define RS_GEMM_GM 8
+#endif
+    const int gm = RS_GEMM_GM;  // row panels per tile group: their activations stay in an XCD's L2 during a sweep over n
     // one workgroup per CU (8 XCDs x CUs / 8), fewer when an XCD's share of the tiles is smaller
     static const int cus = [] {
         int dev = 0, n = 0;
@@ -620,6 +620,7 @@ hipError_t launch_gemm(rs_dtype dt, GemmEpilogue epi, rs_dist dist, const void* 
             if (dist == RS_DIST_L2) return launch_any<EPI_BIAS_RES_SHIFT, RS_DIST_L2>(dt, a, w, bias, res, out, partials, ref, post, M, N, K, s);
             if (dist == RS_DIST_L1) return launch_any<EPI_BIAS_RES_SHIFT, RS_DIST_L1>(dt, a, w, bias, res, out, partials, ref, post, M, N, K, s);
             return launch_any<EPI_BIAS_RES_SHIFT, RS_DIST_COS>(dt, a, w, bias, res, out, partials, ref, post, M, N, K, s);
+        default: break;  // the LayerNorm-folded epilogues go through launch_gemm_ln
     }
     return hipErrorInvalidValue;
 }
