@@ -428,7 +428,9 @@ __global__ __launch_bounds__(512, 2) void attention_bf16_tail_kernel(
 // barrier, then wave w runs query rows 32w .. 32w+31 against all key tiles without further
 // synchronisation.  Against the tiled kernel this reads K and V once instead of once per
 // query tile and has no per-tile barrier or staging latency; two workgroups share a CU, so
-// one wave's exp/max/sum work runs under another's MFMAs.
+// one's load phase runs under the other's tile loop.  The tile loop itself is bound by
+// instruction issue (plain ALU and matrix instructions of a SIMD's waves do not overlap), so
+// it carries no masking work outside the last key tile.
 // LDS: K rows of 128 bytes, chunk c of row r in slot c ^ ((r ^ r>>3) & 7); V^T rows of 512
 // bytes (256 key positions), 16-byte chunk c of channel row d in slot c ^ ((d ^ d>>3) & 15):
 // both the 16-lane operand reads and the transposing 4-byte writes are bank-conflict free.
