@@ -38,8 +38,9 @@ def parse():
     ap.add_argument("--unpruned", action="store_true", help="run the same stack without pruning")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-sample", type=int, default=0, help="images for the CPU baseline (0 = auto)")
-    ap.add_argument("--stress", action="store_true",
-                    help="also time rs_shift_topk alone on an HBM-resident shape (B=4096, N=197, D=768)")
+    ap.add_argument("--no-extras", action="store_true",
+                    help="skip the two side measurements: rs_shift_topk alone on an HBM-resident shape (B=4096, "
+                         "N=197, D=768) and rs_attention_fwd alone at the long video shape (4 x 4097 tokens x 16 heads)")
     ap.add_argument("--graph", action="store_true",
                     help="capture one step into a HIP graph and time its replays (for the small, launch-bound "
                          "workloads; the per-kernel replay stays eager)")
@@ -220,7 +221,7 @@ def main():
     }
 
     # ---- optional: the prune pass alone on an HBM-resident shape ----
-    if a.stress:
+    if not a.no_extras:
         Bs, Ns, Ds, Ks = 4096, 197, 768, 177
         f_in = torch.randn((Bs, Ns, Ds), device=dev, dtype=tdt)
         f_out = f_in + 0.1 * torch.randn((Bs, Ns, Ds), device=dev, dtype=tdt)
@@ -240,6 +241,22 @@ def main():
         out["prune_stress"] = {"shape": [Bs, Ns, Ds, Ks], "ms": round(ts * 1e3, 4),
                                "GB/s": round(alg / ts / 1e9, 1), "frac_hbm": round(alg / ts / 1e9 / PEAK_HBM_GBS, 4)}
         del f_in, f_out, g
+        # fused attention alone at the long-sequence video shape (matrix-core utilisation of the core step)
+        Ba, Na, Ha = 4, 4097, 16
+        qkv = torch.randn((Ba, Na, 3, Ha, 64), device=dev, dtype=tdt)
+        oa = torch.empty((Ba, Na, Ha, 64), device=dev, dtype=tdt)
+        for _ in range(3):
+            rs.rs_attention_fwd(qkv[:, :, 0], qkv[:, :, 1], qkv[:, :, 2], oa, 0.125)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(20):
+            rs.rs_attention_fwd(qkv[:, :, 0], qkv[:, :, 1], qkv[:, :, 2], oa, 0.125)
+        torch.cuda.synchronize()
+        ta = (time.perf_counter() - t0) / 20
+        fa = 4.0 * Ba * Ha * Na * Na * 64
+        out["attention_long"] = {"shape": [Ba, Na, Ha, 64], "us": round(ta * 1e6, 1),
+                                 "TFLOP/s": round(fa / ta / 1e12, 1), "frac_mfma": round(fa / ta / 1e12 / PEAK_BF16_TFLOPS, 4)}
+        del qkv, oa
 
     if a.calib_copy_mb:
         src_c = torch.empty(a.calib_copy_mb << 20, dtype=torch.uint8, device=dev).fill_(1)
