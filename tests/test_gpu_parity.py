@@ -254,6 +254,15 @@ def test_block_operation_choice(op, dist, dtype):
     _check_block(x, w, 3, 1, 120, dtype, dist=dist, op=op)
 
 
+@pytest.mark.parametrize("dtype", ["bf16", "f32"])
+def test_block_widest_supported_rows(dtype):
+    """D = 4096 (the library's limit), 64 heads: the wide-row paths of the row-statistics /
+    LayerNorm kernels, 16 column tiles in the projection, 64 score slots per row."""
+    _say("block D=4096", dtype)
+    x, w = _block_inputs(13, 1, 40, 4096, 128, dtype, std=0.02, spread=0.3)
+    _check_block(x, w, 64, 1, 17, dtype)
+
+
 @pytest.mark.parametrize("pack", [False, True])
 def test_block_offset_rows_and_outlier_channels(pack):
     """Rows far from zero mean (offset 6 standard deviations) with two channels 30 times larger
