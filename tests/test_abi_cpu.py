@@ -59,6 +59,8 @@ def test_block_rejects_bad_config():
                      (dict(ln_eps=0.0), rs.RS_ERR_INVALID_ARG),
                      (dict(dtype=7), rs.RS_ERR_INVALID_ARG),
                      (dict(dist=9), rs.RS_ERR_INVALID_ARG),
+                     (dict(op=5), rs.RS_ERR_INVALID_ARG),           # beyond the five shift operations
+                     (dict(op=-1), rs.RS_ERR_INVALID_ARG),
                      (dict(B=-1), rs.RS_ERR_INVALID_ARG)]:
         cfg = _cfg(**kw)
         st = rs.lib().rs_block_fwd(ctypes.byref(cfg), ctypes.byref(w), FAKE, FAKE * 2, FAKE * 3, None,
@@ -130,6 +132,26 @@ def test_shift_topk_rejects_bad_arguments():
     assert call(g=2 * FAKE) == rs.RS_ERR_INVALID_ARG       # gathered aliases src (= f_in)
     assert call(dist=4) == rs.RS_ERR_INVALID_ARG
     assert call(B=0, fo=None) == rs.RS_OK
+
+
+def test_grid_line_prune_rejects_bad_arguments():
+    L = rs.lib()
+
+    def call(fo=FAKE, fi=2 * FAKE, src=None, B=2, H=6, W=5, C=16, R=4, Q=3, dist=0, dt=rs.RS_BF16,
+             sc=3 * FAKE, rsc=4 * FAKE, csc=5 * FAKE, kr=6 * FAKE, kc=7 * FAKE, g=8 * FAKE):
+        return L.rs_grid_line_prune(fo, fi, src, B, H, W, C, R, Q, dist, dt, sc, rsc, csc, kr, kc, g, None)
+
+    assert call(C=12) == rs.RS_ERR_INVALID_ARG
+    assert call(R=7) == rs.RS_ERR_INVALID_ARG              # more rows kept than there are
+    assert call(Q=-1) == rs.RS_ERR_INVALID_ARG
+    assert call(fi=None) == rs.RS_ERR_INVALID_ARG
+    assert call(rsc=None) == rs.RS_ERR_INVALID_ARG
+    assert call(kr=None) == rs.RS_ERR_INVALID_ARG
+    assert call(g=FAKE) == rs.RS_ERR_INVALID_ARG           # gathered aliases src (= f_out)
+    assert call(dist=3) == rs.RS_ERR_INVALID_ARG
+    assert call(dt=5) == rs.RS_ERR_INVALID_ARG
+    assert call(B=0, fo=None) == rs.RS_OK
+    assert "keep_rows" in rs.rs_last_error() or rs.rs_last_error() != ""
 
 
 def test_pack_weights_validation():
