@@ -215,8 +215,12 @@ RS_API rs_status rs_linear_fwd(const void *a, const void *w, const void *bias, c
  *     x1   = SA(LN(x)) + x             SA = fused attention + output projection
  *     mlp  = W2 GELU(W1 LN(x1) + b1) + b2        (exact-erf GELU)
  *     xhat = mlp + x1
- *     scores[b, i] = || mlp[b, i, :] - x1[b, i, :] ||_2      (cfg->dist)
+ *     scores[b, i] = D(f_out[b, i, :], f_in[b, i, :])   pair by cfg->op (default: mlp, x1),
+ *                                                        distance by cfg->dist (default L2)
  *     kept_idx, y  = selection and gather of xhat as in rs_shift_topk.
+ *   RS_BF16: the two LayerNorms are applied inside the GEMMs that follow them (their scale is
+ *   folded into the packed weights, mean and variance come from a row-statistics pass), so the
+ *   normalised rows are never written; results agree with the definition above to bf16 rounding.
  *   x        : [B, N, D] in.            y : [B, K, D] out, must not alias x.
  *   kept_idx : int32 [B, K] out.        scores : float [B, N] out, or NULL.
  *   workspace: rs_block_workspace_size(cfg) bytes, 256-byte aligned.
