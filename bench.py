@@ -41,6 +41,10 @@ def parse():
     ap.add_argument("--no-extras", action="store_true",
                     help="skip the two side measurements: rs_shift_topk alone on an HBM-resident shape (B=4096, "
                          "N=197, D=768) and rs_attention_fwd alone at the long video shape (4 x 4097 tokens x 16 heads)")
+    ap.add_argument("--streams", type=int, default=2,
+                    help="the batch is cut into this many equal parts, each run block by block on a HIP stream of "
+                         "its own: images are independent, and the parts' kernels fill each other's idle CUs "
+                         "(last rounds of the GEMMs, small kernels).  1 = the whole batch on one stream")
     ap.add_argument("--graph", action="store_true",
                     help="capture one step into a HIP graph and time its replays (for the small, launch-bound "
                          "workloads; the per-kernel replay stays eager)")
@@ -113,7 +117,28 @@ def main():
             src = dst
         return src
 
+    # the timed configuration: S parts of the batch on S streams (same kernels, same results)
+    S = min(a.streams, B) if (a.streams > 1 and not a.graph) else 1
     run = step
+    if S > 1:
+        parts, first = [], 0
+        for i in range(S):
+            Bp = B // S + (1 if i < B % S else 0)
+            cfgs_p = [rs.make_cfg(Bp, n_in, D, H, Dm, P, n_keep, tdt, op=op) for n_in, n_keep in sched]
+            parts.append(dict(x=x0[first:first + Bp], cfgs=cfgs_p,
+                              ws=torch.empty(max(rs.rs_block_workspace_size(c) for c in cfgs_p), dtype=torch.uint8, device=dev),
+                              bufs=[torch.empty((Bp, N, D), device=dev, dtype=tdt) for _ in range(2)],
+                              kept=torch.empty((Bp, N), device=dev, dtype=torch.int32), stream=torch.cuda.Stream()))
+            first += Bp
+
+        def step_parts():
+            src = [p["x"] for p in parts]
+            for l in range(L):
+                for i, p in enumerate(parts):
+                    dst = p["bufs"][l & 1]
+                    rs.rs_block_fwd(p["cfgs"][l], weights[l], src[i], dst, p["kept"], None, p["ws"], p["stream"])
+                    src[i] = dst
+        run = step_parts
     if a.graph:
         # the library neither allocates nor synchronises, so a whole step records as is
         side = torch.cuda.Stream()
@@ -218,7 +243,11 @@ def main():
         "kernels": kernels,
         "instrumented_ms_per_step": round(instr_ms_per_step, 4),
         "launch": "hip graph replay" if a.graph else "eager",
+        "streams": S,
     }
+    if S > 1:
+        out["roofline"]["measured_on"] = ("instrumented replay of the whole batch on one stream (a launch has the "
+                                          "chip to itself); the timed steps run %d parts of the batch on %d streams" % (S, S))
 
     # ---- optional: the prune pass alone on an HBM-resident shape ----
     if not a.no_extras:

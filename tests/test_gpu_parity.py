@@ -425,3 +425,48 @@ def test_grid_line_prune(dtype, dist, B, H, W, C, R, Q):
     check_kept_admissible(kr_h, r_, r_ref, 0, R)
     check_kept_admissible(kc_h, c_, c_ref, 0, Q)
     np.testing.assert_array_equal(to_host(g), oracle.grid_gather(src, kr_h, kc_h))
+
+
+def test_batch_parts_on_streams_equal_the_whole_batch():
+    """bench.py runs the batch as parts on separate HIP streams.  Images are independent and every
+    kernel's arithmetic per row is the same whatever the batch size, so the parts must reproduce
+    the whole-batch result bit for bit (two pruning blocks, 8 images as 2 x 4)."""
+    B, N, D, H, Dm, S = 8, 197, 192, 3, 768, 2
+    sched = rs.keep_counts(N, 1, 2, dict(kind="drop_pct", pct=20, after=[1, 2]))
+    x0 = to_dev(host_round(si.tokens(21, B, N, D, 0.3), "bf16"), "bf16")
+    blocks, keep = [], []
+    for l in range(2):
+        w = {k: to_dev(host_round(v, "bf16"), "bf16") for k, v in si.block_weights(21, l, D, Dm, 0.05).items()}
+        cfg = rs.make_cfg(B, N, D, H, Dm, 1, N - 1, torch.bfloat16)
+        packed = torch.empty(rs.rs_packed_weights_size(cfg), dtype=torch.uint8, device="cuda")
+        rs.rs_pack_weights(cfg, rs.make_weights(w), packed)
+        keep.append((w, packed))
+        blocks.append(rs.make_weights(w, packed))
+
+    def forward(x, stream):
+        Bx = x.shape[0]
+        cfgs = [rs.make_cfg(Bx, n_in, D, H, Dm, 1, n_keep, torch.bfloat16) for n_in, n_keep in sched]
+        ws = torch.empty(max(rs.rs_block_workspace_size(c) for c in cfgs), dtype=torch.uint8, device="cuda")
+        bufs = [torch.zeros((Bx, N, D), device="cuda", dtype=torch.bfloat16) for _ in range(2)]
+        kepts = [torch.zeros((Bx, N), device="cuda", dtype=torch.int32) for _ in range(2)]
+        src = x
+        for l in range(2):
+            rs.rs_block_fwd(cfgs[l], blocks[l], src, bufs[l], kepts[l], None, ws, stream)
+            src = bufs[l]
+        return bufs, kepts, ws
+
+    torch.cuda.synchronize()
+    whole_b, whole_k, _ws = forward(x0, torch.cuda.current_stream())
+    streams = [torch.cuda.Stream() for _ in range(S)]
+    Bp = B // S
+    outs = [forward(x0[i * Bp:(i + 1) * Bp], streams[i]) for i in range(S)]
+    torch.cuda.synchronize()
+    for l, (n_in, n_keep) in enumerate(sched):
+        K = 1 + n_keep
+        for i in range(S):
+            part_y = outs[i][0][l].view(-1)[:Bp * K * D].view(Bp, K, D)
+            part_k = outs[i][1][l].view(-1)[:Bp * K].view(Bp, K)
+            whole_y = whole_b[l].view(-1)[:B * K * D].view(B, K, D)[i * Bp:(i + 1) * Bp]
+            whole_kk = whole_k[l].view(-1)[:B * K].view(B, K)[i * Bp:(i + 1) * Bp]
+            assert torch.equal(part_k, whole_kk), (l, i)
+            assert torch.equal(part_y.view(torch.int16), whole_y.view(torch.int16)), (l, i)
