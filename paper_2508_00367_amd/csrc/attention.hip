@@ -9,11 +9,11 @@
 //                     accumulator: lane (q = lane%32, g = lane/32) holds, for its query q,
 //                     keys 8j + 4g + i  (register 4j + i)  of each 32-key block.
 //     O^T = V^T P^T   B operand = P taken straight from the S^T accumulator registers
-//                     (8 registers = the lane's 8 keys of a 16-key group), A operand = V^T
-//                     from LDS.  V is transposed on its way into LDS, with the keys of each
-//                     16-key group stored in the order the accumulator layout yields them
-//                     (position 8g + 4u + i  <->  key 8u + 4g + i), so a lane reads its 8
-//                     keys as one 16-byte vector.
+//                     (8 registers = the lane's 8 keys of a 16-key group), A operand = V^T.
+//                     V sits in LDS as it sits in memory, one row per key; the transposing
+//                     LDS read of gfx950 (ds_read_b64_tr_b16) hands a lane one channel at 4
+//                     keys, and two of them fetch the 8 keys in the order the accumulator
+//                     layout yields them (slot 4u + i  <->  key 8u + 4g + i of the group).
 // Row max / row sum need one exchange between the two half-waves per tile.
 //
 // fp32 path: one query row per thread, true fp32 products (parity configuration).
@@ -25,27 +25,28 @@ constexpr int ATT_BM = 256;  // query rows per workgroup (8 waves x 32)
 constexpr int ATT_BN = 64;   // keys per tile
 constexpr int DH = 64;
 
-// 16-byte chunk `c` (0..7) of 128-byte LDS row `r`; the XOR spreads both the 16-lane operand
-// reads and the transposed V writes over the 64 banks (rows r and r + 8 must differ).
+// 16-byte chunk `c` (0..7) of 128-byte LDS row `r` of a K tile; the XOR spreads the 16-lane
+// operand reads over the 64 banks.
 __device__ __forceinline__ int att_swz(int r, int c) { return r * 128 + (((c ^ r ^ (r >> 3)) & 7) << 4); }
 
 typedef __attribute__((address_space(3))) void* att_lds_ptr;
+typedef short v4i16 __attribute__((ext_vector_type(4)));
+typedef __attribute__((address_space(3))) v4i16* lds_v4i16;
 
-// 16-byte chunk `chunk` (0..31) of the 512-byte row of channel `d` in a resident V^T array of
-// 256 key positions (short-sequence kernel).
-__device__ __forceinline__ int vt_off(int d, int chunk) { return d * 512 + ((chunk ^ ((d ^ (d >> 3)) & 15)) << 4); }
+// Row-major V tile [64 keys][128 B]: 16-byte chunk c of key row r sits in slot c ^ att_vswz(r).  A
+// transposing read touches 4 consecutive key rows x 64 bytes per 32 lanes; flipping the 64-byte
+// half on every second pair of rows keeps those four rows on different banks.
+__device__ __forceinline__ int att_vswz(int r) { return ((r >> 1) & 1) << 2; }
 
 // QB query-row blocks of 32 rows against one resident tile of 64 keys: S^T = K Q^T, online
 // softmax in registers (one lane = one query row per block, half of the tile's keys),
-// O^T += V^T P^T.  Every K and V^T fragment read from LDS serves all QB blocks.
-// `sk`: K tile [64 keys][128 B] swizzled; `svt`: V^T tile [64 channels][64 key positions], or
-// (RESIDENT) the whole head's V^T [64 channels][256 key positions] with `vt_tile` = index of the
-// 64-key tile inside it.
-template <bool MASK, int QB, bool RESIDENT = false>
-__device__ __forceinline__ void att_tile(const unsigned char* sk, const unsigned char* svt,
+// O^T += V^T P^T.  Every K and V fragment read from LDS serves all QB blocks.
+// `sk`: K tile [64 keys][128 B] (att_swz); `sv`: V tile [64 keys][128 B] (att_vswz).
+template <bool MASK, int QB>
+__device__ __forceinline__ void att_tile(const unsigned char* sk, const unsigned char* sv,
                                          const bf16x8 (&qf)[QB][4], f32x16 (&oacc)[QB][2],
                                          float (&m_run)[QB], float (&l_run)[QB], int key0, int N,
-                                         float scale_log2e, int l32, int g, int vt_tile = 0) {
+                                         float scale_log2e, int l32, int g) {
     f32x16 sacc[QB][2];
 #pragma unroll
     for (int qb = 0; qb < QB; ++qb)
@@ -118,8 +119,21 @@ __device__ __forceinline__ void att_tile(const unsigned char* sk, const unsigned
             }
 #pragma unroll
         for (int db = 0; db < 2; ++db) {
-            const bf16x8 vf = *reinterpret_cast<const bf16x8*>(
-                svt + (RESIDENT ? vt_off(db * 32 + l32, 2 * (vt_tile * 4 + t) + g) : att_swz(db * 32 + l32, 2 * t + g)));
+            // V tile as it sits in memory, [64 keys][64 channels]: two transposing LDS reads
+            // (ds_read_b64_tr_b16) hand this lane its channel's values at 4 keys each.  Within a
+            // group of 16 lanes, lane s = 4 j + a points at key j, channels 4 a .. 4 a + 3, and
+            // lane L receives channel L of keys j = 0 .. 3.  The keys are taken in the order of
+            // the P operand: slot 4 u + j of this lane is key 16 t + 8 u + 4 g + j.
+            const int s16 = l32 & 15;
+            const int chunk = db * 4 + 2 * (l32 >> 4) + ((s16 & 3) >> 1);
+            union { v4i16 h[2]; bf16x8 v; } tr;
+#pragma unroll
+            for (int u = 0; u < 2; ++u) {
+                const int key = 16 * t + 8 * u + 4 * g + (s16 >> 2);
+                tr.h[u] = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
+                    (lds_v4i16)(sv + key * 128 + ((chunk ^ att_vswz(key)) << 4) + (s16 & 1) * 8));
+            }
+            const bf16x8 vf = tr.v;
 #pragma unroll
             for (int qb = 0; qb < QB; ++qb)
                 oacc[qb][db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, pf[qb].v, oacc[qb][db], 0, 0, 0);
@@ -131,10 +145,9 @@ __device__ __forceinline__ void att_tile(const unsigned char* sk, const unsigned
 
 // Long sequences: workgroup = 256 * QB query rows (8 waves, QB blocks of 32 rows each) of one
 // (image, head).  QB = 2 halves the LDS reads and the barriers per unit of work; which one is
-// launched depends on how the row count fills the workgroups.  K tiles stream
+// launched depends on how the row count fills the workgroups.  K and V tiles stream
 // global -> LDS directly (buffer_load ... lds, rows past N read as zero through the buffer
-// resource); V tiles go through registers because they are transposed on the way in.  Two
-// stages each; the copies of tile t+1 are issued before the MFMAs of tile t, one barrier per tile.
+// resource).  Two stages each; the copies of tile t+1 are issued before the MFMAs of tile t, one barrier per tile.
 template <int QB>
 __global__ __launch_bounds__(512, 2) void attention_bf16_kernel(
     const bf16raw* __restrict__ q, const bf16raw* __restrict__ k, const bf16raw* __restrict__ v,
@@ -156,7 +169,6 @@ __global__ __launch_bounds__(512, 2) void attention_bf16_kernel(
     const int b = head / H, h = head - b * H;
     const int q0 = (local % q_tiles) * (ATT_BM * QB) + wave * (32 * QB);
     const int64_t base = (int64_t)b * sb + (int64_t)h * sh;
-    const bf16raw* vb = v + base;
 
     // Q fragments: B operand, column = query row q0 + 32 qb + l32, k-slots = 8 channels 16*kk + 8*g ..
     bf16x8 qf[QB][4];
@@ -178,40 +190,24 @@ __global__ __launch_bounds__(512, 2) void attention_bf16_kernel(
     const int k_voff = (int)(((int64_t)(wave * 8 + k_lr) * sn + (((lane & 7) ^ k_lr ^ wave) << 3)) * 2);
     const int k_tile_bytes = (int)(ATT_BN * sn * 2);
 
-    // V staging: thread -> 4 channels (tid & 15) of the key pair at positions 2a, 2a+1 (a = tid >> 4);
-    // position p = 16T + 8g' + 4u + i  <->  key 16T + 8u + 4g' + i
-    const int v_dc = tid & 15, v_pos = 2 * (tid >> 4);
-    const int v_key = (v_pos & ~15) | (((v_pos >> 2) & 1) << 3) | (((v_pos >> 3) & 1) << 2) | (v_pos & 3);
-    uint2 v_reg[2];
+    // V copies: the same rows and lanes as K, chunk (l%8) ^ att_vswz(row) in slot l%8.
+    const __amdgpu_buffer_rsrc_t rs_v = __builtin_amdgcn_make_buffer_rsrc(
+        const_cast<bf16raw*>(v + base), 0, (int)(k_bytes < 0xffffffffll ? k_bytes : 0xffffffffll), 0x00020000);
+    const int v_voff = (int)(((int64_t)(wave * 8 + k_lr) * sn + (((lane & 7) ^ att_vswz(k_lr)) << 3)) * 2);
 
-#define ATT_LOAD_NEXT(SKn, kt_)                                                                          \
+#define ATT_LOAD_NEXT(SKn, SVn, kt_)                                                                     \
     {                                                                                                    \
         __builtin_amdgcn_raw_ptr_buffer_load_lds(rs_k, (att_lds_ptr)((SKn) + wave * 1024), 16, k_voff,    \
                                                  (kt_) * k_tile_bytes, 0, 0);                            \
-        _Pragma("unroll") for (int i = 0; i < 2; ++i) {                                                  \
-            const int kr = (kt_) * ATT_BN + v_key + i;                                                   \
-            uint2 t = make_uint2(0u, 0u); /* keys past the end contribute exact zeros */                 \
-            if (kr < N) t = *reinterpret_cast<const uint2*>(vb + (int64_t)kr * sn + v_dc * 4);           \
-            v_reg[i] = t;                                                                                \
-        }                                                                                                \
-    }
-#define ATT_STORE_V(SVn)                                                                                 \
-    {                                                                                                    \
-        const uint32_t w0[2] = {v_reg[0].x, v_reg[0].y}, w1[2] = {v_reg[1].x, v_reg[1].y};               \
-        _Pragma("unroll") for (int e = 0; e < 4; ++e) {                                                  \
-            const uint32_t lo = (e & 1) ? (w0[e >> 1] >> 16) : (w0[e >> 1] & 0xffffu);                   \
-            const uint32_t hi = (e & 1) ? (w1[e >> 1] & 0xffff0000u) : (w1[e >> 1] << 16);               \
-            const int d = v_dc * 4 + e;                                                                  \
-            *reinterpret_cast<uint32_t*>((SVn) + att_swz(d, v_pos >> 3) + (v_pos & 7) * 2) = lo | hi;    \
-        }                                                                                                \
+        __builtin_amdgcn_raw_ptr_buffer_load_lds(rs_v, (att_lds_ptr)((SVn) + wave * 1024), 16, v_voff,    \
+                                                 (kt_) * k_tile_bytes, 0, 0);                            \
     }
 // tile kt_ is resident in (SKc, SVc); tile kt_+1 is fetched into (SKn, SVn) meanwhile
 #define ATT_STEP(SKc, SVc, SKn, SVn, kt_, MASK_)                                                              \
     {                                                                                                    \
-        ATT_LOAD_NEXT(SKn, (kt_) + 1)                                                                    \
+        ATT_LOAD_NEXT(SKn, SVn, (kt_) + 1)                                                               \
         att_tile<MASK_, QB>(SKc, SVc, qf, oacc, m_run, l_run, (kt_) * ATT_BN, N, scale_log2e, l32, g);   \
-        ATT_STORE_V(SVn)                                                                                 \
-        __builtin_amdgcn_s_waitcnt(0x0F70); /* this wave's K copy has landed */                          \
+        __builtin_amdgcn_s_waitcnt(0x0F70); /* this wave's K and V copies have landed */                 \
         __syncthreads();                                                                                 \
     }
 
@@ -229,8 +225,7 @@ __global__ __launch_bounds__(512, 2) void attention_bf16_kernel(
     }
 
     const int KT = (N + ATT_BN - 1) / ATT_BN;
-    ATT_LOAD_NEXT(sk0, 0)
-    ATT_STORE_V(sv0)
+    ATT_LOAD_NEXT(sk0, sv0, 0)
     __builtin_amdgcn_s_waitcnt(0x0F70);
     __syncthreads();
     const int KF = N / ATT_BN;  // tiles without padding keys
@@ -244,7 +239,6 @@ __global__ __launch_bounds__(512, 2) void attention_bf16_kernel(
         if (kt + 1 < KT) ATT_STEP(sk1, sv1, sk0, sv0, kt + 1, true)
     }
 #undef ATT_LOAD_NEXT
-#undef ATT_STORE_V
 #undef ATT_STEP
 
     // ---- normalise and store: lane holds O[q][db*32 + 8j + 4g + i] in oacc[qb][db][4j + i]
@@ -273,7 +267,7 @@ __global__ __launch_bounds__(512, 2) void attention_bf16_kernel(
 // query tile, a whole workgroup of the kernel above would stream every K/V tile for them with
 // one or two of its eight waves working.  Here one workgroup per (image, head) takes those rows
 // and its eight waves split the KEY tiles instead (wave w: tiles w, w + 8, ...), each with its
-// own K / V^T tile in LDS and no workgroup barrier inside the loop; the eight partial results
+// own K / V tile in LDS and no workgroup barrier inside the loop; the eight partial results
 // (running maximum, row sum, unnormalised output) are merged through LDS in wave order, so the
 // result does not depend on timing.
 // ---------------------------------------------------------------------------
@@ -283,7 +277,7 @@ __global__ __launch_bounds__(512, 2) void attention_bf16_tail_kernel(
     const bf16raw* __restrict__ q, const bf16raw* __restrict__ k, const bf16raw* __restrict__ v,
     bf16raw* __restrict__ o, int N, int64_t sb, int64_t sn, int64_t sh, int64_t osb, int64_t osn,
     int64_t osh, float scale_log2e, int H, int q_begin) {
-    // per wave: K tile (8 KB) + V^T tile (8 KB); after the loop the same 16 KB hold the wave's
+    // per wave: K tile (8 KB) + V tile (8 KB); after the loop the same 16 KB hold the wave's
     // output partial [2 blocks][32 rows][64 channels] fp32
     __shared__ __attribute__((aligned(1024))) unsigned char s_tiles[8][16384];
     __shared__ float s_m[8][2][32];
@@ -294,7 +288,6 @@ __global__ __launch_bounds__(512, 2) void attention_bf16_tail_kernel(
     const int l32 = lane & 31, g = lane >> 5;
     const int b = blockIdx.x / H, h = blockIdx.x - b * H;
     const int64_t base = (int64_t)b * sb + (int64_t)h * sh;
-    const bf16raw* vb = v + base;
     unsigned char* sk = s_tiles[wave];
     unsigned char* svt = sk + ATT_BN * 128;
 
@@ -310,6 +303,8 @@ __global__ __launch_bounds__(512, 2) void attention_bf16_tail_kernel(
     const int64_t k_bytes = ((int64_t)(N - 1) * sn + DH) * 2;
     const __amdgpu_buffer_rsrc_t rs_k = __builtin_amdgcn_make_buffer_rsrc(
         const_cast<bf16raw*>(k + base), 0, (int)(k_bytes < 0xffffffffll ? k_bytes : 0xffffffffll), 0x00020000);
+    const __amdgpu_buffer_rsrc_t rs_v = __builtin_amdgcn_make_buffer_rsrc(
+        const_cast<bf16raw*>(v + base), 0, (int)(k_bytes < 0xffffffffll ? k_bytes : 0xffffffffll), 0x00020000);
     const int k_lr = lane >> 3;
     const int k_tile_bytes = (int)(ATT_BN * sn * 2);
 
@@ -333,34 +328,13 @@ __global__ __launch_bounds__(512, 2) void attention_bf16_tail_kernel(
             const int voff = (int)(((int64_t)(i * 8 + k_lr) * sn + (((lane & 7) ^ k_lr ^ i) << 3)) * 2);
             __builtin_amdgcn_raw_ptr_buffer_load_lds(rs_k, (att_lds_ptr)(sk + i * 1024), 16, voff, kt * k_tile_bytes, 0, 0);
         }
-        // V^T tile: pass i plays thread 64 i + lane of the 512-thread staging pattern above; all
-        // loads are issued before the first transposing write
-        uint2 vr0[8], vr1[8];
+        // V tile: the same rows and lanes, chunk (l%8) ^ att_vswz(row) in slot l%8
 #pragma unroll
         for (int i = 0; i < 8; ++i) {
-            const int t = i * 64 + lane;
-            const int v_dc = t & 15, v_pos = 2 * (t >> 4);
-            const int v_key = (v_pos & ~15) | (((v_pos >> 2) & 1) << 3) | (((v_pos >> 3) & 1) << 2) | (v_pos & 3);
-            const int kr = kt * ATT_BN + v_key;
-            vr0[i] = make_uint2(0u, 0u);  // keys past the end contribute exact zeros
-            vr1[i] = make_uint2(0u, 0u);
-            if (kr < N) vr0[i] = *reinterpret_cast<const uint2*>(vb + (int64_t)kr * sn + v_dc * 4);
-            if (kr + 1 < N) vr1[i] = *reinterpret_cast<const uint2*>(vb + (int64_t)(kr + 1) * sn + v_dc * 4);
+            const int voff = (int)(((int64_t)(i * 8 + k_lr) * sn + (((lane & 7) ^ att_vswz(k_lr)) << 3)) * 2);
+            __builtin_amdgcn_raw_ptr_buffer_load_lds(rs_v, (att_lds_ptr)(svt + i * 1024), 16, voff, kt * k_tile_bytes, 0, 0);
         }
-#pragma unroll
-        for (int i = 0; i < 8; ++i) {
-            const int t = i * 64 + lane;
-            const int v_dc = t & 15, v_pos = 2 * (t >> 4);
-            const uint32_t w0[2] = {vr0[i].x, vr0[i].y}, w1[2] = {vr1[i].x, vr1[i].y};
-#pragma unroll
-            for (int e = 0; e < 4; ++e) {
-                const uint32_t lo = (e & 1) ? (w0[e >> 1] >> 16) : (w0[e >> 1] & 0xffffu);
-                const uint32_t hi = (e & 1) ? (w1[e >> 1] & 0xffff0000u) : (w1[e >> 1] << 16);
-                const int d = v_dc * 4 + e;
-                *reinterpret_cast<uint32_t*>(svt + att_swz(d, v_pos >> 3) + (v_pos & 7) * 2) = lo | hi;
-            }
-        }
-        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");  // this wave's K copies have landed
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");  // this wave's K and V copies have landed
         // one block of 32 rows at a time: fewer live registers than both at once, and LDS
         // bandwidth is not what limits this kernel
 #pragma unroll
@@ -424,16 +398,14 @@ __global__ __launch_bounds__(512, 2) void attention_bf16_tail_kernel(
 
 // ---------------------------------------------------------------------------
 // Short sequences (N <= 256, every image-classification block): one workgroup of 8 waves per
-// (image, head).  K (N x 64) and V^T (64 x N) of the head are copied into LDS once, one
+// (image, head).  K and V (N x 64 each) of the head are copied into LDS once, one
 // barrier, then wave w runs query rows 32w .. 32w+31 against all key tiles without further
 // synchronisation.  Against the tiled kernel this reads K and V once instead of once per
 // query tile and has no per-tile barrier or staging latency; two workgroups share a CU, so
 // one's load phase runs under the other's tile loop.  The tile loop itself is bound by
 // instruction issue (plain ALU and matrix instructions of a SIMD's waves do not overlap), so
 // it carries no masking work outside the last key tile.
-// LDS: K rows of 128 bytes, chunk c of row r in slot c ^ ((r ^ r>>3) & 7); V^T rows of 512
-// bytes (256 key positions), 16-byte chunk c of channel row d in slot c ^ ((d ^ d>>3) & 15):
-// both the 16-lane operand reads and the transposing 4-byte writes are bank-conflict free.
+// LDS: K and V rows of 128 bytes in the tiled kernel's two slot orders (att_swz, att_vswz).
 // ---------------------------------------------------------------------------
 constexpr int SM_MAXN = 256;
 
@@ -441,43 +413,34 @@ __global__ __launch_bounds__(512) void attention_bf16_small_kernel(
     const bf16raw* __restrict__ q, const bf16raw* __restrict__ k, const bf16raw* __restrict__ v,
     bf16raw* __restrict__ o, int N, int64_t sb, int64_t sn, int64_t sh, int64_t osb, int64_t osn,
     int64_t osh, float scale_log2e) {
-    __shared__ __attribute__((aligned(16))) unsigned char s_k[SM_MAXN * 128];
-    __shared__ __attribute__((aligned(16))) unsigned char s_vt[DH * 512];
+    __shared__ __attribute__((aligned(1024))) unsigned char s_k[SM_MAXN * 128];
+    __shared__ __attribute__((aligned(1024))) unsigned char s_v[SM_MAXN * 128];
 
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int l32 = lane & 31, g = lane >> 5;
     const int b = blockIdx.y, h = blockIdx.x;
     const int64_t base = (int64_t)b * sb + (int64_t)h * sh;
-    const bf16raw* kb = k + base;
-    const bf16raw* vb = v + base;
     const int KT = (N + ATT_BN - 1) / ATT_BN;   // key tiles of 64
-    const int NP = KT * ATT_BN;                 // keys including the padding of the last tile
 
-    // All global loads of the workgroup's share of K, V and Q are issued first and written to LDS
-    // afterwards: one memory latency per workgroup instead of one per loop iteration.
-    // K: 16-byte chunk (tid & 7) of key rows (tid >> 3) + 64 i.  V: channel chunk (tid & 7), key
-    // positions 2a, 2a+1 with a = (tid >> 3) + 64 i; position p = 16T + 8g' + 4u + i  <->  key
-    // 16T + 8u + 4g' + i.
-    const int ld_chunk = tid & 7, ld_row = tid >> 3;
-    uint4 k_reg[SM_MAXN / 64];
-#pragma unroll
-    for (int i = 0; i < SM_MAXN / 64; ++i) {
-        const int r = ld_row + 64 * i;
-        const int kr = r < N ? r : N - 1;  // padded keys are masked to -inf in the last tile
-        k_reg[i] = make_uint4(0u, 0u, 0u, 0u);
-        if (r < NP) k_reg[i] = *reinterpret_cast<const uint4*>(kb + (int64_t)kr * sn + ld_chunk * 8);
-    }
-    uint4 v_reg0[SM_MAXN / 128], v_reg1[SM_MAXN / 128];
-    int v_posn[SM_MAXN / 128];
-#pragma unroll
-    for (int i = 0; i < SM_MAXN / 128; ++i) {
-        const int vpos = 2 * (ld_row + 64 * i);
-        const int vkey = (vpos & ~15) | (((vpos >> 2) & 1) << 3) | (((vpos >> 3) & 1) << 2) | (vpos & 3);
-        v_posn[i] = vpos;
-        v_reg0[i] = make_uint4(0u, 0u, 0u, 0u);  // keys past the end contribute exact zeros
-        v_reg1[i] = make_uint4(0u, 0u, 0u, 0u);
-        if (vkey < N) v_reg0[i] = *reinterpret_cast<const uint4*>(vb + (int64_t)vkey * sn + ld_chunk * 8);
-        if (vkey + 1 < N) v_reg1[i] = *reinterpret_cast<const uint4*>(vb + (int64_t)(vkey + 1) * sn + ld_chunk * 8);
+    // K and V of the head go from memory straight into LDS: per tile of 64 keys, wave w copies
+    // rows 8w .. 8w+7 (lane l: row l/8, 16-byte slot l%8).  Both resources end with key N-1, so
+    // the padding rows of the last tile arrive as zeros: zero V rows add nothing, and the padded
+    // keys' logits are masked in the last tile.
+    const int64_t k_bytes = ((int64_t)(N - 1) * sn + DH) * 2;
+    const __amdgpu_buffer_rsrc_t rs_k = __builtin_amdgcn_make_buffer_rsrc(
+        const_cast<bf16raw*>(k + base), 0, (int)(k_bytes < 0xffffffffll ? k_bytes : 0xffffffffll), 0x00020000);
+    const __amdgpu_buffer_rsrc_t rs_v = __builtin_amdgcn_make_buffer_rsrc(
+        const_cast<bf16raw*>(v + base), 0, (int)(k_bytes < 0xffffffffll ? k_bytes : 0xffffffffll), 0x00020000);
+    const int k_lr = lane >> 3;
+    const int k_voff = (int)(((int64_t)(wave * 8 + k_lr) * sn + (((lane & 7) ^ k_lr ^ wave) << 3)) * 2);
+    const int v_voff = (int)(((int64_t)(wave * 8 + k_lr) * sn + (((lane & 7) ^ att_vswz(k_lr)) << 3)) * 2);
+    const int k_tile_bytes = (int)(ATT_BN * sn * 2);
+    for (int i = 0; i < KT; ++i) {
+        __builtin_amdgcn_raw_ptr_buffer_load_lds(rs_k, (att_lds_ptr)(s_k + i * 8192 + wave * 1024), 16, k_voff,
+                                                 i * k_tile_bytes, 0, 0);
+        __builtin_amdgcn_raw_ptr_buffer_load_lds(rs_v, (att_lds_ptr)(s_v + i * 8192 + wave * 1024), 16, v_voff,
+                                                 i * k_tile_bytes, 0, 0);
     }
     const int q0 = wave * 32;
     // Q fragments (B operand): column = query row q0 + l32, k-slots = channels 16 kk + 8 g ..
@@ -489,26 +452,7 @@ __global__ __launch_bounds__(512) void attention_bf16_small_kernel(
 #pragma unroll
         for (int kk = 0; kk < 4; ++kk) qf[0][kk] = *reinterpret_cast<const bf16x8*>(qp + kk * 16 + g * 8);
     }
-#pragma unroll
-    for (int i = 0; i < SM_MAXN / 64; ++i) {
-        const int r = ld_row + 64 * i;
-        if (r < NP) *reinterpret_cast<uint4*>(&s_k[att_swz(r, ld_chunk)]) = k_reg[i];
-    }
-#pragma unroll
-    for (int i = 0; i < SM_MAXN / 128; ++i) {
-        const int vpos = v_posn[i];
-        if (vpos < NP) {
-            const uint32_t w0[4] = {v_reg0[i].x, v_reg0[i].y, v_reg0[i].z, v_reg0[i].w};
-            const uint32_t w1[4] = {v_reg1[i].x, v_reg1[i].y, v_reg1[i].z, v_reg1[i].w};
-#pragma unroll
-            for (int e = 0; e < 8; ++e) {
-                const uint32_t lo = (e & 1) ? (w0[e >> 1] >> 16) : (w0[e >> 1] & 0xffffu);
-                const uint32_t hi = (e & 1) ? (w1[e >> 1] & 0xffff0000u) : (w1[e >> 1] << 16);
-                const int d = ld_chunk * 8 + e;
-                *reinterpret_cast<uint32_t*>(&s_vt[vt_off(d, vpos >> 3) + (vpos & 7) * 2]) = lo | hi;
-            }
-        }
-    }
+    __builtin_amdgcn_s_waitcnt(0x0F70);  // this wave's copies have landed
     __syncthreads();
     if (q0 >= N) return;  // whole-wave exit after the only barrier
 
@@ -521,11 +465,11 @@ __global__ __launch_bounds__(512) void attention_bf16_small_kernel(
 
     const int KF = N / ATT_BN;  // tiles without padding keys: no masking work in the loop
     for (int kt = 0; kt < KF; ++kt)
-        att_tile<false, 1, true>(s_k + kt * (ATT_BN * 128), s_vt, qf, oacc, m_run, l_run, kt * ATT_BN, N, scale_log2e,
-                                 l32, g, kt);
+        att_tile<false, 1>(s_k + kt * (ATT_BN * 128), s_v + kt * (ATT_BN * 128), qf, oacc, m_run, l_run, kt * ATT_BN, N,
+                           scale_log2e, l32, g);
     if (KF < KT)
-        att_tile<true, 1, true>(s_k + KF * (ATT_BN * 128), s_vt, qf, oacc, m_run, l_run, KF * ATT_BN, N, scale_log2e,
-                                l32, g, KF);
+        att_tile<true, 1>(s_k + KF * (ATT_BN * 128), s_v + KF * (ATT_BN * 128), qf, oacc, m_run, l_run, KF * ATT_BN, N,
+                          scale_log2e, l32, g);
 
     const float l_tot = l_run[0] + __shfl_xor(l_run[0], 32, 64);
     const float inv = 1.0f / l_tot;
