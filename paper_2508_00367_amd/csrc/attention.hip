@@ -398,23 +398,25 @@ __global__ __launch_bounds__(512, 2) void attention_bf16_tail_kernel(
 
 // ---------------------------------------------------------------------------
 // Short sequences (N <= 256, every image-classification block): one workgroup of 8 waves per
-// (image, head).  K and V (N x 64 each) of the head are copied into LDS once, one
-// barrier, then wave w runs query rows 32w .. 32w+31 against all key tiles without further
-// synchronisation.  Against the tiled kernel this reads K and V once instead of once per
-// query tile and has no per-tile barrier or staging latency; two workgroups share a CU, so
-// one's load phase runs under the other's tile loop.  The tile loop itself is bound by
-// instruction issue (plain ALU and matrix instructions of a SIMD's waves do not overlap), so
-// it carries no masking work outside the last key tile.
+// (image, head).  K and V (N x 64 each) of the head are copied into LDS once; wave w runs query
+// rows 32w .. 32w+31 against all key tiles.  The copies are requested in tile order and the
+// first two tiles are used as soon as they have landed, while the other two still stream in:
+// two barriers in all.  Against the tiled kernel this reads K and V once instead of once per
+// query tile and has no per-tile barrier; two workgroups share a CU, so one's load phase runs
+// under the other's tile loop.  The tile loop itself is bound by instruction issue (plain ALU
+// and matrix instructions of a SIMD's waves do not overlap), so it carries no masking work
+// outside the last key tile.
 // LDS: K and V rows of 128 bytes in the tiled kernel's two slot orders (att_swz, att_vswz).
 // ---------------------------------------------------------------------------
 constexpr int SM_MAXN = 256;
 
-__global__ __launch_bounds__(512) void attention_bf16_small_kernel(
+__global__ __launch_bounds__(512, 4) void attention_bf16_small_kernel(
     const bf16raw* __restrict__ q, const bf16raw* __restrict__ k, const bf16raw* __restrict__ v,
     bf16raw* __restrict__ o, int N, int64_t sb, int64_t sn, int64_t sh, int64_t osb, int64_t osn,
     int64_t osh, float scale_log2e) {
-    __shared__ __attribute__((aligned(1024))) unsigned char s_k[SM_MAXN * 128];
-    __shared__ __attribute__((aligned(1024))) unsigned char s_v[SM_MAXN * 128];
+    // one array per half and operand: the compiler then knows which copies a half's LDS reads wait for
+    __shared__ __attribute__((aligned(1024))) unsigned char s_ka[2 * ATT_BN * 128], s_kb[2 * ATT_BN * 128];
+    __shared__ __attribute__((aligned(1024))) unsigned char s_va[2 * ATT_BN * 128], s_vb[2 * ATT_BN * 128];
 
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -422,26 +424,8 @@ __global__ __launch_bounds__(512) void attention_bf16_small_kernel(
     const int b = blockIdx.y, h = blockIdx.x;
     const int64_t base = (int64_t)b * sb + (int64_t)h * sh;
     const int KT = (N + ATT_BN - 1) / ATT_BN;   // key tiles of 64
+    const int KF = N / ATT_BN;                  // tiles without padding keys: no masking work in them
 
-    // K and V of the head go from memory straight into LDS: per tile of 64 keys, wave w copies
-    // rows 8w .. 8w+7 (lane l: row l/8, 16-byte slot l%8).  Both resources end with key N-1, so
-    // the padding rows of the last tile arrive as zeros: zero V rows add nothing, and the padded
-    // keys' logits are masked in the last tile.
-    const int64_t k_bytes = ((int64_t)(N - 1) * sn + DH) * 2;
-    const __amdgpu_buffer_rsrc_t rs_k = __builtin_amdgcn_make_buffer_rsrc(
-        const_cast<bf16raw*>(k + base), 0, (int)(k_bytes < 0xffffffffll ? k_bytes : 0xffffffffll), 0x00020000);
-    const __amdgpu_buffer_rsrc_t rs_v = __builtin_amdgcn_make_buffer_rsrc(
-        const_cast<bf16raw*>(v + base), 0, (int)(k_bytes < 0xffffffffll ? k_bytes : 0xffffffffll), 0x00020000);
-    const int k_lr = lane >> 3;
-    const int k_voff = (int)(((int64_t)(wave * 8 + k_lr) * sn + (((lane & 7) ^ k_lr ^ wave) << 3)) * 2);
-    const int v_voff = (int)(((int64_t)(wave * 8 + k_lr) * sn + (((lane & 7) ^ att_vswz(k_lr)) << 3)) * 2);
-    const int k_tile_bytes = (int)(ATT_BN * sn * 2);
-    for (int i = 0; i < KT; ++i) {
-        __builtin_amdgcn_raw_ptr_buffer_load_lds(rs_k, (att_lds_ptr)(s_k + i * 8192 + wave * 1024), 16, k_voff,
-                                                 i * k_tile_bytes, 0, 0);
-        __builtin_amdgcn_raw_ptr_buffer_load_lds(rs_v, (att_lds_ptr)(s_v + i * 8192 + wave * 1024), 16, v_voff,
-                                                 i * k_tile_bytes, 0, 0);
-    }
     const int q0 = wave * 32;
     // Q fragments (B operand): column = query row q0 + l32, k-slots = channels 16 kk + 8 g ..
     bf16x8 qf[1][4];
@@ -452,9 +436,28 @@ __global__ __launch_bounds__(512) void attention_bf16_small_kernel(
 #pragma unroll
         for (int kk = 0; kk < 4; ++kk) qf[0][kk] = *reinterpret_cast<const bf16x8*>(qp + kk * 16 + g * 8);
     }
-    __builtin_amdgcn_s_waitcnt(0x0F70);  // this wave's copies have landed
-    __syncthreads();
-    if (q0 >= N) return;  // whole-wave exit after the only barrier
+    // K and V of the head go from memory straight into LDS: per tile of 64 keys, wave w copies
+    // rows 8w .. 8w+7 (lane l: row l/8, 16-byte slot l%8).  Both resources end with key N-1, so
+    // rows past the end arrive as zeros without touching memory: zero V rows add nothing, and
+    // the padded keys' logits are masked in the last tile.  All four tiles are always requested,
+    // in tile order, so that "all but the newest 2 (3 - i) copies" means "tile i has landed".
+    const int64_t k_bytes = ((int64_t)(N - 1) * sn + DH) * 2;
+    const __amdgpu_buffer_rsrc_t rs_k = __builtin_amdgcn_make_buffer_rsrc(
+        const_cast<bf16raw*>(k + base), 0, (int)(k_bytes < 0xffffffffll ? k_bytes : 0xffffffffll), 0x00020000);
+    const __amdgpu_buffer_rsrc_t rs_v = __builtin_amdgcn_make_buffer_rsrc(
+        const_cast<bf16raw*>(v + base), 0, (int)(k_bytes < 0xffffffffll ? k_bytes : 0xffffffffll), 0x00020000);
+    const int k_lr = lane >> 3;
+    const int k_voff = (int)(((int64_t)(wave * 8 + k_lr) * sn + (((lane & 7) ^ k_lr ^ wave) << 3)) * 2);
+    const int v_voff = (int)(((int64_t)(wave * 8 + k_lr) * sn + (((lane & 7) ^ att_vswz(k_lr)) << 3)) * 2);
+    const int k_tile_bytes = (int)(ATT_BN * sn * 2);
+#define SM_COPY(SK, SV, i_)                                                                                       \
+    __builtin_amdgcn_raw_ptr_buffer_load_lds(rs_k, (att_lds_ptr)((SK) + wave * 1024), 16, k_voff, (i_) * k_tile_bytes, 0, 0); \
+    __builtin_amdgcn_raw_ptr_buffer_load_lds(rs_v, (att_lds_ptr)((SV) + wave * 1024), 16, v_voff, (i_) * k_tile_bytes, 0, 0);
+    SM_COPY(s_ka, s_va, 0)
+    SM_COPY(s_ka + ATT_BN * 128, s_va + ATT_BN * 128, 1)
+    SM_COPY(s_kb, s_vb, 2)
+    SM_COPY(s_kb + ATT_BN * 128, s_vb + ATT_BN * 128, 3)
+#undef SM_COPY
 
     f32x16 oacc[1][2];
 #pragma unroll
@@ -463,13 +466,30 @@ __global__ __launch_bounds__(512) void attention_bf16_small_kernel(
         for (int r = 0; r < 16; ++r) oacc[0][i][r] = 0.f;
     float m_run[1] = {-INFINITY}, l_run[1] = {0.f};
 
-    const int KF = N / ATT_BN;  // tiles without padding keys: no masking work in the loop
-    for (int kt = 0; kt < KF; ++kt)
-        att_tile<false, 1>(s_k + kt * (ATT_BN * 128), s_v + kt * (ATT_BN * 128), qf, oacc, m_run, l_run, kt * ATT_BN, N,
-                           scale_log2e, l32, g);
-    if (KF < KT)
-        att_tile<true, 1>(s_k + KF * (ATT_BN * 128), s_v + KF * (ATT_BN * 128), qf, oacc, m_run, l_run, KF * ATT_BN, N,
-                          scale_log2e, l32, g);
+    // The first two tiles are used as soon as every wave's share of them has landed; the other
+    // two keep streaming in meanwhile.  Waves without query rows (q0 >= N) still wait and meet
+    // the barriers: the others read the rows they copied.
+#define SM_HALF(SK, SV, t0_, WAIT)                                                                                \
+    if ((t0_) < KT) {                                                                                             \
+        __builtin_amdgcn_s_waitcnt(WAIT);                                                                         \
+        __builtin_amdgcn_s_barrier();                                                                             \
+        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup"); /* the LDS reads stay below the barrier */         \
+        if (q0 < N) {                                                                                             \
+            const int t1 = KF < (t0_) + 2 ? KF : (t0_) + 2;                                                       \
+            int t = (t0_);                                                                                        \
+            for (; t < t1; ++t)                                                                                   \
+                att_tile<false, 1>((SK) + (t - (t0_)) * (ATT_BN * 128), (SV) + (t - (t0_)) * (ATT_BN * 128), qf, oacc, \
+                                   m_run, l_run, t * ATT_BN, N, scale_log2e, l32, g);                             \
+            if (t < KT && t < (t0_) + 2)                                                                          \
+                att_tile<true, 1>((SK) + (t - (t0_)) * (ATT_BN * 128), (SV) + (t - (t0_)) * (ATT_BN * 128), qf, oacc, \
+                                  m_run, l_run, t * ATT_BN, N, scale_log2e, l32, g);                              \
+        }                                                                                                         \
+    }
+    SM_HALF(s_ka, s_va, 0, 0x0F74)  // vmcnt(4): all but the newest four copies
+    SM_HALF(s_kb, s_vb, 2, 0x0F70)
+#undef SM_HALF
+    __builtin_amdgcn_s_waitcnt(0x0F70);  // no copy is in flight when the wave ends
+    if (q0 >= N) return;
 
     const float l_tot = l_run[0] + __shfl_xor(l_run[0], 32, 64);
     const float inv = 1.0f / l_tot;
