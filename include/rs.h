@@ -128,7 +128,8 @@ RS_API const char *rs_profile_class_name(int32_t cls);
  * N x N attention map never leaves the chip.
  *   q, k, v : element (b, n, h, d) at  b*stride_b + n*stride_n + h*stride_h + d
  *             (strides in ELEMENTS, shared by q, k and v; d is contiguous);
- *             strides must be multiples of 8 elements (16 bytes in bf16).
+ *             strides must be multiples of 8 elements (16 bytes in bf16); bf16 needs
+ *             (N + 256) * stride_n * 2 bytes < 2 GiB (RS_ERR_UNSUPPORTED otherwise).
  *   o       : same addressing with the o_stride_* values; must not alias q, k, v.
  *   dh      : must be 64.   scale: the caller's (1/sqrt(dh) for ViT heads; the
  *             paper prints 1/sqrt(C)).   Needs no workspace.
@@ -224,7 +225,8 @@ RS_API rs_status rs_linear_fwd(const void *a, const void *w, const void *bias, c
  *   x        : [B, N, D] in.            y : [B, K, D] out, must not alias x.
  *   kept_idx : int32 [B, K] out.        scores : float [B, N] out, or NULL.
  *   workspace: rs_block_workspace_size(cfg) bytes, 256-byte aligned.
- * Restrictions: D/H == 64, D % 64 == 0, Dm % 64 == 0; else RS_ERR_UNSUPPORTED.
+ * Restrictions: D/H == 64, D % 64 == 0, Dm % 64 == 0, D <= 4096, B*N < 2^31 and, in bf16,
+ *   (N + 256) * 3 D * 2 bytes < 2 GiB; else RS_ERR_UNSUPPORTED.
  */
 RS_API size_t rs_block_workspace_size(const rs_block_cfg *cfg);
 RS_API rs_status rs_block_fwd(const rs_block_cfg *cfg, const rs_block_weights *w,

@@ -159,6 +159,9 @@ static rs_status check_cfg(const rs_block_cfg* c) {
     RS_REQUIRE(c->Dm % 64 == 0, RS_ERR_UNSUPPORTED, "Dm %d is not a multiple of 64", c->Dm);
     RS_REQUIRE(c->D <= 4096, RS_ERR_UNSUPPORTED, "D %d > 4096", c->D);
     RS_REQUIRE((int64_t)c->B * c->N < (int64_t)1 << 31, RS_ERR_UNSUPPORTED, "B*N does not fit 31 bits");
+    // bf16 attention addresses one image's rows of the [N, 3D] QKV buffer with 32-bit byte offsets
+    RS_REQUIRE(c->dtype != RS_BF16 || ((int64_t)c->N + 256) * 3 * c->D * 2 < (int64_t)0x7fffffff, RS_ERR_UNSUPPORTED,
+               "(N + 256) * 3 D * 2 bytes must stay below 2 GiB in bf16");
     RS_REQUIRE(c->n_prefix >= 0 && c->n_keep >= 0, RS_ERR_INVALID_ARG, "negative n_prefix or n_keep");
     RS_REQUIRE((int64_t)c->n_prefix + c->n_keep <= c->N, RS_ERR_INVALID_ARG,
                "n_prefix %d + n_keep %d exceeds N %d", c->n_prefix, c->n_keep, c->N);
@@ -225,6 +228,10 @@ rs_status rs_attention_fwd(const void* q, const void* k, const void* v, void* o,
         RS_REQUIRE(st[i] >= 0 && st[i] % 8 == 0, RS_ERR_INVALID_ARG,
                    "strides must be non-negative multiples of 8 elements");
     RS_REQUIRE(stride_n >= dh && o_stride_n >= dh, RS_ERR_INVALID_ARG, "token stride smaller than dh");
+    // the bf16 kernels address the K and V rows of one (image, head) with 32-bit byte offsets,
+    // up to 256 rows past the last one (those read as zeros)
+    RS_REQUIRE(dtype != RS_BF16 || ((int64_t)N + 256) * stride_n * 2 < (int64_t)0x7fffffff, RS_ERR_UNSUPPORTED,
+               "(N + 256) * stride_n * 2 bytes must stay below 2 GiB for bf16 attention");
     RS_LAUNCH_K(K_ATTN, (hipStream_t)hip_stream, launch_attention(dtype, q, k, v, o, B, H, N, stride_b, stride_n, stride_h, o_stride_b,
                                o_stride_n, o_stride_h, scale, (hipStream_t)hip_stream));
     return RS_OK;

@@ -54,6 +54,7 @@ def test_block_rejects_bad_config():
     for kw, want in [(dict(H=3), rs.RS_ERR_INVALID_ARG),           # D not divisible by H
                      (dict(D=256, H=2), rs.RS_ERR_UNSUPPORTED),    # head width 128
                      (dict(Dm=100), rs.RS_ERR_UNSUPPORTED),
+                     (dict(B=1, N=100000, D=4096, H=64, n_keep=0), rs.RS_ERR_UNSUPPORTED),  # QKV rows beyond 32-bit byte offsets
                      (dict(n_keep=10), rs.RS_ERR_INVALID_ARG),     # prefix + keep > N
                      (dict(n_prefix=-1), rs.RS_ERR_INVALID_ARG),
                      (dict(ln_eps=0.0), rs.RS_ERR_INVALID_ARG),
@@ -113,6 +114,9 @@ def test_attention_rejects_bad_arguments():
     assert call(dt=5) == rs.RS_ERR_INVALID_ARG
     assert call(B=-2) == rs.RS_ERR_INVALID_ARG
     assert call(N=0) == rs.RS_OK and call(B=0, q=None) == rs.RS_OK
+    assert call(N=1 << 20, sn=1024) == rs.RS_ERR_UNSUPPORTED    # K/V rows of a head beyond 32-bit byte offsets
+    assert "2 GiB" in rs.rs_last_error()
+    assert call(sn=60) == rs.RS_ERR_INVALID_ARG
     assert "stride" in rs.rs_last_error() or rs.rs_last_error() != ""
 
 
