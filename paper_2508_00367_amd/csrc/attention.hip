@@ -38,85 +38,71 @@ typedef __attribute__((address_space(3))) v4i16* lds_v4i16;
 // half on every second pair of rows keeps those four rows on different banks.
 __device__ __forceinline__ int att_vswz(int r) { return ((r >> 1) & 1) << 2; }
 
-// QB query-row blocks of 32 rows against one resident tile of 64 keys: S^T = K Q^T, online
-// softmax in registers (one lane = one query row per block, half of the tile's keys),
-// O^T += V^T P^T.  Every K and V fragment read from LDS serves all QB blocks.
+// One block of 32 query rows against one resident tile of 64 keys: S^T = K Q^T, online softmax
+// in registers (one lane = one query row, half of the tile's keys), O^T += V^T P^T.
 // `sk`: K tile [64 keys][128 B] (att_swz); `sv`: V tile [64 keys][128 B] (att_vswz).
-template <bool MASK, int QB>
+template <bool MASK>
 __device__ __forceinline__ void att_tile(const unsigned char* sk, const unsigned char* sv,
-                                         const bf16x8 (&qf)[QB][4], f32x16 (&oacc)[QB][2],
-                                         float (&m_run)[QB], float (&l_run)[QB], int key0, int N,
-                                         float scale_log2e, int l32, int g) {
-    f32x16 sacc[QB][2];
+                                         const bf16x8 (&qf)[4], f32x16 (&oacc)[2], float& m_run,
+                                         float& l_run, int key0, int N, float scale_log2e, int l32, int g) {
+    f32x16 sacc[2];
 #pragma unroll
-    for (int qb = 0; qb < QB; ++qb)
+    for (int kb2 = 0; kb2 < 2; ++kb2)
 #pragma unroll
-        for (int kb2 = 0; kb2 < 2; ++kb2)
-#pragma unroll
-            for (int r = 0; r < 16; ++r) sacc[qb][kb2][r] = 0.f;
+        for (int r = 0; r < 16; ++r) sacc[kb2][r] = 0.f;
 #pragma unroll
     for (int kk = 0; kk < 4; ++kk)
 #pragma unroll
         for (int kb2 = 0; kb2 < 2; ++kb2) {  // independent accumulator chains alternate
             const bf16x8 kf = *reinterpret_cast<const bf16x8*>(sk + att_swz(kb2 * 32 + l32, kk * 2 + g));
-#pragma unroll
-            for (int qb = 0; qb < QB; ++qb)
-                sacc[qb][kb2] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[qb][kk], sacc[qb][kb2], 0, 0, 0);
+            sacc[kb2] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[kk], sacc[kb2], 0, 0, 0);
         }
-    float alpha[QB];
+    if (MASK) {  // keys past the end (last tile only)
 #pragma unroll
-    for (int qb = 0; qb < QB; ++qb) {
-        if (MASK) {  // keys past the end (last tile only)
+        for (int kb2 = 0; kb2 < 2; ++kb2)
 #pragma unroll
-            for (int kb2 = 0; kb2 < 2; ++kb2)
+            for (int r = 0; r < 16; ++r) {
+                const int key = key0 + kb2 * 32 + (r >> 2) * 8 + g * 4 + (r & 3);
+                if (key >= N) sacc[kb2][r] = -INFINITY;
+            }
+    }
+    float mx = fmaxf(sacc[0][0], sacc[1][0]);
 #pragma unroll
-                for (int r = 0; r < 16; ++r) {
-                    const int key = key0 + kb2 * 32 + (r >> 2) * 8 + g * 4 + (r & 3);
-                    if (key >= N) sacc[qb][kb2][r] = -INFINITY;
-                }
-        }
-        float mx = fmaxf(sacc[qb][0][0], sacc[qb][1][0]);
+    for (int r = 1; r < 16; ++r) mx = fmaxf(fmaxf(mx, sacc[0][r]), sacc[1][r]);
+    mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
+    const float m_new = fmaxf(m_run, mx);  // finite: every tile holds at least one real key
+    const float alpha = __builtin_amdgcn_exp2f((m_run - m_new) * scale_log2e);
+    const float mb = m_new * scale_log2e;
+    m_run = m_new;
 #pragma unroll
-        for (int r = 1; r < 16; ++r) mx = fmaxf(fmaxf(mx, sacc[qb][0][r]), sacc[qb][1][r]);
-        mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
-        const float m_new = fmaxf(m_run[qb], mx);  // finite: every tile holds at least one real key
-        alpha[qb] = __builtin_amdgcn_exp2f((m_run[qb] - m_new) * scale_log2e);
-        const float mb = m_new * scale_log2e;
-        m_run[qb] = m_new;
+    for (int r = 0; r < 16; ++r) {
+        sacc[0][r] = __builtin_amdgcn_exp2f(fmaf(sacc[0][r], scale_log2e, -mb));
+        sacc[1][r] = __builtin_amdgcn_exp2f(fmaf(sacc[1][r], scale_log2e, -mb));
+    }
+    if (__ballot(alpha != 1.0f)) {  // the running maximum moved for some row of this block
+        // in-place multiplies: with plain C++ the compiler renames the 32 accumulators on this
+        // rarely taken path and pays 32 register copies on EVERY tile to merge the two paths
 #pragma unroll
-        for (int r = 0; r < 16; ++r) {
-            sacc[qb][0][r] = __builtin_amdgcn_exp2f(fmaf(sacc[qb][0][r], scale_log2e, -mb));
-            sacc[qb][1][r] = __builtin_amdgcn_exp2f(fmaf(sacc[qb][1][r], scale_log2e, -mb));
-        }
-        if (__ballot(alpha[qb] != 1.0f)) {  // the running maximum moved for some row of this block
-            // in-place multiplies: with plain C++ the compiler renames the 32 accumulators on this
-            // rarely taken path and pays 32 register copies on EVERY tile to merge the two paths
+        for (int i = 0; i < 2; ++i)
 #pragma unroll
-            for (int i = 0; i < 2; ++i)
-#pragma unroll
-                for (int r = 0; r < 16; ++r) {
-                    float t = oacc[qb][i][r];
-                    asm volatile("v_mul_f32 %0, %0, %1" : "+v"(t) : "v"(alpha[qb]));
-                    oacc[qb][i][r] = t;
-                }
-        }
+            for (int r = 0; r < 16; ++r) {
+                float t = oacc[i][r];
+                asm volatile("v_mul_f32 %0, %0, %1" : "+v"(t) : "v"(alpha));
+                oacc[i][r] = t;
+            }
     }
     // P goes to bf16 once; the row sum is taken over the same rounded values (v_dot2 with ones)
-    float psum[QB];
-#pragma unroll
-    for (int qb = 0; qb < QB; ++qb) psum[qb] = 0.f;
+    float psum = 0.f;
     const bf16x2 ones = __builtin_bit_cast(bf16x2, 0x3f803f80u);
 #pragma unroll
     for (int t = 0; t < 4; ++t) {
         const int kb2 = t >> 1, r0 = (t & 1) * 8;
-        union { uint32_t u[4]; bf16x8 v; } pf[QB];
+        union { uint32_t u[4]; bf16x8 v; } pf;
 #pragma unroll
-        for (int qb = 0; qb < QB; ++qb)
-#pragma unroll
-            for (int e = 0; e < 4; ++e) {
-                pf[qb].u[e] = pack2bf(sacc[qb][kb2][r0 + 2 * e], sacc[qb][kb2][r0 + 2 * e + 1]);
-                psum[qb] = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, pf[qb].u[e]), ones, psum[qb], false);
-            }
+        for (int e = 0; e < 4; ++e) {
+            pf.u[e] = pack2bf(sacc[kb2][r0 + 2 * e], sacc[kb2][r0 + 2 * e + 1]);
+            psum = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, pf.u[e]), ones, psum, false);
+        }
 #pragma unroll
         for (int db = 0; db < 2; ++db) {
             // V tile as it sits in memory, [64 keys][64 channels]: two transposing LDS reads
@@ -133,23 +119,17 @@ __device__ __forceinline__ void att_tile(const unsigned char* sk, const unsigned
                 tr.h[u] = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
                     (lds_v4i16)(sv + key * 128 + ((chunk ^ att_vswz(key)) << 4) + (s16 & 1) * 8));
             }
-            const bf16x8 vf = tr.v;
-#pragma unroll
-            for (int qb = 0; qb < QB; ++qb)
-                oacc[qb][db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, pf[qb].v, oacc[qb][db], 0, 0, 0);
+            oacc[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(tr.v, pf.v, oacc[db], 0, 0, 0);
         }
     }
-#pragma unroll
-    for (int qb = 0; qb < QB; ++qb) l_run[qb] = l_run[qb] * alpha[qb] + psum[qb];
+    l_run = l_run * alpha + psum;
 }
 
-// Long sequences: workgroup = 256 * QB query rows (8 waves, QB blocks of 32 rows each) of one
-// (image, head).  QB = 2 halves the LDS reads and the barriers per unit of work; which one is
-// launched depends on how the row count fills the workgroups.  K and V tiles stream
+// Long sequences: workgroup = 256 query rows (8 waves x 32 rows) of one (image, head); two
+// workgroups share a CU (at most 128 registers), four waves per SIMD.  K and V tiles stream
 // global -> LDS directly (buffer_load ... lds, rows past N read as zero through the buffer
 // resource).  Two stages each; the copies of tile t+1 are issued before the MFMAs of tile t, one barrier per tile.
-template <int QB>
-__global__ __launch_bounds__(512, 2) void attention_bf16_kernel(
+__global__ __launch_bounds__(512, 4) void attention_bf16_kernel(
     const bf16raw* __restrict__ q, const bf16raw* __restrict__ k, const bf16raw* __restrict__ v,
     bf16raw* __restrict__ o, int N, int64_t sb, int64_t sn, int64_t sh, int64_t osb, int64_t osn,
     int64_t osh, float scale_log2e, int H, int BH, int q_tiles) {
@@ -167,18 +147,17 @@ __global__ __launch_bounds__(512, 2) void attention_bf16_kernel(
     const int head = xcd + 8 * (local / q_tiles);
     if (head >= BH) return;  // whole workgroup, before any barrier
     const int b = head / H, h = head - b * H;
-    const int q0 = (local % q_tiles) * (ATT_BM * QB) + wave * (32 * QB);
+    const int q0 = (local % q_tiles) * ATT_BM + wave * 32;
     const int64_t base = (int64_t)b * sb + (int64_t)h * sh;
 
-    // Q fragments: B operand, column = query row q0 + 32 qb + l32, k-slots = 8 channels 16*kk + 8*g ..
-    bf16x8 qf[QB][4];
-#pragma unroll
-    for (int qb = 0; qb < QB; ++qb) {
-        int qr = q0 + qb * 32 + l32;
+    // Q fragments: B operand, column = query row q0 + l32, k-slots = 8 channels 16*kk + 8*g ..
+    bf16x8 qf[4];
+    {
+        int qr = q0 + l32;
         qr = qr < N ? qr : N - 1;  // rows past the end are computed on a copy and never stored
         const bf16raw* qp = q + base + (int64_t)qr * sn;
 #pragma unroll
-        for (int kk = 0; kk < 4; ++kk) qf[qb][kk] = *reinterpret_cast<const bf16x8*>(qp + kk * 16 + g * 8);
+        for (int kk = 0; kk < 4; ++kk) qf[kk] = *reinterpret_cast<const bf16x8*>(qp + kk * 16 + g * 8);
     }
 
     // K copies: wave w fills LDS rows 8w .. 8w+7 of the tile (lane l: row l/8, slot l%8 holds
@@ -206,24 +185,24 @@ __global__ __launch_bounds__(512, 2) void attention_bf16_kernel(
 #define ATT_STEP(SKc, SVc, SKn, SVn, kt_, MASK_)                                                              \
     {                                                                                                    \
         ATT_LOAD_NEXT(SKn, SVn, (kt_) + 1)                                                               \
-        att_tile<MASK_, QB>(SKc, SVc, qf, oacc, m_run, l_run, (kt_) * ATT_BN, N, scale_log2e, l32, g);   \
+        if (active)                                                                                      \
+            att_tile<MASK_>(SKc, SVc, qf, oacc, m_run, l_run, (kt_) * ATT_BN, N, scale_log2e, l32, g);   \
         __builtin_amdgcn_s_waitcnt(0x0F70); /* this wave's K and V copies have landed */                 \
         __syncthreads();                                                                                 \
     }
 
-    f32x16 oacc[QB][2];
-    float m_run[QB];  // running max of the raw logits of this lane's query rows
-    float l_run[QB];  // this lane's share of the running row sums
+    f32x16 oacc[2];
 #pragma unroll
-    for (int qb = 0; qb < QB; ++qb) {
+    for (int i = 0; i < 2; ++i)
 #pragma unroll
-        for (int i = 0; i < 2; ++i)
-#pragma unroll
-            for (int r = 0; r < 16; ++r) oacc[qb][i][r] = 0.f;
-        m_run[qb] = -INFINITY;
-        l_run[qb] = 0.f;
-    }
+        for (int r = 0; r < 16; ++r) oacc[i][r] = 0.f;
+    float m_run = -INFINITY;  // running max of the raw logits of this lane's query row
+    float l_run = 0.f;        // this lane's share of the running row sum
 
+    // A wave whose query rows all lie past N (last query tile of a head) copies its share of the
+    // K/V tiles and meets the barriers but computes nothing: the wave it shares a SIMD with then
+    // has that SIMD to itself.
+    const bool active = q0 < N;
     const int KT = (N + ATT_BN - 1) / ATT_BN;
     ATT_LOAD_NEXT(sk0, sv0, 0)
     __builtin_amdgcn_s_waitcnt(0x0F70);
@@ -241,24 +220,21 @@ __global__ __launch_bounds__(512, 2) void attention_bf16_kernel(
 #undef ATT_LOAD_NEXT
 #undef ATT_STEP
 
-    // ---- normalise and store: lane holds O[q][db*32 + 8j + 4g + i] in oacc[qb][db][4j + i]
+    // ---- normalise and store: lane holds O[q][db*32 + 8j + 4g + i] in oacc[db][4j + i]
+    const float l_tot = l_run + __shfl_xor(l_run, 32, 64);
+    const float inv = 1.0f / l_tot;
+    const int qr = q0 + l32;
+    if (qr < N) {
+        bf16raw* op = o + (int64_t)b * osb + (int64_t)qr * osn + (int64_t)h * osh;
 #pragma unroll
-    for (int qb = 0; qb < QB; ++qb) {
-        const float l_tot = l_run[qb] + __shfl_xor(l_run[qb], 32, 64);
-        const float inv = 1.0f / l_tot;
-        const int qr = q0 + qb * 32 + l32;
-        if (qr < N) {
-            bf16raw* op = o + (int64_t)b * osb + (int64_t)qr * osn + (int64_t)h * osh;
+        for (int db = 0; db < 2; ++db)
 #pragma unroll
-            for (int db = 0; db < 2; ++db)
-#pragma unroll
-                for (int j = 0; j < 4; ++j) {
-                    uint2 w;
-                    w.x = pack2bf(oacc[qb][db][4 * j] * inv, oacc[qb][db][4 * j + 1] * inv);
-                    w.y = pack2bf(oacc[qb][db][4 * j + 2] * inv, oacc[qb][db][4 * j + 3] * inv);
-                    *reinterpret_cast<uint2*>(op + db * 32 + j * 8 + g * 4) = w;
-                }
-        }
+            for (int j = 0; j < 4; ++j) {
+                uint2 w;
+                w.x = pack2bf(oacc[db][4 * j] * inv, oacc[db][4 * j + 1] * inv);
+                w.y = pack2bf(oacc[db][4 * j + 2] * inv, oacc[db][4 * j + 3] * inv);
+                *reinterpret_cast<uint2*>(op + db * 32 + j * 8 + g * 4) = w;
+            }
     }
 }
 
@@ -291,14 +267,14 @@ __global__ __launch_bounds__(512, 2) void attention_bf16_tail_kernel(
     unsigned char* sk = s_tiles[wave];
     unsigned char* svt = sk + ATT_BN * 128;
 
-    bf16x8 qf[2][1][4];
+    bf16x8 qf[2][4];
 #pragma unroll
     for (int qb = 0; qb < 2; ++qb) {
         int qr = q_begin + qb * 32 + l32;
         qr = qr < N ? qr : N - 1;  // rows past the end are computed on a copy and never stored
         const bf16raw* qp = q + base + (int64_t)qr * sn;
 #pragma unroll
-        for (int kk = 0; kk < 4; ++kk) qf[qb][0][kk] = *reinterpret_cast<const bf16x8*>(qp + kk * 16 + g * 8);
+        for (int kk = 0; kk < 4; ++kk) qf[qb][kk] = *reinterpret_cast<const bf16x8*>(qp + kk * 16 + g * 8);
     }
     const int64_t k_bytes = ((int64_t)(N - 1) * sn + DH) * 2;
     const __amdgpu_buffer_rsrc_t rs_k = __builtin_amdgcn_make_buffer_rsrc(
@@ -308,16 +284,16 @@ __global__ __launch_bounds__(512, 2) void attention_bf16_tail_kernel(
     const int k_lr = lane >> 3;
     const int k_tile_bytes = (int)(ATT_BN * sn * 2);
 
-    f32x16 oacc[2][1][2];
-    float m_run[2][1], l_run[2][1];
+    f32x16 oacc[2][2];
+    float m_run[2], l_run[2];
 #pragma unroll
     for (int qb = 0; qb < 2; ++qb) {
 #pragma unroll
         for (int i = 0; i < 2; ++i)
 #pragma unroll
-            for (int r = 0; r < 16; ++r) oacc[qb][0][i][r] = 0.f;
-        m_run[qb][0] = -INFINITY;
-        l_run[qb][0] = 0.f;
+            for (int r = 0; r < 16; ++r) oacc[qb][i][r] = 0.f;
+        m_run[qb] = -INFINITY;
+        l_run[qb] = 0.f;
     }
 
     const int KT = (N + ATT_BN - 1) / ATT_BN;
@@ -340,18 +316,18 @@ __global__ __launch_bounds__(512, 2) void attention_bf16_tail_kernel(
 #pragma unroll
         for (int qb = 0; qb < 2; ++qb) {
             if (kt == KT - 1 && (N & (ATT_BN - 1)))
-                att_tile<true, 1>(sk, svt, qf[qb], oacc[qb], m_run[qb], l_run[qb], kt * ATT_BN, N, scale_log2e, l32, g);
+                att_tile<true>(sk, svt, qf[qb], oacc[qb], m_run[qb], l_run[qb], kt * ATT_BN, N, scale_log2e, l32, g);
             else
-                att_tile<false, 1>(sk, svt, qf[qb], oacc[qb], m_run[qb], l_run[qb], kt * ATT_BN, N, scale_log2e, l32, g);
+                att_tile<false>(sk, svt, qf[qb], oacc[qb], m_run[qb], l_run[qb], kt * ATT_BN, N, scale_log2e, l32, g);
         }
     }
 
     // ---- merge the eight partials
 #pragma unroll
     for (int qb = 0; qb < 2; ++qb) {
-        const float l_tot = l_run[qb][0] + __shfl_xor(l_run[qb][0], 32, 64);
+        const float l_tot = l_run[qb] + __shfl_xor(l_run[qb], 32, 64);
         if (g == 0) {
-            s_m[wave][qb][l32] = m_run[qb][0];
+            s_m[wave][qb][l32] = m_run[qb];
             s_l[wave][qb][l32] = l_tot;
         }
     }
@@ -366,14 +342,14 @@ __global__ __launch_bounds__(512, 2) void attention_bf16_tail_kernel(
 #pragma unroll
         for (int w = 0; w < 8; ++w)
             L += s_l[w][qb][l32] * __builtin_amdgcn_exp2f((s_m[w][qb][l32] - m_tot) * scale_log2e);
-        const float f = __builtin_amdgcn_exp2f((m_run[qb][0] - m_tot) * scale_log2e) / L;  // 0 for a wave without tiles
+        const float f = __builtin_amdgcn_exp2f((m_run[qb] - m_tot) * scale_log2e) / L;  // 0 for a wave without tiles
 #pragma unroll
         for (int db = 0; db < 2; ++db)
 #pragma unroll
             for (int j = 0; j < 4; ++j) {
                 const int slot = db * 8 + 2 * j + g;  // 4 channels db*32 + 8j + 4g ..
-                const f32x4 val = {oacc[qb][0][db][4 * j] * f, oacc[qb][0][db][4 * j + 1] * f,
-                                   oacc[qb][0][db][4 * j + 2] * f, oacc[qb][0][db][4 * j + 3] * f};
+                const f32x4 val = {oacc[qb][db][4 * j] * f, oacc[qb][db][4 * j + 1] * f,
+                                   oacc[qb][db][4 * j + 2] * f, oacc[qb][db][4 * j + 3] * f};
                 *reinterpret_cast<f32x4*>(part + (qb * 32 + l32) * 64 + ((slot ^ (l32 & 15)) << 2)) = val;
             }
     }
@@ -428,13 +404,13 @@ __global__ __launch_bounds__(512, 4) void attention_bf16_small_kernel(
 
     const int q0 = wave * 32;
     // Q fragments (B operand): column = query row q0 + l32, k-slots = channels 16 kk + 8 g ..
-    bf16x8 qf[1][4];
+    bf16x8 qf[4];
     {
         int qr = q0 + l32;
         qr = qr < N ? qr : N - 1;
         const bf16raw* qp = q + base + (int64_t)qr * sn;
 #pragma unroll
-        for (int kk = 0; kk < 4; ++kk) qf[0][kk] = *reinterpret_cast<const bf16x8*>(qp + kk * 16 + g * 8);
+        for (int kk = 0; kk < 4; ++kk) qf[kk] = *reinterpret_cast<const bf16x8*>(qp + kk * 16 + g * 8);
     }
     // K and V of the head go from memory straight into LDS: per tile of 64 keys, wave w copies
     // rows 8w .. 8w+7 (lane l: row l/8, 16-byte slot l%8).  Both resources end with key N-1, so
@@ -459,12 +435,12 @@ __global__ __launch_bounds__(512, 4) void attention_bf16_small_kernel(
     SM_COPY(s_kb + ATT_BN * 128, s_vb + ATT_BN * 128, 3)
 #undef SM_COPY
 
-    f32x16 oacc[1][2];
+    f32x16 oacc[2];
 #pragma unroll
     for (int i = 0; i < 2; ++i)
 #pragma unroll
-        for (int r = 0; r < 16; ++r) oacc[0][i][r] = 0.f;
-    float m_run[1] = {-INFINITY}, l_run[1] = {0.f};
+        for (int r = 0; r < 16; ++r) oacc[i][r] = 0.f;
+    float m_run = -INFINITY, l_run = 0.f;
 
     // The first two tiles are used as soon as every wave's share of them has landed; the other
     // two keep streaming in meanwhile.  Waves without query rows (q0 >= N) still wait and meet
@@ -478,10 +454,10 @@ __global__ __launch_bounds__(512, 4) void attention_bf16_small_kernel(
             const int t1 = KF < (t0_) + 2 ? KF : (t0_) + 2;                                                       \
             int t = (t0_);                                                                                        \
             for (; t < t1; ++t)                                                                                   \
-                att_tile<false, 1>((SK) + (t - (t0_)) * (ATT_BN * 128), (SV) + (t - (t0_)) * (ATT_BN * 128), qf, oacc, \
+                att_tile<false>((SK) + (t - (t0_)) * (ATT_BN * 128), (SV) + (t - (t0_)) * (ATT_BN * 128), qf, oacc, \
                                    m_run, l_run, t * ATT_BN, N, scale_log2e, l32, g);                             \
             if (t < KT && t < (t0_) + 2)                                                                          \
-                att_tile<true, 1>((SK) + (t - (t0_)) * (ATT_BN * 128), (SV) + (t - (t0_)) * (ATT_BN * 128), qf, oacc, \
+                att_tile<true>((SK) + (t - (t0_)) * (ATT_BN * 128), (SV) + (t - (t0_)) * (ATT_BN * 128), qf, oacc, \
                                   m_run, l_run, t * ATT_BN, N, scale_log2e, l32, g);                              \
         }                                                                                                         \
     }
@@ -491,7 +467,7 @@ __global__ __launch_bounds__(512, 4) void attention_bf16_small_kernel(
     __builtin_amdgcn_s_waitcnt(0x0F70);  // no copy is in flight when the wave ends
     if (q0 >= N) return;
 
-    const float l_tot = l_run[0] + __shfl_xor(l_run[0], 32, 64);
+    const float l_tot = l_run + __shfl_xor(l_run, 32, 64);
     const float inv = 1.0f / l_tot;
     const int qr = q0 + l32;
     if (qr < N) {
@@ -501,8 +477,8 @@ __global__ __launch_bounds__(512, 4) void attention_bf16_small_kernel(
 #pragma unroll
             for (int j = 0; j < 4; ++j) {
                 uint2 w;
-                w.x = pack2bf(oacc[0][db][4 * j] * inv, oacc[0][db][4 * j + 1] * inv);
-                w.y = pack2bf(oacc[0][db][4 * j + 2] * inv, oacc[0][db][4 * j + 3] * inv);
+                w.x = pack2bf(oacc[db][4 * j] * inv, oacc[db][4 * j + 1] * inv);
+                w.y = pack2bf(oacc[db][4 * j + 2] * inv, oacc[db][4 * j + 3] * inv);
                 *reinterpret_cast<uint2*>(op + db * 32 + j * 8 + g * 4) = w;
             }
     }
@@ -605,37 +581,20 @@ hipError_t launch_attention(rs_dtype dt, const void* q, const void* k, const voi
                            (const bf16raw*)k, (const bf16raw*)v, (bf16raw*)o, N, sb, sn, sh, osb, osn, osh,
                            scale_log2e);
     } else if (dt == RS_BF16) {
-        // Rows per workgroup (256 or 512) and whether the rows beyond the last full query tile go
-        // to the tail kernel: the combination with the least estimated time.  One workgroup per CU;
-        // a 512-row workgroup costs ~1.6x a 256-row one (half the barriers and LDS reads per row);
-        // the tail kernel costs about a third of a 256-row workgroup.
+        // Whether the rows beyond the last full query tile of 256 go to the tail kernel: a CU holds
+        // two workgroups, so a round is 512 of them; the tail kernel costs about a fifth of a round.
         const int BH = B * H;
-        int best_qb = 1, best_tail = 0;
-        float best_cost = 1e30f;
-        for (int qb = 1; qb <= 2; ++qb)
-            for (int tail = 0; tail <= 1; ++tail) {
-                const int bm = ATT_BM * qb, rem = N % bm;
-                if (tail && !(rem > 0 && rem <= ATT_TAIL_ROWS && N > bm)) continue;
-                const int tiles = tail ? N / bm : (N + bm - 1) / bm;
-                const float rounds = (float)(((int64_t)BH * tiles + 255) / 256);
-                float cost = rounds * (qb == 2 ? 1.6f : 1.0f);
-                if (tail) cost += 0.35f * (float)((BH + 255) / 256);
-                if (cost < best_cost) { best_cost = cost; best_qb = qb; best_tail = tail; }
-            }
-#ifdef RS_ATT_FORCE_QB
-        best_qb = RS_ATT_FORCE_QB; best_tail = 0;
-#endif
-        const int bm = ATT_BM * best_qb;
+        const int rem = N % ATT_BM;
+        const bool tail_ok = rem > 0 && rem <= ATT_TAIL_ROWS && N > ATT_BM;
+        const float cost_plain = (float)(((int64_t)BH * ((N + ATT_BM - 1) / ATT_BM) + 511) / 512);
+        const float cost_tail = (float)(((int64_t)BH * (N / ATT_BM) + 511) / 512) + 0.22f * (float)((BH + 255) / 256);
+        const bool best_tail = tail_ok && cost_tail < cost_plain;
+        const int bm = ATT_BM;
         const int q_tiles = best_tail ? N / bm : (N + bm - 1) / bm;
         dim3 grid(8 * ((BH + 7) / 8) * q_tiles);
-        if (best_qb == 2)
-            hipLaunchKernelGGL(attention_bf16_kernel<2>, grid, dim3(512), 0, s, (const bf16raw*)q,
-                               (const bf16raw*)k, (const bf16raw*)v, (bf16raw*)o, N, sb, sn, sh, osb, osn,
-                               osh, scale_log2e, H, BH, q_tiles);
-        else
-            hipLaunchKernelGGL(attention_bf16_kernel<1>, grid, dim3(512), 0, s, (const bf16raw*)q,
-                               (const bf16raw*)k, (const bf16raw*)v, (bf16raw*)o, N, sb, sn, sh, osb, osn,
-                               osh, scale_log2e, H, BH, q_tiles);
+        hipLaunchKernelGGL(attention_bf16_kernel, grid, dim3(512), 0, s, (const bf16raw*)q, (const bf16raw*)k,
+                           (const bf16raw*)v, (bf16raw*)o, N, sb, sn, sh, osb, osn, osh, scale_log2e, H, BH,
+                           q_tiles);
         if (best_tail)
             hipLaunchKernelGGL(attention_bf16_tail_kernel, dim3(BH), dim3(512), 0, s, (const bf16raw*)q,
                                (const bf16raw*)k, (const bf16raw*)v, (bf16raw*)o, N, sb, sn, sh, osb, osn,

@@ -45,10 +45,12 @@ def test_attention_packed_qkv(dtype, B, N, H):
     assert err < TOL[dtype]
 
 
-# (B, N, H) chosen so that the launcher takes each of its long-sequence plans: 256-row workgroups
-# plus the tail kernel for the one row left over (128 heads x 513); 512-row workgroups (96 x 1024);
-# 512-row workgroups plus the tail kernel for 36 rows, with a padded last key tile (96 x 1060).
-@pytest.mark.parametrize("B,N,H", [(8, 513, 16), (8, 1024, 12), (8, 1060, 12)])
+# (B, N, H) chosen so that the launcher takes each of its long-sequence plans (a round is 512
+# workgroups of 256 rows): every row in the tiled kernel, the last workgroup of a head holding one
+# row and seven idle waves (128 heads x 3 tiles fit one round); the one row beyond the last full
+# tile in the tail kernel (128 x 5 tiles would start a second round); 36 tail rows with a padded
+# last key tile; no rows left over.
+@pytest.mark.parametrize("B,N,H", [(8, 513, 16), (8, 1025, 16), (8, 1060, 16), (8, 1024, 12)])
 def test_attention_long_sequence_plans(B, N, H):
     _say("attention plans", B, N, H)
     qkv = host_round(si.generic(7, 1, (B, N, 3, H, 64)), "bf16")
