@@ -45,19 +45,30 @@ template <bool MASK>
 __device__ __forceinline__ void att_tile(const unsigned char* sk, const unsigned char* sv,
                                          const bf16x8 (&qf)[4], f32x16 (&oacc)[2], float& m_run,
                                          float& l_run, int key0, int N, float scale_log2e, int l32, int g) {
+    // In the padded last tile only the 32-key blocks and 16-key groups that hold real keys are
+    // worked on (wave-uniform conditions): N = 197 leaves 5 keys in its fourth tile.
+    const int valid = MASK ? N - key0 : ATT_BN;  // real keys in this tile, 1 .. 64
     f32x16 sacc[2];
 #pragma unroll
     for (int kb2 = 0; kb2 < 2; ++kb2)
 #pragma unroll
         for (int r = 0; r < 16; ++r) sacc[kb2][r] = 0.f;
+    if (!MASK || valid > 32) {
 #pragma unroll
-    for (int kk = 0; kk < 4; ++kk)
+        for (int kk = 0; kk < 4; ++kk)
 #pragma unroll
-        for (int kb2 = 0; kb2 < 2; ++kb2) {  // independent accumulator chains alternate
-            const bf16x8 kf = *reinterpret_cast<const bf16x8*>(sk + att_swz(kb2 * 32 + l32, kk * 2 + g));
-            sacc[kb2] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[kk], sacc[kb2], 0, 0, 0);
+            for (int kb2 = 0; kb2 < 2; ++kb2) {  // independent accumulator chains alternate
+                const bf16x8 kf = *reinterpret_cast<const bf16x8*>(sk + att_swz(kb2 * 32 + l32, kk * 2 + g));
+                sacc[kb2] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[kk], sacc[kb2], 0, 0, 0);
+            }
+    } else {
+#pragma unroll
+        for (int kk = 0; kk < 4; ++kk) {
+            const bf16x8 kf = *reinterpret_cast<const bf16x8*>(sk + att_swz(l32, kk * 2 + g));
+            sacc[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[kk], sacc[0], 0, 0, 0);
         }
-    if (MASK) {  // keys past the end (last tile only)
+    }
+    if (MASK) {  // keys past the end
 #pragma unroll
         for (int kb2 = 0; kb2 < 2; ++kb2)
 #pragma unroll
@@ -74,10 +85,15 @@ __device__ __forceinline__ void att_tile(const unsigned char* sk, const unsigned
     const float alpha = __builtin_amdgcn_exp2f((m_run - m_new) * scale_log2e);
     const float mb = m_new * scale_log2e;
     m_run = m_new;
+    if (!MASK || valid > 32) {
 #pragma unroll
-    for (int r = 0; r < 16; ++r) {
-        sacc[0][r] = __builtin_amdgcn_exp2f(fmaf(sacc[0][r], scale_log2e, -mb));
-        sacc[1][r] = __builtin_amdgcn_exp2f(fmaf(sacc[1][r], scale_log2e, -mb));
+        for (int r = 0; r < 16; ++r) {
+            sacc[0][r] = __builtin_amdgcn_exp2f(fmaf(sacc[0][r], scale_log2e, -mb));
+            sacc[1][r] = __builtin_amdgcn_exp2f(fmaf(sacc[1][r], scale_log2e, -mb));
+        }
+    } else {
+#pragma unroll
+        for (int r = 0; r < 16; ++r) sacc[0][r] = __builtin_amdgcn_exp2f(fmaf(sacc[0][r], scale_log2e, -mb));
     }
     if (__ballot(alpha != 1.0f)) {  // the running maximum moved for some row of this block
         // in-place multiplies: with plain C++ the compiler renames the 32 accumulators on this
@@ -96,6 +112,7 @@ __device__ __forceinline__ void att_tile(const unsigned char* sk, const unsigned
     const bf16x2 ones = __builtin_bit_cast(bf16x2, 0x3f803f80u);
 #pragma unroll
     for (int t = 0; t < 4; ++t) {
+        if (MASK && 16 * t >= valid) break;  // groups of padding keys only: P = 0
         const int kb2 = t >> 1, r0 = (t & 1) * 8;
         union { uint32_t u[4]; bf16x8 v; } pf;
 #pragma unroll
