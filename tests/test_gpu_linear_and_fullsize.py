@@ -112,15 +112,18 @@ def test_fullsize_vit_b_block_sampled_images():
 
 
 @pytest.mark.parametrize("name,block,sample", [("video_vit_b16", 2, [0, 7]), ("video_vit_l14", 4, [3]),
-                                               ("umt_b_ret", 1, [19])])
+                                               ("umt_b_ret", 1, [19]), ("umt_b_ret", 3, [4]), ("umt_b_qa", 3, [11]),
+                                               ("deit_t", 1, [0, 300, 511])])
 def test_fullsize_video_block_sampled_clips(name, block, sample):
-    """First pruning block of the video workloads at full size (8 x 1569 x 768 keep half; 4 x 4097
-    x 1024 keep 70 %; 20 x 2352 x 768 without class token keep 80 %): long-sequence attention
-    plans, LayerNorm-folded GEMMs and the prune pass together.  The checker recomputes the
-    sampled clips; invariants cover the rest."""
+    """Pruning blocks of the video workloads at full size, with the sequence length the block sees
+    in the schedule (8 x 1569 x 768 keep half; 4 x 4097 x 1024 keep 70 %; 20 x 2352 x 768 without
+    class token keep 80 %; the third UMT blocks at 1506 -> 1205 and 1906 -> 1716 tokens), and the
+    narrowest image model (512 x 197 x 192): long-sequence attention plans, LayerNorm-folded GEMMs
+    and the prune pass together.  The checker recomputes the sampled clips; invariants cover the rest."""
     wl = si.WORKLOADS[name]
-    B, N, D, H, Dm, P = wl["B"], wl["N"], wl["D"], wl["H"], wl["Dm"], wl.get("n_prefix", 1)
-    n_keep = rs.keep_counts(N, P, wl["blocks"], wl["prune"])[block - 1][1]
+    B, D, H, Dm, P = wl["B"], wl["D"], wl["H"], wl["Dm"], wl.get("n_prefix", 1)
+    n_in, n_keep = rs.keep_counts(wl["N"], P, wl["blocks"], wl["prune"])[block - 1]
+    N = n_in
     assert n_keep < N - P
     _say("full-size block", name, B, N, D, "keep", n_keep)
     x = host_round(si.tokens(0, B, N, D, 0.3), "bf16")
