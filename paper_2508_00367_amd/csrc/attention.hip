@@ -313,6 +313,7 @@ __global__ __launch_bounds__(512, 2) void attention_bf16_tail_kernel(
         l_run[qb] = 0.f;
     }
 
+    const bool second = N - q_begin > 32;  // rows in the second block of 32
     const int KT = (N + ATT_BN - 1) / ATT_BN;
     for (int kt = wave; kt < KT; kt += 8) {
         // K tile: copy i fills rows 8i .. 8i+7 (lane l: row l/8, slot l%8 holds chunk (l%8) ^ f(row))
@@ -332,6 +333,7 @@ __global__ __launch_bounds__(512, 2) void attention_bf16_tail_kernel(
         // bandwidth is not what limits this kernel
 #pragma unroll
         for (int qb = 0; qb < 2; ++qb) {
+            if (qb == 1 && !second) break;  // at most 32 rows left: the second block has none
             if (kt == KT - 1 && (N & (ATT_BN - 1)))
                 att_tile<true>(sk, svt, qf[qb], oacc[qb], m_run[qb], l_run[qb], kt * ATT_BN, N, scale_log2e, l32, g);
             else
@@ -352,6 +354,7 @@ __global__ __launch_bounds__(512, 2) void attention_bf16_tail_kernel(
     float* part = reinterpret_cast<float*>(s_tiles[wave]);
 #pragma unroll
     for (int qb = 0; qb < 2; ++qb) {
+        if (qb == 1 && !second) break;  // its rows are never stored
         float m_tot = s_m[0][qb][l32];
 #pragma unroll
         for (int w = 1; w < 8; ++w) m_tot = fmaxf(m_tot, s_m[w][qb][l32]);
