@@ -101,11 +101,51 @@ __global__ __launch_bounds__(256) void rowstats_kernel(const T* __restrict__ x, 
     if (lane == 0) stats[row] = make_float2(mean, inv);
 }
 
+// Narrow rows (D <= 8 G, G = 16 or 32 lanes): 64 / G rows per wave, so that the lanes of a wave
+// cover whole 16-byte chunks of consecutive rows instead of leaving most of them idle.  The sums
+// run over the same lanes in the same butterfly order as above (the missing partners there
+// hold zeros), so the statistics are the same bits.
+template <typename T, int G>
+__global__ __launch_bounds__(256) void rowstats_narrow_kernel(const T* __restrict__ x, float2* __restrict__ stats,
+                                                              int64_t M, int D, float eps) {
+    constexpr int RPW = 64 / G;  // rows per wave
+    const int lane = threadIdx.x & 63, sub = lane % G;
+    const int64_t row = ((int64_t)blockIdx.x * 4 + (threadIdx.x >> 6)) * RPW + lane / G;
+    const bool on = row < M && sub < (D >> 3);  // whole waves stay in the shuffles below
+    float v[8];
+#pragma unroll
+    for (int i = 0; i < 8; ++i) v[i] = 0.f;
+    if (on) Elem<T>::load8(x + row * D + sub * 8, v);
+    float sum = 0.f;
+#pragma unroll
+    for (int i = 0; i < 8; ++i) sum += v[i];
+#pragma unroll
+    for (int off = G / 2; off >= 1; off >>= 1) sum += __shfl_xor(sum, off, kWave);
+    const float mean = sum / (float)D;
+    float sq = 0.f;
+    if (on) {
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+            const float d = v[i] - mean;
+            sq += d * d;
+        }
+    }
+#pragma unroll
+    for (int off = G / 2; off >= 1; off >>= 1) sq += __shfl_xor(sq, off, kWave);
+    if (sub == 0 && row < M) stats[row] = make_float2(mean, rsqrtf(sq / (float)D + eps));
+}
+
 hipError_t launch_rowstats(rs_dtype dt, const void* x, float* stats, int64_t M, int D, float eps,
                            hipStream_t s) {
     if (M == 0) return hipSuccess;
     dim3 grid((unsigned)((M + 3) / 4)), block(256);
     float2* st = reinterpret_cast<float2*>(stats);
+    if (dt == RS_BF16 && D <= 256) {
+        const bf16raw* xb = (const bf16raw*)x;
+        if (D <= 128) hipLaunchKernelGGL((rowstats_narrow_kernel<bf16raw, 16>), dim3((unsigned)((M + 15) / 16)), block, 0, s, xb, st, M, D, eps);
+        else hipLaunchKernelGGL((rowstats_narrow_kernel<bf16raw, 32>), dim3((unsigned)((M + 7) / 8)), block, 0, s, xb, st, M, D, eps);
+        return hipGetLastError();
+    }
     if (dt == RS_F32) {
         if (D <= 2 * 512) hipLaunchKernelGGL((rowstats_kernel<float, 2>), grid, block, 0, s, (const float*)x, st, M, D, eps);
         else hipLaunchKernelGGL((rowstats_kernel<float, 8>), grid, block, 0, s, (const float*)x, st, M, D, eps);
