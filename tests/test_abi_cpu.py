@@ -187,3 +187,14 @@ def test_schedule_matches_workload_statement():
     for name, wl in si.WORKLOADS.items():
         ours = [n for n, _ in rs.keep_counts(wl["N"], 1, wl["blocks"], wl["prune"])]
         assert ours == osch.tokens_per_block(wl["N"], 1, wl["blocks"], wl["prune"]), name
+
+
+def test_missing_library_fails_loudly(monkeypatch, tmp_path):
+    """No CPU or PyTorch fallback: without the built library every call raises."""
+    monkeypatch.setattr(binding, "_lib", None)
+    monkeypatch.setattr(binding, "LIB_PATH", str(tmp_path / "librs_hip.so"))
+    import pytest
+    with pytest.raises(ImportError, match="no fallback"):
+        binding.lib()
+    with pytest.raises(ImportError):
+        rs.rs_version()
