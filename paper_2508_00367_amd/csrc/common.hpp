@@ -115,6 +115,12 @@ struct GemmLnFold {
     const float* bias;    // [N]
 };
 
+// Largest K and N of a GEMM: a workgroup addresses the (at most 256) rows of its tile with 32-bit
+// byte offsets from the tile's first row, 256 * K * 2 bytes, and the copies of a K slice that does
+// not exist are aimed at byte 0x7ff00000 of a resource that ends with the tile's last row.
+constexpr int kGemmMaxK = 1 << 20;
+constexpr int kGemmMaxN = 1 << 24;
+
 // Number of per-row partial slots the SHIFT epilogue writes for an output width N.
 int gemm_shift_slots(rs_dtype dt, int N);
 constexpr int kShiftLanes = 3;  // floats per slot (L2/L1 use the first, cosine all three)

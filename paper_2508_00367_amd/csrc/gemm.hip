@@ -56,10 +56,12 @@ __device__ __forceinline__ void dma16(__amdgpu_buffer_rsrc_t rsrc, unsigned char
     __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrc, (lds_ptr)lds_base, 16, voff, soff, 0, 0);
 }
 
+// Buffer resource over the rows of ONE tile (at most 256 rows of K <= kGemmMaxK elements: under
+// 2^29 bytes), so that every offset from kPastEnd upwards lies outside it and reads as zero.
 __device__ __forceinline__ __amdgpu_buffer_rsrc_t make_rsrc(const void* base, int64_t bytes) {
-    const int64_t lim = 0xffffffffll;
-    return __builtin_amdgcn_make_buffer_rsrc(const_cast<void*>(base), 0, (int)(bytes < lim ? bytes : lim), 0x00020000);
+    return __builtin_amdgcn_make_buffer_rsrc(const_cast<void*>(base), 0, (int)bytes, 0x00020000);
 }
+constexpr int kPastEnd = 0x7ff00000;
 
 // s_waitcnt immediate for "at most n vector-memory operations outstanding" (gfx9 encoding,
 // other counters left at their maximum).
@@ -150,8 +152,8 @@ __global__ __launch_bounds__(WGM* WGN * 64, WGM* WGN / 4) void gemm_bf16_kernel(
     //    64-byte rows (BK 32): f(r) = (r >> 2) & 3         (r & 3 picks the quarter line)
     // global -> LDS: wave copy i of wave w fills rows (NW*i + w)*RPI .. +RPI-1 (lane l: row l / SPR,
     // slot l % SPR), so the lane fetches chunk (l % SPR) ^ f(row).
-    __amdgpu_buffer_rsrc_t rs_a = make_rsrc(a + (int64_t)m0 * K, (int64_t)(M - m0) * K * 2);
-    __amdgpu_buffer_rsrc_t rs_w = make_rsrc(wt + (int64_t)n0 * K, (int64_t)(N - n0) * K * 2);
+    __amdgpu_buffer_rsrc_t rs_a = make_rsrc(a + (int64_t)m0 * K, (int64_t)min(M - m0, BM) * K * 2);
+    __amdgpu_buffer_rsrc_t rs_w = make_rsrc(wt + (int64_t)n0 * K, (int64_t)min(N - n0, BN) * K * 2);
     const int ld_r = lane / SPR, ld_p = lane % SPR;
     int voff_e, voff_o;  // lane byte offset for even / odd copy index i
     if (SPR == 8) {  // row >> 3 = NW*i + w
@@ -169,14 +171,16 @@ __global__ __launch_bounds__(WGM* WGN * 64, WGM* WGN / 4) void gemm_bf16_kernel(
     const int sw_e = SPR == 8 ? ((l32 ^ (l32 >> 3)) & 7) : ((l32 >> 2) & 3);
     const int sw_o = SPR == 8 ? (sw_e ^ 4) : sw_e;
 
-// copies of K slice t_ into stage_; slices past the end are aimed beyond the resource
+// copies of K slice t_ into stage_; slices past the end are aimed beyond the resource (which covers
+// this tile's rows only, so the aim is past its end whatever the size of the whole matrix)
 #define RS_GEMM_DMA(stage_, t_)                                                                           \
     {                                                                                                     \
-        const int kb_ = (t_) < S ? (t_) * RB : 0x7ff00000;                                                \
+        const bool real_ = (t_) < S;                                                                      \
+        const int kb_ = (t_) * RB;                                                                        \
         _Pragma("unroll") for (int i = 0; i < A_LOADS; ++i)                                               \
-            dma16(rs_a, (stage_) + (i * NW + wave) * 1024, (i & 1) ? voff_o : voff_e, i * pass_bytes + kb_); \
+            dma16(rs_a, (stage_) + (i * NW + wave) * 1024, (i & 1) ? voff_o : voff_e, real_ ? i * pass_bytes + kb_ : kPastEnd); \
         _Pragma("unroll") for (int i = 0; i < W_LOADS; ++i)                                               \
-            dma16(rs_w, (stage_) + BM * RB + (i * NW + wave) * 1024, (i & 1) ? voff_o : voff_e, i * pass_bytes + kb_); \
+            dma16(rs_w, (stage_) + BM * RB + (i * NW + wave) * 1024, (i & 1) ? voff_o : voff_e, real_ ? i * pass_bytes + kb_ : kPastEnd); \
     }
 #define RS_GEMM_LOAD_FRAGS(f_, stage_, kk_)                                                               \
     {                                                                                                     \
@@ -296,8 +300,8 @@ __global__ __launch_bounds__(WGM* WGN * 64, WGM* WGN / 4) void gemm_bf16_kernel(
     const bool more = seq < x_cnt;
     if (more) {
         RS_GEMM_DECODE(seq, m0, n0)
-        rs_a = make_rsrc(a + (int64_t)m0 * K, (int64_t)(M - m0) * K * 2);
-        rs_w = make_rsrc(wt + (int64_t)n0 * K, (int64_t)(N - n0) * K * 2);
+        rs_a = make_rsrc(a + (int64_t)m0 * K, (int64_t)min(M - m0, BM) * K * 2);
+        rs_w = make_rsrc(wt + (int64_t)n0 * K, (int64_t)min(N - n0, BN) * K * 2);
     }
 
     // ---- epilogue, staged through LDS so that global traffic is row-contiguous.
