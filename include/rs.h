@@ -108,6 +108,10 @@ RS_API const char *rs_last_error(void);
 /* Library version as major*10000 + minor*100 + patch. */
 RS_API int32_t rs_version(void);
 
+/* Host string (static storage): the tile configurations the matrix kernels were built with.
+ * Counter readings carried from one profiling run to another are valid only for the same string. */
+RS_API const char *rs_build_info(void);
+
 /*
  * Measurement aid (not part of the method): while enabled, every kernel the library
  * launches is bracketed by two HIP events on the caller's stream.  rs_profile_read waits

@@ -121,6 +121,10 @@ struct GemmLnFold {
 constexpr int kGemmMaxK = 1 << 20;
 constexpr int kGemmMaxN = 1 << 24;
 
+// Tile configurations the bf16 GEMM was built with (measurements carried from one run to another
+// are only valid for the same string).
+const char* gemm_build_info();
+
 // Number of per-row partial slots the SHIFT epilogue writes for an output width N.
 int gemm_shift_slots(rs_dtype dt, int N);
 constexpr int kShiftLanes = 3;  // floats per slot (L2/L1 use the first, cosine all three)
@@ -164,6 +168,13 @@ hipError_t launch_select(const float* scores, int32_t* kept_idx, int B, int N, i
 // out[b, j, :] = src[b, kept_idx[b, j], :]
 hipError_t launch_gather(rs_dtype dt, const void* src, const int32_t* kept_idx, void* out, int B,
                          int N, int K, int D, hipStream_t s);
+
+// scores, kept_idx and gathered = f_in[kept_idx] of every image in one launch that reads f_out and
+// f_in once (images whose f_in rows fit a compute unit's registers: shift_topk_resident_fits)
+bool shift_topk_resident_fits(rs_dtype dt, int N, int D);
+hipError_t launch_shift_topk_resident(rs_dtype dt, rs_dist dist, const void* f_out, const void* f_in,
+                                      float* scores, int32_t* kept_idx, void* gathered, int B, int N, int D,
+                                      int n_prefix, int n_keep, hipStream_t s);
 
 // 2-D grid: row_scores[b, h] = mean_w scores[b, h, w], col_scores[b, w] = mean_h scores[b, h, w]
 hipError_t launch_grid_line_scores(const float* scores, float* row_scores, float* col_scores, int B, int H,

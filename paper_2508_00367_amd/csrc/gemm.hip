@@ -599,6 +599,10 @@ static hipError_t launch_f32(const void* a, const void* w, const void* bias, con
     return hipGetLastError();
 }
 
+#define RS_STR2(...) #__VA_ARGS__
+#define RS_STR(...) RS_STR2(__VA_ARGS__)
+const char* gemm_build_info() { return "bf16 gemm tiles (BM,BN,BK,stages,waves m,waves n): " RS_STR(RS_GEMM_CFG); }
+
 int gemm_shift_slots(rs_dtype dt, int N) {
     if (dt == RS_F32) return (N + 63) / 64;
     return ((N + GemmCfg::BN - 1) / GemmCfg::BN) * GemmCfg::BN / GemmCfg::WN;

@@ -106,8 +106,9 @@ __device__ __forceinline__ uint32_t score_key(float s) {
     return (u & 0x80000000u) ? ~u : (u | 0x80000000u);
 }
 
-// inclusive scan over the 256 threads of a workgroup (4 waves), values in thread order
-__device__ __forceinline__ int block_scan_incl(int v, int* s_wave /*[4]*/, int tid) {
+// inclusive scan over the NT threads of a workgroup (NT / 64 waves), values in thread order
+template <int NT>
+__device__ __forceinline__ int block_scan_incl(int v, int* s_wave /*[NT / 64]*/, int tid) {
     const int lane = tid & 63, wave = tid >> 6;
 #pragma unroll
     for (int off = 1; off < 64; off <<= 1) {
@@ -122,6 +123,81 @@ __device__ __forceinline__ int block_scan_incl(int v, int* s_wave /*[4]*/, int t
     return v + add;
 }
 
+struct SelectShared {
+    int hist[256];
+    int wave[16];
+    uint32_t prefix;
+    int remaining;
+};
+
+// Selection of one image by the NT threads of a workgroup (all of them must call it): among
+// the tokens i >= n_prefix of sc[0 .. N) the n_keep highest keys survive, equal keys by lower
+// index; out[0 .. n_prefix + n_keep) lists the prefix and the survivors in ascending order.
+// With `slot` (N ints, workgroup-visible) slot[i] becomes the position of token i in `out`, or
+// -1 for a dropped token.  `sc` may be LDS or global memory written before a barrier.
+template <int NT>
+__device__ __forceinline__ void block_select(const float* sc, int N, int n_prefix, int n_keep,
+                                             int32_t* __restrict__ out, int* slot, SelectShared& sh, int tid) {
+    for (int i = tid; i < n_prefix; i += NT) out[i] = i;
+    if (slot)
+        for (int i = tid; i < N; i += NT) slot[i] = i < n_prefix ? i : -1;
+    if (n_keep == 0) return;  // uniform over the workgroup
+
+    uint32_t prefix = 0, mask = 0;
+    int remaining = n_keep;  // how many of the candidates matching `prefix` still to take
+    for (int pass = 0; pass < 4; ++pass) {
+        const int shift = 24 - 8 * pass;
+        if (tid < 256) sh.hist[tid] = 0;
+        __syncthreads();
+        for (int i = n_prefix + tid; i < N; i += NT) {
+            const uint32_t key = score_key(sc[i]);
+            if ((key & mask) == prefix) atomicAdd(&sh.hist[(key >> shift) & 255], 1);
+        }
+        __syncthreads();
+        // suffix sums over the bins: thread t < 256 looks at bin 255 - t, so an inclusive scan in
+        // thread order counts the candidates in bins >= bin (threads beyond 255 add nothing).
+        const int bin = 255 - tid;
+        const int cnt = tid < 256 ? sh.hist[bin] : 0;
+        const int incl = block_scan_incl<NT>(cnt, sh.wave, tid);
+        // the wanted key's digit is the first bin (from the top) whose suffix count reaches `remaining`
+        if (tid < 256 && incl >= remaining && incl - cnt < remaining) {
+            sh.prefix = prefix | ((uint32_t)bin << shift);
+            sh.remaining = remaining - (incl - cnt);
+        }
+        __syncthreads();
+        prefix = sh.prefix;
+        remaining = sh.remaining;
+        mask |= 255u << shift;
+        __syncthreads();
+    }
+    // `prefix` = key of the n_keep-th largest candidate; `remaining` = how many candidates with
+    // exactly that key are kept (those with the lowest indices).
+    const uint32_t thr = prefix;
+    const int n = N - n_prefix;
+    const int seg = (n + NT - 1) / NT;
+    const int lo = n_prefix + tid * seg;
+    const int hi = min(lo + seg, N);
+    int gt = 0, eq = 0;
+    for (int i = lo; i < hi; ++i) {
+        const uint32_t key = score_key(sc[i]);
+        gt += key > thr;
+        eq += key == thr;
+    }
+    const int gt_before = block_scan_incl<NT>(gt, sh.wave, tid) - gt;
+    const int eq_before = block_scan_incl<NT>(eq, sh.wave, tid) - eq;
+    int pos = n_prefix + gt_before + min(eq_before, remaining);
+    int eq_rank = eq_before;
+    for (int i = lo; i < hi; ++i) {
+        const uint32_t key = score_key(sc[i]);
+        bool keep = key > thr;
+        if (key == thr) { keep = eq_rank < remaining; ++eq_rank; }
+        if (keep) {
+            if (slot) slot[i] = pos;
+            out[pos++] = i;
+        }
+    }
+}
+
 // With `partials` the scores are first formed from the GEMM epilogue's per-row slots (added in
 // slot order, as finalize_scores_kernel does), kept in LDS for the selection and written to
 // `scores`: the block's prune pass needs no separate score launch.  N * 4 bytes of dynamic LDS.
@@ -129,10 +205,7 @@ __global__ __launch_bounds__(256) void select_kernel(float* __restrict__ scores,
                                                      int32_t* __restrict__ kept_idx, int N,
                                                      int n_prefix, int n_keep,
                                                      const float* __restrict__ partials, int slots, int dist) {
-    __shared__ int hist[256];
-    __shared__ int s_wave[4];
-    __shared__ uint32_t s_prefix;
-    __shared__ int s_remaining;
+    __shared__ SelectShared sh;
     extern __shared__ float s_scores[];
     const int tid = threadIdx.x;
     const float* sc = scores + (int64_t)blockIdx.x * N;
@@ -155,60 +228,158 @@ __global__ __launch_bounds__(256) void select_kernel(float* __restrict__ scores,
         sc = s_scores;
         __syncthreads();
     }
+    block_select<256>(sc, N, n_prefix, n_keep, out, nullptr, sh, tid);
+}
 
-    for (int i = tid; i < n_prefix; i += 256) out[i] = i;
-    if (n_keep == 0) return;
+// ---------------------------------------------------------------------------
+// Score, selection and gather of one image in ONE pass over memory, for images whose f_in rows
+// fit the register file of a compute unit (N <= 16 NR rows of at most 512 CH bytes: every
+// image-classification shape).  One workgroup of 16 waves per image at a time: wave w holds rows
+// w, w + 16, ... of f_in in registers (8 bytes per lane and chunk), streams the same rows of f_out
+// past them for the scores, the workgroup selects, and every wave then writes its surviving rows
+// to their places in `gathered` straight from registers.  Against the three-launch path the
+// kept rows are not read a second time: memory traffic is the algorithmic minimum
+// (2 N D e read, K D e written per image).  Workgroups loop over images (persistent grid).
+// ---------------------------------------------------------------------------
+typedef unsigned int u32x2 __attribute__((ext_vector_type(2)));
+template <typename T> __device__ __forceinline__ void unpack8(u32x2 v, float (&f)[4]);
+template <> __device__ __forceinline__ void unpack8<bf16raw>(u32x2 v, float (&f)[4]) {
+    f[0] = __uint_as_float(v.x << 16); f[1] = __uint_as_float(v.x & 0xffff0000u);
+    f[2] = __uint_as_float(v.y << 16); f[3] = __uint_as_float(v.y & 0xffff0000u);
+}
+template <> __device__ __forceinline__ void unpack8<float>(u32x2 v, float (&f)[4]) {
+    f[0] = __uint_as_float(v.x); f[1] = __uint_as_float(v.y); f[2] = 0.f; f[3] = 0.f;
+}
 
-    uint32_t prefix = 0, mask = 0;
-    int remaining = n_keep;  // how many of the candidates matching `prefix` still to take
-    for (int pass = 0; pass < 4; ++pass) {
-        const int shift = 24 - 8 * pass;
-        hist[tid] = 0;
-        __syncthreads();
-        for (int i = n_prefix + tid; i < N; i += 256) {
-            const uint32_t key = score_key(sc[i]);
-            if ((key & mask) == prefix) atomicAdd(&hist[(key >> shift) & 255], 1);
+constexpr int RES_WAVES = 16;
+
+template <typename T, int DIST, int CH, int NR>
+__global__ __launch_bounds__(RES_WAVES * 64) void shift_topk_resident_kernel(
+    const T* __restrict__ f_out, const T* __restrict__ f_in, float* __restrict__ scores,
+    int32_t* __restrict__ kept_idx, T* __restrict__ gathered, int B, int N, int D, int n_prefix, int n_keep) {
+    constexpr int NT = RES_WAVES * 64;
+    __shared__ SelectShared sh;
+    __shared__ float s_scores[NR * RES_WAVES];
+    __shared__ int s_slot[NR * RES_WAVES];
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);  // wave-uniform: row addresses stay scalar
+    const int row_u = D * (int)sizeof(T) / 8;  // 8-byte units per row
+    const int K = n_prefix + n_keep;
+    // Rows are addressed through buffer resources over one image: the row offset is a scalar, the
+    // lane offset one register per chunk, and whatever lies outside (rows past N, lanes past the
+    // row's end, which are aimed far outside) reads as zero and is dropped on stores.
+    const int row_bytes = D * (int)sizeof(T);
+    int voff[CH];
+#pragma unroll
+    for (int c = 0; c < CH; ++c) voff[c] = (lane + 64 * c) < row_u ? (lane + 64 * c) * 8 : 0x7fff0000;
+    for (int b = blockIdx.x; b < B; b += gridDim.x) {
+        const __amdgpu_buffer_rsrc_t r_in = __builtin_amdgcn_make_buffer_rsrc(
+            const_cast<T*>(f_in + (int64_t)b * N * D), 0, N * row_bytes, 0x00020000);
+        const __amdgpu_buffer_rsrc_t r_fo = __builtin_amdgcn_make_buffer_rsrc(
+            const_cast<T*>(f_out + (int64_t)b * N * D), 0, N * row_bytes, 0x00020000);
+        u32x2 keep[NR][CH];
+#pragma unroll
+        for (int k = 0; k < NR; ++k)
+#pragma unroll
+            for (int c = 0; c < CH; ++c)
+                keep[k][c] = __builtin_amdgcn_raw_buffer_load_b64(r_in, voff[c], (wave + RES_WAVES * k) * row_bytes, 0);
+        __builtin_amdgcn_sched_barrier(0);
+        constexpr int G = CH == 3 ? 2 : 4;  // rows of f_out in flight per wave (next to the resident rows)
+#pragma unroll
+        for (int k0 = 0; k0 < NR; k0 += G) {
+            u32x2 t[G][CH];
+#pragma unroll
+            for (int kk = 0; kk < G; ++kk)
+#pragma unroll
+                for (int c = 0; c < CH; ++c)
+                    if (k0 + kk < NR)
+                        t[kk][c] = __builtin_amdgcn_raw_buffer_load_b64(r_fo, voff[c], (wave + RES_WAVES * (k0 + kk)) * row_bytes, 0);
+#pragma unroll
+            for (int kk = 0; kk < G; ++kk) {
+                if (k0 + kk >= NR) break;
+                const int i = wave + RES_WAVES * (k0 + kk);
+                float p0 = 0.f, p1 = 0.f, p2 = 0.f;
+#pragma unroll
+                for (int c = 0; c < CH; ++c) {
+                    float x[4], y[4];
+                    unpack8<T>(t[kk][c], x);
+                    unpack8<T>(keep[k0 + kk][c], y);
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) {
+                        if (DIST == RS_DIST_L2) { float d = x[e] - y[e]; p0 = fmaf(d, d, p0); }
+                        else if (DIST == RS_DIST_L1) { p0 += fabsf(x[e] - y[e]); }
+                        else { p0 = fmaf(x[e], y[e], p0); p1 = fmaf(x[e], x[e], p1); p2 = fmaf(y[e], y[e], p2); }
+                    }
+                }
+                p0 = wave_sum(p0);
+                if (DIST == RS_DIST_COS) { p1 = wave_sum(p1); p2 = wave_sum(p2); }
+                if (lane == 0 && i < N) {
+                    float sc;
+                    if (DIST == RS_DIST_L2) sc = sqrtf(p0);
+                    else if (DIST == RS_DIST_L1) sc = p0;
+                    else sc = 1.0f - p0 / (sqrtf(p1) * sqrtf(p2));
+                    s_scores[i] = sc;
+                    scores[(int64_t)b * N + i] = sc;
+                }
+            }
+            __builtin_amdgcn_sched_barrier(0);  // the next group's loads stay behind this group's sums
         }
         __syncthreads();
-        // suffix sums over the bins: thread t looks at bin 255 - t, so an inclusive scan in
-        // thread order counts the candidates in bins >= bin.
-        const int bin = 255 - tid;
-        const int cnt = hist[bin];
-        const int incl = block_scan_incl(cnt, s_wave, tid);
-        // the wanted key's digit is the first bin (from the top) whose suffix count reaches `remaining`
-        if (incl >= remaining && incl - cnt < remaining) {
-            s_prefix = prefix | ((uint32_t)bin << shift);
-            s_remaining = remaining - (incl - cnt);
+        block_select<NT>(s_scores, N, n_prefix, n_keep, kept_idx + (int64_t)b * K, s_slot, sh, tid);
+        __syncthreads();
+        const __amdgpu_buffer_rsrc_t r_out = __builtin_amdgcn_make_buffer_rsrc(
+            gathered + (int64_t)b * K * D, 0, K * row_bytes, 0x00020000);
+#pragma unroll
+        for (int k = 0; k < NR; ++k) {
+            const int i = wave + RES_WAVES * k;
+            const int j = i < N ? s_slot[i] : -1;  // wave-uniform
+            if (j >= 0) {
+#pragma unroll
+                for (int c = 0; c < CH; ++c)
+                    __builtin_amdgcn_raw_buffer_store_b64(keep[k][c], r_out, voff[c], __builtin_amdgcn_readfirstlane(j) * row_bytes, 0);
+            }
         }
-        __syncthreads();
-        prefix = s_prefix;
-        remaining = s_remaining;
-        mask |= 255u << shift;
-        __syncthreads();
+        __syncthreads();  // s_scores and s_slot are reused by the next image
     }
-    // `prefix` = key of the n_keep-th largest candidate; `remaining` = how many candidates with
-    // exactly that key are kept (those with the lowest indices).
-    const uint32_t thr = prefix;
-    const int n = N - n_prefix;
-    const int seg = (n + 255) / 256;
-    const int lo = n_prefix + tid * seg;
-    const int hi = min(lo + seg, N);
-    int gt = 0, eq = 0;
-    for (int i = lo; i < hi; ++i) {
-        const uint32_t key = score_key(sc[i]);
-        gt += key > thr;
-        eq += key == thr;
-    }
-    const int gt_before = block_scan_incl(gt, s_wave, tid) - gt;
-    const int eq_before = block_scan_incl(eq, s_wave, tid) - eq;
-    int pos = n_prefix + gt_before + min(eq_before, remaining);
-    int eq_rank = eq_before;
-    for (int i = lo; i < hi; ++i) {
-        const uint32_t key = score_key(sc[i]);
-        bool keep = key > thr;
-        if (key == thr) { keep = eq_rank < remaining; ++eq_rank; }
-        if (keep) out[pos++] = i;
-    }
+}
+
+constexpr int RES_NR = 13;  // rows per wave: N <= 208
+
+bool shift_topk_resident_fits(rs_dtype dt, int N, int D) {
+    return N <= RES_NR * RES_WAVES && (size_t)D * elem_size(dt) <= 512 * 3;
+}
+
+template <typename T, int CH>
+static hipError_t launch_resident_t(rs_dist dist, const void* f_out, const void* f_in, float* scores,
+                                    int32_t* kept_idx, void* gathered, int B, int N, int D, int n_prefix,
+                                    int n_keep, int grid, hipStream_t s) {
+#define RS_RES_LAUNCH(DIST_)                                                                                  \
+    hipLaunchKernelGGL((shift_topk_resident_kernel<T, DIST_, CH, RES_NR>), dim3(grid), dim3(RES_WAVES * 64), 0, s, \
+                       (const T*)f_out, (const T*)f_in, scores, kept_idx, (T*)gathered, B, N, D, n_prefix, n_keep)
+    if (dist == RS_DIST_L2) RS_RES_LAUNCH(RS_DIST_L2);
+    else if (dist == RS_DIST_L1) RS_RES_LAUNCH(RS_DIST_L1);
+    else RS_RES_LAUNCH(RS_DIST_COS);
+#undef RS_RES_LAUNCH
+    return hipGetLastError();
+}
+
+hipError_t launch_shift_topk_resident(rs_dtype dt, rs_dist dist, const void* f_out, const void* f_in,
+                                      float* scores, int32_t* kept_idx, void* gathered, int B, int N, int D,
+                                      int n_prefix, int n_keep, hipStream_t s) {
+    if (B == 0 || N == 0) return hipSuccess;
+    static const int cus = [] {
+        int dev = 0, n = 0;
+        if (hipGetDevice(&dev) != hipSuccess || hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n < 1) n = 256;
+        return n;
+    }();
+    const int grid = B < cus ? B : cus;  // one workgroup fills a compute unit's register file
+    const int ch = (int)(((size_t)D * elem_size(dt) + 511) / 512);
+#define RS_RES_CH(T_)                                                                                                   \
+    (ch == 1 ? launch_resident_t<T_, 1>(dist, f_out, f_in, scores, kept_idx, gathered, B, N, D, n_prefix, n_keep, grid, s) \
+     : ch == 2 ? launch_resident_t<T_, 2>(dist, f_out, f_in, scores, kept_idx, gathered, B, N, D, n_prefix, n_keep, grid, s) \
+               : launch_resident_t<T_, 3>(dist, f_out, f_in, scores, kept_idx, gathered, B, N, D, n_prefix, n_keep, grid, s))
+    return dt == RS_F32 ? RS_RES_CH(float) : RS_RES_CH(bf16raw);
+#undef RS_RES_CH
 }
 
 // kept_idx[b, j] = j when every token survives
@@ -242,21 +413,34 @@ hipError_t launch_select_from_partials(rs_dist dist, const float* partials, int 
 }
 
 // ---------------------------------------------------------------------------
-// Gather: out[b, j, :] = src[b, kept_idx[b, j], :]; one wavefront per row, 16 bytes per
-// lane per step (rows are D * e bytes, a multiple of 16).
+// Gather: out[b, j, :] = src[b, kept_idx[b, j], :].  The output is one contiguous run of
+// 16-byte vectors; thread t copies vectors t, t + 256, ... of its workgroup's stretch (four per
+// thread, all loads issued before the stores), so every lane works whatever the row length
+// (rows are D * e bytes, a multiple of 16).
 // ---------------------------------------------------------------------------
+constexpr int GATHER_UNROLL = 4;
+
 __global__ __launch_bounds__(256) void gather_rows_kernel(const uint4* __restrict__ src,
                                                           const int32_t* __restrict__ kept_idx,
-                                                          uint4* __restrict__ out, int64_t rows,
+                                                          uint4* __restrict__ out, int64_t total_vec,
                                                           int N, int K, int row_vec) {
-    const int lane = threadIdx.x & 63;
-    const int64_t r = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
-    if (r >= rows) return;
-    const int64_t b = r / K;
-    const int32_t idx = kept_idx[r];
-    const uint4* s = src + (b * N + idx) * row_vec;
-    uint4* d = out + r * row_vec;
-    for (int c = lane; c < row_vec; c += 64) d[c] = s[c];
+    const int64_t base = (int64_t)blockIdx.x * (256 * GATHER_UNROLL) + threadIdx.x;
+    uint4 v[GATHER_UNROLL];
+#pragma unroll
+    for (int u = 0; u < GATHER_UNROLL; ++u) {
+        const int64_t t = base + u * 256;
+        if (t < total_vec) {
+            const int64_t r = t / row_vec;           // output row b * K + j
+            const int c = (int)(t - r * row_vec);
+            const int64_t b = r / K;
+            v[u] = src[(b * N + kept_idx[r]) * row_vec + c];
+        }
+    }
+#pragma unroll
+    for (int u = 0; u < GATHER_UNROLL; ++u) {
+        const int64_t t = base + u * 256;
+        if (t < total_vec) out[t] = v[u];
+    }
 }
 
 hipError_t launch_gather(rs_dtype dt, const void* src, const int32_t* kept_idx, void* out, int B,
@@ -264,8 +448,10 @@ hipError_t launch_gather(rs_dtype dt, const void* src, const int32_t* kept_idx, 
     const int64_t rows = (int64_t)B * K;
     if (rows == 0) return hipSuccess;
     const int row_vec = (int)((size_t)D * elem_size(dt) / 16);
-    hipLaunchKernelGGL(gather_rows_kernel, dim3((unsigned)((rows + 3) / 4)), dim3(256), 0, s,
-                       (const uint4*)src, kept_idx, (uint4*)out, rows, N, K, row_vec);
+    const int64_t total_vec = rows * row_vec;
+    const int64_t per_wg = 256 * GATHER_UNROLL;
+    hipLaunchKernelGGL(gather_rows_kernel, dim3((unsigned)((total_vec + per_wg - 1) / per_wg)), dim3(256), 0, s,
+                       (const uint4*)src, kept_idx, (uint4*)out, total_vec, N, K, row_vec);
     return hipGetLastError();
 }
 

@@ -6,6 +6,7 @@
 #include <stdio.h>
 #include <string.h>
 
+#include <atomic>
 #include <mutex>
 #include <vector>
 
@@ -28,6 +29,13 @@ rs_status device_error(const char* what, hipError_t e) {
 }
 
 static bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+// [a, a + na) and [b, b + nb) share a byte (NULL or empty ranges never do)
+static bool overlaps(const void* a, size_t na, const void* b, size_t nb) {
+    if (!a || !b || na == 0 || nb == 0) return false;
+    const uintptr_t pa = reinterpret_cast<uintptr_t>(a), pb = reinterpret_cast<uintptr_t>(b);
+    return pa < pb + nb && pb < pa + na;
+}
 
 #define RS_REQUIRE(cond, status, ...)  \
     do {                               \
@@ -53,7 +61,7 @@ static const char* const kClassNames[K_COUNT] = {"pack_weights", "layernorm", "g
 struct ProfRec { int cls; hipEvent_t start, stop; };
 static struct {
     std::mutex mu;
-    bool on = false;
+    std::atomic<bool> on{false};  // read on every launch without the mutex
     std::vector<ProfRec> recs;
     std::vector<hipEvent_t> pool;
 } g_prof;
@@ -72,16 +80,17 @@ static hipEvent_t prof_event() {
 // Runs `launch` and, when profiling is on, brackets it with two events on `s`.
 template <typename F>
 static hipError_t timed(int cls, hipStream_t s, F launch) {
-    if (!g_prof.on) return launch();
+    if (!g_prof.on.load(std::memory_order_relaxed)) return launch();
     std::lock_guard<std::mutex> lk(g_prof.mu);
     hipEvent_t a = prof_event(), b = prof_event();
-    if (!a || !b) return hipErrorOutOfMemory;
-    hipError_t e = hipEventRecord(a, s);
-    if (e != hipSuccess) return e;
-    e = launch();
-    if (e != hipSuccess) return e;
-    e = hipEventRecord(b, s);
-    if (e != hipSuccess) return e;
+    hipError_t e = (a && b) ? hipEventRecord(a, s) : hipErrorOutOfMemory;
+    if (e == hipSuccess) e = launch();
+    if (e == hipSuccess) e = hipEventRecord(b, s);
+    if (e != hipSuccess) {  // nothing recorded: the events go back to the pool
+        if (a) g_prof.pool.push_back(a);
+        if (b) g_prof.pool.push_back(b);
+        return e;
+    }
     g_prof.recs.push_back({cls, a, b});
     return hipSuccess;
 }
@@ -153,11 +162,13 @@ static rs_status check_cfg(const rs_block_cfg* c) {
     RS_REQUIRE(c->op >= RS_SHIFT_MLP && c->op <= RS_SHIFT_MLP_NORMED, RS_ERR_INVALID_ARG,
                "unknown shift operation %d", (int)c->op);
     RS_REQUIRE(c->B >= 0 && c->N >= 0, RS_ERR_INVALID_ARG, "negative B or N");
+    RS_REQUIRE(c->B <= 65535, RS_ERR_UNSUPPORTED, "B %d > 65535 (one launch-grid axis of the attention kernels)", c->B);
     RS_REQUIRE(c->D > 0 && c->H > 0 && c->Dm > 0, RS_ERR_INVALID_ARG, "D, H, Dm must be positive");
     RS_REQUIRE(c->D % c->H == 0, RS_ERR_INVALID_ARG, "D %d not divisible by H %d", c->D, c->H);
     RS_REQUIRE(c->D / c->H == 64, RS_ERR_UNSUPPORTED, "head width D/H = %d, only 64 is built", c->D / c->H);
     RS_REQUIRE(c->Dm % 64 == 0, RS_ERR_UNSUPPORTED, "Dm %d is not a multiple of 64", c->Dm);
     RS_REQUIRE(c->D <= 4096, RS_ERR_UNSUPPORTED, "D %d > 4096", c->D);
+    RS_REQUIRE(c->Dm <= kGemmMaxK, RS_ERR_UNSUPPORTED, "Dm %d > %d", c->Dm, kGemmMaxK);
     RS_REQUIRE((int64_t)c->B * c->N < (int64_t)1 << 31, RS_ERR_UNSUPPORTED, "B*N does not fit 31 bits");
     // bf16 attention addresses one image's rows of the [N, 3D] QKV buffer with 32-bit byte offsets
     RS_REQUIRE(c->dtype != RS_BF16 || ((int64_t)c->N + 256) * 3 * c->D * 2 < (int64_t)0x7fffffff, RS_ERR_UNSUPPORTED,
@@ -173,15 +184,21 @@ static rs_status check_cfg(const rs_block_cfg* c) {
 
 using namespace rs;
 
+static rs_status block_fwd(const rs_block_cfg* cfg, const rs_block_weights* w, const void* x, void* y,
+                           int32_t* kept_idx, float* scores, void* workspace, size_t workspace_bytes,
+                           void* hip_stream);
+
 extern "C" {
 
 const char* rs_last_error(void) { return g_err; }
 
-int32_t rs_version(void) { return 101; }
+int32_t rs_version(void) { return 200; }
+
+const char* rs_build_info(void) { return gemm_build_info(); }
 
 rs_status rs_profile_enable(int32_t enable) {
     std::lock_guard<std::mutex> lk(g_prof.mu);
-    g_prof.on = enable != 0;
+    g_prof.on.store(enable != 0);
     return RS_OK;
 }
 
@@ -266,6 +283,12 @@ rs_status rs_shift_topk(const void* f_out, const void* f_in, const void* src, in
     RS_REQUIRE(gathered == nullptr || gathered != s, RS_ERR_INVALID_ARG, "gathered must not alias src");
     hipStream_t st = (hipStream_t)hip_stream;
     const int K = n_prefix + n_keep;
+    if (gathered && s == f_in && K > 0 && shift_topk_resident_fits(dtype, N, D)) {
+        // small images: one pass over memory, the rows to keep never leave the registers
+        RS_LAUNCH_K(K_SCORE, st, launch_shift_topk_resident(dtype, dist, f_out, f_in, scores, kept_idx, gathered, B, N, D,
+                                                          n_prefix, n_keep, st));
+        return RS_OK;
+    }
     RS_LAUNCH_K(K_SCORE, st, launch_shift_scores(dtype, dist, f_out, f_in, scores, (int64_t)B * N, D, st));
     RS_LAUNCH_K(K_SELECT, st, launch_select(scores, kept_idx, B, N, n_prefix, n_keep, st));
     if (gathered) RS_LAUNCH_K(K_GATHER, st, launch_gather(dtype, s, kept_idx, gathered, B, N, K, D, st));
@@ -366,6 +389,8 @@ rs_status rs_linear_fwd(const void* a, const void* w, const void* bias, const vo
     RS_REQUIRE(M >= 0 && M < ((int64_t)1 << 31), RS_ERR_INVALID_ARG, "M out of range");
     RS_REQUIRE(N > 0 && K > 0, RS_ERR_INVALID_ARG, "N and K must be positive");
     RS_REQUIRE(N % 64 == 0 && K % 64 == 0, RS_ERR_UNSUPPORTED, "N and K must be multiples of 64");
+    // a tile's rows are addressed with 32-bit byte offsets from the tile's first row
+    RS_REQUIRE(K <= kGemmMaxK && N <= kGemmMaxN, RS_ERR_UNSUPPORTED, "K > %d or N > %d", kGemmMaxK, kGemmMaxN);
     if (M == 0) return RS_OK;
     RS_REQUIRE(a && w && out, RS_ERR_INVALID_ARG, "a, w and out must not be NULL");
     RS_REQUIRE(epi != RS_EPI_BIAS_RES || res, RS_ERR_INVALID_ARG, "res must not be NULL for RS_EPI_BIAS_RES");
@@ -386,6 +411,14 @@ size_t rs_block_workspace_size(const rs_block_cfg* cfg) {
 rs_status rs_block_fwd(const rs_block_cfg* cfg, const rs_block_weights* w, const void* x, void* y,
                        int32_t* kept_idx, float* scores, void* workspace, size_t workspace_bytes,
                        void* hip_stream) {
+    return block_fwd(cfg, w, x, y, kept_idx, scores, workspace, workspace_bytes, hip_stream);
+}
+
+}  // extern "C"
+
+static rs_status block_fwd(const rs_block_cfg* cfg, const rs_block_weights* w, const void* x, void* y,
+                           int32_t* kept_idx, float* scores, void* workspace, size_t workspace_bytes,
+                           void* hip_stream) {
     rs_status st = check_cfg(cfg);
     if (st != RS_OK) return st;
     st = check_weights(w);
@@ -403,6 +436,14 @@ rs_status rs_block_fwd(const rs_block_cfg* cfg, const rs_block_weights* w, const
                "workspace must be 256-byte aligned");
     RS_REQUIRE(aligned16(x) && aligned16(y), RS_ERR_INVALID_ARG, "x and y must be 16-byte aligned");
     RS_REQUIRE(x != y, RS_ERR_INVALID_ARG, "y must not alias x");
+    {   // the kernels write y, kept_idx and scores while workspace tensors are still being read
+        const size_t e = elem_size(c.dtype), M_ = (size_t)c.B * c.N;
+        RS_REQUIRE(!overlaps(workspace, L.total, x, M_ * c.D * e) &&
+                   !overlaps(workspace, L.total, y, (size_t)c.B * K * c.D * e) &&
+                   !overlaps(workspace, L.total, kept_idx, (size_t)c.B * K * sizeof(int32_t)) &&
+                   !overlaps(workspace, L.total, scores, M_ * sizeof(float)),
+                   RS_ERR_INVALID_ARG, "x, y, kept_idx and scores must lie outside the workspace");
+    }
 
     hipStream_t s = (hipStream_t)hip_stream;
     char* ws = (char*)workspace;
@@ -491,5 +532,3 @@ rs_status rs_block_fwd(const rs_block_cfg* cfg, const rs_block_weights* w, const
     if (prune) RS_LAUNCH_K(K_GATHER, s, launch_gather(dt, xhat, kept_idx, y, c.B, c.N, K, D, s));
     return RS_OK;
 }
-
-}  // extern "C"

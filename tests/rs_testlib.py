@@ -34,6 +34,16 @@ def norm_err(got, ref):
     return float(np.abs(got - ref).max() / (den if den > 0 else 1.0))
 
 
+def rel_err_floor(got, ref, floor=1e-3):
+    """max over elements of |got - ref| / max(|ref|, floor * max|ref|): per-element relative error
+    with an absolute floor (reported next to norm_err, not bounded by the tolerance: an element
+    much smaller than the tensor's largest carries the same absolute rounding error)."""
+    ref = np.asarray(ref, np.float64)
+    got = np.asarray(got, np.float64)
+    den = np.maximum(np.abs(ref), floor * max(np.abs(ref).max(), 1e-300))
+    return float((np.abs(got - ref) / den).max())
+
+
 def check_kept_admissible(kept_gpu, scores_gpu, scores_ref, n_prefix, n_keep):
     """kept_idx must equal the checker's selection except for tokens whose checker score
     lies within 2*tau of the checker's threshold score, tau = max |s_gpu - s_ref| of the image.

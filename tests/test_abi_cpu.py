@@ -62,6 +62,8 @@ def test_block_rejects_bad_config():
                      (dict(dist=9), rs.RS_ERR_INVALID_ARG),
                      (dict(op=5), rs.RS_ERR_INVALID_ARG),           # beyond the five shift operations
                      (dict(op=-1), rs.RS_ERR_INVALID_ARG),
+                     (dict(B=70000, N=2, n_keep=1), rs.RS_ERR_UNSUPPORTED),   # beyond one launch-grid axis
+                     (dict(Dm=1 << 21), rs.RS_ERR_UNSUPPORTED),      # fc2's K beyond a tile's 32-bit byte offsets
                      (dict(B=-1), rs.RS_ERR_INVALID_ARG)]:
         cfg = _cfg(**kw)
         st = rs.lib().rs_block_fwd(ctypes.byref(cfg), ctypes.byref(w), FAKE, FAKE * 2, FAKE * 3, None,
@@ -93,6 +95,14 @@ def test_block_rejects_bad_pointers_and_workspace():
     assert call(_weights(w_fc1=None), FAKE, 2 * FAKE, 3 * FAKE, 16 * FAKE, need) == rs.RS_ERR_INVALID_ARG
     assert L.rs_block_fwd(None, ctypes.byref(w), FAKE, FAKE, FAKE, None, FAKE, need, None) == rs.RS_ERR_INVALID_ARG
     assert L.rs_block_fwd(ctypes.byref(cfg), None, FAKE, 2 * FAKE, FAKE, None, FAKE, need, None) == rs.RS_ERR_INVALID_ARG
+    # outputs (or the input) inside the workspace: the kernels would overwrite tensors still in use
+    ws0 = 1 << 30
+    assert call(w, FAKE, ws0 + 256, 3 * FAKE, ws0, need) == rs.RS_ERR_INVALID_ARG
+    assert "outside the workspace" in rs.rs_last_error()
+    assert call(w, FAKE, 2 * FAKE, ws0 + need - 16, ws0, need) == rs.RS_ERR_INVALID_ARG
+    assert call(w, ws0 + 1024, 2 * FAKE, 3 * FAKE, ws0, need) == rs.RS_ERR_INVALID_ARG
+    assert L.rs_block_fwd(ctypes.byref(cfg), ctypes.byref(w), FAKE, 2 * FAKE, 3 * FAKE, ws0 + 4096, ws0, need,
+                          None) == rs.RS_ERR_INVALID_ARG      # scores
     # empty batch is a successful no-op that never reaches the device
     cfg0 = _cfg(B=0)
     assert L.rs_block_fwd(ctypes.byref(cfg0), ctypes.byref(w), None, None, None, None, None, 0, None) == rs.RS_OK
@@ -156,6 +166,24 @@ def test_grid_line_prune_rejects_bad_arguments():
     assert call(dt=5) == rs.RS_ERR_INVALID_ARG
     assert call(B=0, fo=None) == rs.RS_OK
     assert "keep_rows" in rs.rs_last_error() or rs.rs_last_error() != ""
+
+
+def test_linear_rejects_bad_arguments():
+    L = rs.lib()
+
+    def call(a=FAKE, w=2 * FAKE, bias=None, res=None, out=3 * FAKE, M=10, N=128, K=128, epi=rs.RS_EPI_BIAS,
+             dt=rs.RS_BF16):
+        return L.rs_linear_fwd(a, w, bias, res, out, M, N, K, epi, dt, None)
+
+    assert call(N=100) == rs.RS_ERR_UNSUPPORTED
+    assert call(K=96) == rs.RS_ERR_UNSUPPORTED
+    assert call(K=1 << 21) == rs.RS_ERR_UNSUPPORTED        # a tile's rows beyond 32-bit byte offsets
+    assert call(M=1 << 31) == rs.RS_ERR_INVALID_ARG
+    assert call(epi=rs.RS_EPI_BIAS_RES) == rs.RS_ERR_INVALID_ARG   # residual missing
+    assert call(out=FAKE) == rs.RS_ERR_INVALID_ARG          # aliases a
+    assert call(a=None) == rs.RS_ERR_INVALID_ARG
+    assert call(epi=7) == rs.RS_ERR_INVALID_ARG
+    assert call(M=0, a=None) == rs.RS_OK
 
 
 def test_pack_weights_validation():

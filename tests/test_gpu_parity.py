@@ -116,6 +116,53 @@ def test_attention_large_logits_and_separate_tensors(dtype):
     assert norm_err(got, ref) < TOL[dtype]
 
 
+@pytest.mark.parametrize("N", [65, 197, 300, 1060])
+def test_attention_rows_behind_the_last_key_are_never_used(N):
+    """The bf16 kernels copy whole 64-key tiles and rely on rows past N arriving as zeros (a padded V
+    row holding NaN or Inf would poison the output through 0 x NaN).  Here q, k, v are the first N
+    tokens of a longer NaN-filled allocation, for the last image too, so a bound that is off by a
+    row shows up as a non-finite output."""
+    B, H, PAD = 3, 4, 80
+    _say("attention nan-padded", N)
+    qkv = host_round(si.generic(13, 1, (B, N, 3, H, 64)), "bf16")
+    big = torch.full((B, N + PAD, 3, H, 64), float("nan"), device="cuda", dtype=torch.bfloat16)
+    big[:, :N] = to_dev(qkv, "bf16")
+    o = torch.full((B, N, H, 64), float("nan"), device="cuda", dtype=torch.bfloat16)
+    d = big[:, :N]
+    rs.rs_attention_fwd(d[:, :, 0], d[:, :, 1], d[:, :, 2], o, 0.125)
+    torch.cuda.synchronize()
+    got = to_host(o)
+    assert np.isfinite(got).all()
+    ref = oracle.attention(qkv[:, :, 0], qkv[:, :, 1], qkv[:, :, 2], 0.125)
+    assert norm_err(got, ref) < TOL["bf16"]
+
+
+@pytest.mark.parametrize("N", [65, 197, 300])
+def test_block_with_poisoned_workspace(N):
+    """The workspace arrives full of 0xFF bytes (NaN in every float format): every scratch tensor
+    must be written before it is read, and rows past the last token of the last image (which, in
+    the packed QKV buffer, are whatever the workspace held) must not reach any output."""
+    B, D, H, Dm, P, K = 2, 128, 2, 256, 1, N // 2
+    _say("block poisoned workspace", N)
+    x, w = _block_inputs(14, B, N, D, Dm, "bf16", std=0.05, spread=0.3)
+    dw = {k: to_dev(v, "bf16") for k, v in w.items()}
+    dx = to_dev(x, "bf16")
+    cfg = rs.make_cfg(B, N, D, H, Dm, P, K, torch.bfloat16)
+    ws = torch.full((rs.rs_block_workspace_size(cfg) + 4096,), 0xFF, dtype=torch.uint8, device="cuda")
+    y = torch.full((B, P + K, D), float("nan"), device="cuda", dtype=torch.bfloat16)
+    kept = torch.full((B, P + K), -1, device="cuda", dtype=torch.int32)
+    scores = torch.full((B, N), float("nan"), device="cuda", dtype=torch.float32)
+    rs.rs_block_fwd(cfg, rs.make_weights(dw), dx, y, kept, scores, ws)
+    torch.cuda.synchronize()
+    assert (ws[-4096:] == 0xFF).all()                      # nothing written past the stated size
+    ref = oracle.block(x, w, H)
+    s, kept_h = to_host(scores), kept.cpu().numpy()
+    assert np.isfinite(s).all() and np.isfinite(to_host(y)).all()
+    assert norm_err(s, ref["scores"]) < TOL["bf16"]
+    check_kept_admissible(kept_h, s, ref["scores"], P, K)
+    assert norm_err(to_host(y), oracle.gather(ref["xhat"], kept_h)) < TOL["bf16"]
+
+
 def test_attention_closed_forms_on_gpu():
     # identical keys -> mean of V; V = 1 -> 1
     B, N, H = 1, 100, 1
@@ -169,6 +216,40 @@ def test_shift_topk(dtype, dist, B, N, D, P, K):
     check_kept_admissible(kept, s, s_ref, P, K)
     # gather is a copy of the selected rows
     np.testing.assert_array_equal(g, oracle.gather(src, kept))
+
+
+# Images whose rows fit a compute unit's registers take the one-pass kernel when the rows to gather
+# are f_in's own (src NULL): rows per wave from 1 to 13, row chunks of 1, 2 and 3 x 512 bytes with
+# ragged ends, more images than workgroups (the grid is persistent), prefix-only and keep-all.
+RESIDENT_CASES = [  # B, N, D, n_prefix, n_keep
+    (3, 17, 64, 1, 7), (4, 197, 768, 1, 177), (2, 208, 384, 0, 100), (300, 33, 192, 1, 20), (2, 1, 8, 1, 0),
+    (2, 197, 192, 1, 196), (3, 100, 520, 2, 0), (2, 16, 256, 0, 16), (1, 207, 760, 1, 1)]
+
+
+@pytest.mark.parametrize("dtype", ["bf16", "f32"])
+@pytest.mark.parametrize("dist", [rs.RS_DIST_L2, rs.RS_DIST_L1, rs.RS_DIST_COS])
+@pytest.mark.parametrize("B,N,D,P,K", RESIDENT_CASES)
+def test_shift_topk_one_pass(dtype, dist, B, N, D, P, K):
+    if dtype == "f32" and D * 4 > 1536:
+        pytest.skip("fp32 rows beyond 1536 bytes take the three-launch path (covered by test_shift_topk)")
+    _say("shift_topk one pass", dtype, dist, B, N, D, P, K)
+    f_in = host_round(si.tokens(3, B, N, D, spread=0.5), dtype)
+    f_out = host_round(f_in + si.generic(3, 8, (B, N, D), std=0.3) * np.exp(si.generic(3, 9, (B, N, 1), std=0.7)), dtype)
+    sample = sorted(set([0, B // 2, B - 1]))      # the checker on a few images when the batch is large
+    s_ref, kept_ref, g_ref = oracle.shift_topk(f_out[sample], f_in[sample], None, P, K, dist)
+    s, kept, g = _run_shift_topk(f_out, f_in, None, P, K, dist, dtype)
+    # fp32 sums of identical inputs; 1 - cos cancels, so the cosine score carries an absolute error of
+    # a few ulps of 1 whatever its size
+    assert (np.abs(s[sample] - s_ref).max() < 2e-6) if dist == rs.RS_DIST_COS else (norm_err(s[sample], s_ref) < 1e-5)
+    np.testing.assert_array_equal(kept, oracle.topk(s, P, K))           # exact on the GPU's own scores, every image
+    check_kept_admissible(kept[sample], s[sample], s_ref, P, K)
+    np.testing.assert_array_equal(g, oracle.gather(f_in, kept))         # every image: a copy of the kept rows
+    # the three-launch path (taken when the rows come from another tensor) agrees
+    s3, kept3, g3 = _run_shift_topk(f_out, f_in, f_in.copy(), P, K, dist, dtype)
+    assert np.abs(s3 - s).max() <= 1e-6 * max(np.abs(s).max(), 1.0)
+    same = (kept3 == kept).all(axis=1)
+    assert same.mean() > 0.9
+    np.testing.assert_array_equal(g3[same], g[same])
 
 
 @pytest.mark.parametrize("dtype", ["bf16", "f32"])
