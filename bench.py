@@ -10,7 +10,9 @@ part of the path.
 Prints ONE JSON line (see the keys below).  `roofline` is measured live: after the timed
 region the same steps are replayed with the library's per-kernel HIP-event timing on the
 launch stream; `cpu_baseline` times the fp64 CPU checker on a bounded sample of the same
-workload on this machine's host cores.
+workload on this machine's host cores.  Unless --no-extras is given the line also carries
+the unpruned run of the same stack, the other BASELINE workloads (a few steps each), the
+prune pass alone on an HBM-resident shape and the fused attention alone at the long video shape.
 """
 from __future__ import annotations
 
@@ -39,8 +41,9 @@ def parse():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-sample", type=int, default=0, help="images for the CPU baseline (0 = auto)")
     ap.add_argument("--no-extras", action="store_true",
-                    help="skip the two side measurements: rs_shift_topk alone on an HBM-resident shape (B=4096, "
-                         "N=197, D=768) and rs_attention_fwd alone at the long video shape (4 x 4097 tokens x 16 heads)")
+                    help="skip the side measurements: the unpruned stack, the other BASELINE workloads, "
+                         "rs_shift_topk alone on an HBM-resident shape (B=4096, N=197, D=768) and "
+                         "rs_attention_fwd alone at the long video shape (4 x 4097 tokens x 16 heads)")
     ap.add_argument("--streams", type=int, default=2,
                     help="the batch is cut into this many equal parts, each run block by block on a HIP stream of "
                          "its own: images are independent, and the parts' kernels fill each other's idle CUs "
@@ -54,15 +57,52 @@ def parse():
     return ap.parse_args()
 
 
-# HBM bytes per launch (fetch + write) from the rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of this
-# script, scaled by what the same counters read for a 1 GiB device copy (fetch x2.000, write x1.000);
-# the runs and their per-kernel table are profiles/vit_b16_forward_hbm_traffic.md.  Counters cannot
-# be read from inside the process, so the figure is carried here; None where no run was made.
+# HBM bytes per launch (fetch + write) of the dominant kernel from the rocprofv3 --pmc FETCH_SIZE /
+# WRITE_SIZE runs of this script (profiles/vit_b16_forward_hbm_traffic.md gives the commands and the
+# scaling by a device copy of known size).  Counters cannot be read from inside the process, so the
+# figure is carried here together with the build string it was measured under; a library built with
+# other tile configurations gets no carried figure.
 MEASURED_HBM_BYTES_PER_LAUNCH = {
-    ("vit_b16", False, "gemm_fc2"): 556.4e6,   # the 8 of 12 launches that carry the shift epilogue
-    ("vit_b16", False, "gemm_fc1"): 574.5e6,
-    ("vit_b16", False, "gemm_qkv"): 445.0e6,
+    # (workload, unpruned, kernel class): (bytes per launch, rs_build_info() of the measured build)
 }
+
+
+def build_stack(rs, si, torch, name, streams, unpruned=False):
+    wl = dict(si.WORKLOADS[name])
+    assert wl["dtype"] == "bf16"
+    tdt = torch.bfloat16
+
+    def up(arr):
+        return torch.from_numpy(si.round_to_bf16(arr)).to("cuda", tdt)
+
+    x0 = up(si.tokens(0, wl["B"], wl["N"], wl["D"]))
+    ws = [{k: up(v) for k, v in si.block_weights(0, l, wl["D"], wl["Dm"]).items()} for l in range(wl["blocks"])]
+    return wl, rs.EncoderStack(wl, x0, ws, streams=streams, unpruned=unpruned)
+
+
+def time_steps(torch, run, steps, warmup):
+    torch.cuda.synchronize()
+    for _ in range(warmup):
+        run()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(steps):
+        run()
+    torch.cuda.synchronize()
+    return (time.perf_counter() - t0) / steps
+
+
+def stack_flops(stack):
+    B, D, Dm = stack.B, stack.D, stack.Dm
+    fl = {k: 0.0 for k in ("gemm_qkv", "gemm_proj", "gemm_fc1", "gemm_fc2", "attention")}
+    for (n_in, _) in stack.sched:
+        M = B * n_in
+        fl["gemm_qkv"] += 2.0 * M * D * 3 * D
+        fl["gemm_proj"] += 2.0 * M * D * D
+        fl["gemm_fc1"] += 2.0 * M * D * Dm
+        fl["gemm_fc2"] += 2.0 * M * Dm * D
+        fl["attention"] += 4.0 * B * n_in * n_in * D
+    return fl
 
 
 def main():
@@ -80,116 +120,56 @@ def main():
 
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     torch.cuda.set_device(0)
-    wl = dict(si.WORKLOADS[a.workload])
-    assert wl["dtype"] == "bf16"
-    B, N, D, H, Dm, L = wl["B"], wl["N"], wl["D"], wl["H"], wl["Dm"], wl["blocks"]
-    P = wl.get("n_prefix", 1)                        # protected prefix (class token), 0 for the video models
-    op = {"mlp": rs.RS_SHIFT_MLP, "attn": rs.RS_SHIFT_ATTN, "block": rs.RS_SHIFT_BLOCK}[wl.get("op", "mlp")]
-    prune = None if a.unpruned else wl["prune"]
-    sched = rs.keep_counts(N, P, L, prune)           # per block: (tokens in, non-prefix kept)
-    tdt = torch.bfloat16
-    dev = "cuda"
+    dev, tdt, e = "cuda", torch.bfloat16, 2
 
-    # ---- inputs and weights: seeded, rounded to bf16 on the host, resident in HBM ----
-    def up(arr):
-        return torch.from_numpy(si.round_to_bf16(arr)).to(dev, tdt)
-
-    x0 = up(si.tokens(0, B, N, D))
-    weights, keep_alive = [], []
-    for l in range(L):
-        w = {k: up(v) for k, v in si.block_weights(0, l, D, Dm).items()}
-        cfg0 = rs.make_cfg(B, N, D, H, Dm, P, N - P, tdt)
-        packed = torch.empty(rs.rs_packed_weights_size(cfg0), dtype=torch.uint8, device=dev)
-        rs.rs_pack_weights(cfg0, rs.make_weights(w), packed)      # one-off, untimed
-        keep_alive.append((w, packed))
-        weights.append(rs.make_weights(w, packed))
-    cfgs = [rs.make_cfg(B, n_in, D, H, Dm, P, n_keep, tdt, op=op) for n_in, n_keep in sched]
-    ws = torch.empty(max(rs.rs_block_workspace_size(c) for c in cfgs), dtype=torch.uint8, device=dev)
-    bufs = [torch.empty((B, N, D), device=dev, dtype=tdt) for _ in range(2)]
-    kept = torch.empty((B, N), device=dev, dtype=torch.int32)
-
-    def step():
-        stream = torch.cuda.current_stream()   # the capture stream while a graph is recorded
-        src = x0
-        for l in range(L):
-            dst = bufs[l & 1]
-            rs.rs_block_fwd(cfgs[l], weights[l], src, dst, kept, None, ws, stream)
-            src = dst
-        return src
-
-    # the timed configuration: S parts of the batch on S streams (same kernels, same results)
-    S = min(a.streams, B) if (a.streams > 1 and not a.graph) else 1
-    run = step
-    if S > 1:
-        parts, first = [], 0
-        for i in range(S):
-            Bp = B // S + (1 if i < B % S else 0)
-            cfgs_p = [rs.make_cfg(Bp, n_in, D, H, Dm, P, n_keep, tdt, op=op) for n_in, n_keep in sched]
-            parts.append(dict(x=x0[first:first + Bp], cfgs=cfgs_p,
-                              ws=torch.empty(max(rs.rs_block_workspace_size(c) for c in cfgs_p), dtype=torch.uint8, device=dev),
-                              bufs=[torch.empty((Bp, N, D), device=dev, dtype=tdt) for _ in range(2)],
-                              kept=torch.empty((Bp, N), device=dev, dtype=torch.int32), stream=torch.cuda.Stream()))
-            first += Bp
-
-        def step_parts():
-            src = [p["x"] for p in parts]
-            for l in range(L):
-                for i, p in enumerate(parts):
-                    dst = p["bufs"][l & 1]
-                    rs.rs_block_fwd(p["cfgs"][l], weights[l], src[i], dst, p["kept"], None, p["ws"], p["stream"])
-                    src[i] = dst
-        run = step_parts
+    # ---- the timed configuration: S parts of the batch on S streams (same kernels, same results) ----
+    S = a.streams if (a.streams > 1 and not a.graph) else 1
+    wl, stack = build_stack(rs, si, torch, a.workload, S, a.unpruned)
+    B, N, D, H, Dm, L, P = stack.B, stack.N, stack.D, stack.H, stack.Dm, stack.L, stack.P
+    sched = stack.sched
+    S = len(stack.parts)
+    run = stack.step
     if a.graph:
         # the library neither allocates nor synchronises, so a whole step records as is
         side = torch.cuda.Stream()
         side.wait_stream(torch.cuda.current_stream())
         with torch.cuda.stream(side):
-            step()
+            stack.step()
         torch.cuda.current_stream().wait_stream(side)
         torch.cuda.synchronize()
         graph = torch.cuda.CUDAGraph()
         with torch.cuda.graph(graph):
-            step()
+            stack.step()
         run = graph.replay
 
-    torch.cuda.synchronize()
-    for _ in range(a.warmup):
-        run()
-    torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    for _ in range(a.steps):
-        run()
-    torch.cuda.synchronize()
-    dt = time.perf_counter() - t0
-    ms_per_step = dt / a.steps * 1e3
-    images_s = B * a.steps / dt
+    sec = time_steps(torch, run, a.steps, a.warmup)
+    ms_per_step = sec * 1e3
+    images_s = B / sec
     tokens_s = images_s * N
 
-    # ---- per-kernel durations: replay the same steps with event timing on ----
+    # ---- per-kernel durations: the same steps, whole batch on one stream, event timing on ----
+    stack.set_streams(1)
+    stack.step()
+    torch.cuda.synchronize()
     rs.rs_profile_enable(True)
     t0 = time.perf_counter()
     for _ in range(a.steps):
-        step()
+        stack.step()
     prof = rs.rs_profile_read()
     instr_ms_per_step = (time.perf_counter() - t0) / a.steps * 1e3
     rs.rs_profile_enable(False)
 
     # algorithmic work per step, per kernel class
-    e = 2
-    fl = {k: 0.0 for k in ("gemm_qkv", "gemm_proj", "gemm_fc1", "gemm_fc2", "attention")}
+    fl = stack_flops(stack)
     by = {k: 0.0 for k in ("attention", "layernorm", "prune")}
+    slots = D // 64                                    # score partial sums per row left by the GEMM epilogue
     for (n_in, n_keep) in sched:
         M = B * n_in
-        fl["gemm_qkv"] += 2.0 * M * D * 3 * D
-        fl["gemm_proj"] += 2.0 * M * D * D
-        fl["gemm_fc1"] += 2.0 * M * D * Dm
-        fl["gemm_fc2"] += 2.0 * M * Dm * D
-        fl["attention"] += 4.0 * B * n_in * n_in * D
         by["attention"] += 4.0 * M * D * e            # read q, k, v once, write o
-        by["layernorm"] += 2 * 2.0 * M * D * e
-        if n_keep < n_in - P:                          # score finalise + select + gather of K rows
+        by["layernorm"] += 2 * (1.0 * M * D * e + 8.0 * M)   # two row-statistics passes: read the rows, write (mean, rstd)
+        if n_keep < n_in - P:                          # partial sums in, scores + kept_idx out, gather of K rows
             K = P + n_keep
-            by["prune"] += B * (8.0 * n_in + 4.0 * K + 2.0 * K * D * e)
+            by["prune"] += B * (12.0 * slots * n_in + 8.0 * n_in + 4.0 * K + 2.0 * K * D * e)
     total_flops = sum(fl.values())
 
     def kern(name):
@@ -206,26 +186,51 @@ def main():
     avg_s, per_step = kern("attention")
     if per_step:
         kernels["attention"]["GB/s"] = round(by["attention"] / per_step / avg_s / 1e9, 1)
+        kernels["attention"]["frac_hbm"] = round(by["attention"] / per_step / avg_s / 1e9 / PEAK_HBM_GBS, 4)
     avg_s, per_step = kern("layernorm")
     if per_step:
-        kernels["layernorm"] = {"avg_us": round(avg_s * 1e6, 2), "launches_per_step": per_step,
-                                "GB/s": round(by["layernorm"] / per_step / avg_s / 1e9, 1)}
+        kernels["row_statistics"] = {"avg_us": round(avg_s * 1e6, 2), "launches_per_step": per_step,
+                                     "GB/s": round(by["layernorm"] / per_step / avg_s / 1e9, 1),
+                                     "note": "the LayerNorms are folded into the GEMMs behind them; this pass reads "
+                                             "the rows once and writes (mean, rstd) per row"}
     prune_ms = sum(prof[k][0] for k in ("shift_score", "select", "gather")) / a.steps
     n_prune = sum(1 for (n_in, n_keep) in sched if n_keep < n_in - P)
     if n_prune:
         kernels["prune_pass"] = {"ms_per_step": round(prune_ms, 4), "passes_per_step": n_prune,
                                  "GB/s": round(by["prune"] / (prune_ms * 1e-3) / 1e9, 1),
-                                 "note": "score finalise + select + gather inside rs_block_fwd"}
+                                 "note": "scores from the epilogue's partial sums + select + gather inside rs_block_fwd "
+                                         "(tensors of 40-80 MB just written by the fc2 GEMM)"}
 
     # the dominant kernel by time
     dom = max(("gemm_qkv", "gemm_proj", "gemm_fc1", "gemm_fc2", "attention"), key=lambda k: prof[k][0])
     avg_s, per_step = kern(dom)
     achieved = fl[dom] / per_step / avg_s / 1e12
+    # algorithmic bytes of that kernel per launch (mean over the step's launches): operands read once,
+    # result written once, plus the residual read and the score partial sums where the epilogue has them
+    Ms = [B * n for n, _ in sched]
+    Mmean = sum(Ms) / len(Ms)
+    shapes = {"gemm_qkv": (D, 3 * D, 0, 0), "gemm_proj": (D, D, 1, 0), "gemm_fc1": (D, Dm, 0, 0),
+              "gemm_fc2": (Dm, D, 1, 1)}
+    alg_bytes = None
+    if dom in shapes:
+        Kd, Nd, res, part = shapes[dom]
+        alg_bytes = (Mmean * Kd + Nd * Kd + Mmean * Nd * (1 + res)) * e + part * Mmean * slots * 4.0 * n_prune / L
+    elif dom == "attention":
+        alg_bytes = by["attention"] / per_step
+    carried = MEASURED_HBM_BYTES_PER_LAUNCH.get((a.workload, a.unpruned, dom))
+    traffic = carried[0] if carried and carried[1] == rs.rs_build_info() else None
     roofline = {"kernel": dom, "bound": "mfma", "achieved": round(achieved, 2), "peak": PEAK_BF16_TFLOPS,
                 "unit": "TFLOP/s", "frac": round(achieved / PEAK_BF16_TFLOPS, 4),
-                "traffic": MEASURED_HBM_BYTES_PER_LAUNCH.get((a.workload, a.unpruned, dom)),
+                "traffic": traffic,
+                "algorithmic_bytes": None if alg_bytes is None else round(alg_bytes),
+                "traffic_ratio": None if (traffic is None or not alg_bytes) else round(traffic / alg_bytes, 3),
                 "avg_launch_us": round(avg_s * 1e6, 2), "launches_per_step": per_step,
-                "whole_step_frac_of_mfma_peak": round(total_flops / (ms_per_step * 1e-3) / 1e12 / PEAK_BF16_TFLOPS, 4)}
+                "whole_step_frac_of_mfma_peak": round(total_flops / (ms_per_step * 1e-3) / 1e12 / PEAK_BF16_TFLOPS, 4),
+                "build": rs.rs_build_info()}
+    if traffic is None:
+        roofline["traffic_note"] = ("no rocprofv3 FETCH_SIZE / WRITE_SIZE run is on record for this kernel under this "
+                                    "build string" if not carried else
+                                    "the figure on record was measured under another build string: " + carried[1])
 
     out = {
         "metric": "images/s ViT-B fwd w/ rep-shift pruning" if a.workload == "vit_b16" else
@@ -248,43 +253,70 @@ def main():
     if S > 1:
         out["roofline"]["measured_on"] = ("instrumented replay of the whole batch on one stream (a launch has the "
                                           "chip to itself); the timed steps run %d parts of the batch on %d streams" % (S, S))
+    del stack
+    torch.cuda.empty_cache()
 
-    # ---- optional: the prune pass alone on an HBM-resident shape ----
     if not a.no_extras:
+        # ---- the same stack without pruning, and the other BASELINE workloads (a few steps each) ----
+        def side_run(name, unpruned, steps=5, warmup=2):
+            _, st = build_stack(rs, si, torch, name, a.streams if a.streams > 1 else 1, unpruned)
+            s_ = time_steps(torch, st.step, steps, warmup)
+            f_ = sum(stack_flops(st).values())
+            r_ = {"images_per_s": round(st.B / s_, 1), "ms_per_step": round(s_ * 1e3, 4), "steps": steps,
+                  "batch": st.B, "tokens_per_block": sorted(set(n for n, _ in st.sched), reverse=True),
+                  "gflop_per_image": round(f_ / st.B / 1e9, 2),
+                  "frac_of_mfma_peak": round(f_ / s_ / 1e12 / PEAK_BF16_TFLOPS, 4)}
+            del st
+            torch.cuda.empty_cache()
+            return r_
+
+        if not a.unpruned:
+            u = side_run(a.workload, True)
+            out["unpruned"] = dict(u, speedup_from_pruning=round(images_s / u["images_per_s"], 3))
+        out["workloads"] = {n: side_run(n, False) for n in ("vit_s16", "video_vit_b16", "video_vit_l14")
+                            if n != a.workload}
+
+        # ---- the prune pass alone on an HBM-resident shape ----
         Bs, Ns, Ds, Ks = 4096, 197, 768, 177
         f_in = torch.randn((Bs, Ns, Ds), device=dev, dtype=tdt)
         f_out = f_in + 0.1 * torch.randn((Bs, Ns, Ds), device=dev, dtype=tdt)
         sc = torch.empty((Bs, Ns), device=dev, dtype=torch.float32)
         kp = torch.empty((Bs, 1 + Ks), device=dev, dtype=torch.int32)
         g = torch.empty((Bs, 1 + Ks, Ds), device=dev, dtype=tdt)
-        for _ in range(3):
-            rs.rs_shift_topk(f_out, f_in, None, 1, Ks, sc, kp, g)
-        torch.cuda.synchronize()
-        t0 = time.perf_counter()
-        reps = 10
-        for _ in range(reps):
-            rs.rs_shift_topk(f_out, f_in, None, 1, Ks, sc, kp, g)
-        torch.cuda.synchronize()
-        ts = (time.perf_counter() - t0) / reps
+        ts = time_steps(torch, lambda: rs.rs_shift_topk(f_out, f_in, None, 1, Ks, sc, kp, g), 10, 3)
         alg = Bs * (2.0 * Ns * Ds * e + 8.0 * Ns + 4.0 * (1 + Ks) + (1 + Ks) * Ds * e)
+        alg_reread = alg + Bs * (1.0 + Ks) * Ds * e
         out["prune_stress"] = {"shape": [Bs, Ns, Ds, Ks], "ms": round(ts * 1e3, 4),
-                               "GB/s": round(alg / ts / 1e9, 1), "frac_hbm": round(alg / ts / 1e9 / PEAK_HBM_GBS, 4)}
-        del f_in, f_out, g
-        # fused attention alone at the long-sequence video shape (matrix-core utilisation of the core step)
+                               "GB/s": round(alg / ts / 1e9, 1), "frac_hbm": round(alg / ts / 1e9 / PEAK_HBM_GBS, 4),
+                               "GB/s_incl_gather_read": round(alg_reread / ts / 1e9, 1),
+                               "note": "GB/s counts every tensor once (read f_out, f_in; write scores, kept_idx, gathered "
+                                       "rows); _incl_gather_read adds a second read of the kept rows, which the one-pass "
+                                       "kernel used for this shape does not perform (they stay in registers)"}
+        # the same pass when the rows to gather come from a third tensor (three launches: score, select, gather)
+        src3 = torch.randn((Bs, Ns, Ds), device=dev, dtype=tdt)
+        t3 = time_steps(torch, lambda: rs.rs_shift_topk(f_out, f_in, src3, 1, Ks, sc, kp, g), 10, 3)
+        out["prune_stress_three_launch"] = {"ms": round(t3 * 1e3, 4), "GB/s": round(alg_reread / t3 / 1e9, 1),
+                                            "frac_hbm": round(alg_reread / t3 / 1e9 / PEAK_HBM_GBS, 4),
+                                            "note": "rows gathered from a separate tensor: its read is algorithmic here"}
+        del f_in, f_out, g, src3
+        # ---- fused attention alone at the long-sequence video shape ----
         Ba, Na, Ha = 4, 4097, 16
         qkv = torch.randn((Ba, Na, 3, Ha, 64), device=dev, dtype=tdt)
         oa = torch.empty((Ba, Na, Ha, 64), device=dev, dtype=tdt)
-        for _ in range(3):
-            rs.rs_attention_fwd(qkv[:, :, 0], qkv[:, :, 1], qkv[:, :, 2], oa, 0.125)
-        torch.cuda.synchronize()
-        t0 = time.perf_counter()
-        for _ in range(20):
-            rs.rs_attention_fwd(qkv[:, :, 0], qkv[:, :, 1], qkv[:, :, 2], oa, 0.125)
-        torch.cuda.synchronize()
-        ta = (time.perf_counter() - t0) / 20
+        ta = time_steps(torch, lambda: rs.rs_attention_fwd(qkv[:, :, 0], qkv[:, :, 1], qkv[:, :, 2], oa, 0.125), 20, 3)
         fa = 4.0 * Ba * Ha * Na * Na * 64
         out["attention_long"] = {"shape": [Ba, Na, Ha, 64], "us": round(ta * 1e6, 1),
                                  "TFLOP/s": round(fa / ta / 1e12, 1), "frac_mfma": round(fa / ta / 1e12 / PEAK_BF16_TFLOPS, 4)}
+        del qkv, oa
+        # ---- and at the image shape (batch 256 x 197 tokens x 12 heads: HBM-bound) ----
+        Bi, Ni, Hi = 256, 197, 12
+        qkv = torch.randn((Bi, Ni, 3, Hi, 64), device=dev, dtype=tdt)
+        oa = torch.empty((Bi, Ni, Hi, 64), device=dev, dtype=tdt)
+        ti = time_steps(torch, lambda: rs.rs_attention_fwd(qkv[:, :, 0], qkv[:, :, 1], qkv[:, :, 2], oa, 0.125), 20, 3)
+        bi = 4.0 * Bi * Ni * Hi * 64 * e
+        out["attention_short"] = {"shape": [Bi, Ni, Hi, 64], "us": round(ti * 1e6, 1), "GB/s": round(bi / ti / 1e9, 1),
+                                  "frac_hbm": round(bi / ti / 1e9 / PEAK_HBM_GBS, 4),
+                                  "frac_mfma": round(4.0 * Bi * Hi * Ni * Ni * 64 / ti / 1e12 / PEAK_BF16_TFLOPS, 4)}
         del qkv, oa
 
     if a.calib_copy_mb:
@@ -303,9 +335,10 @@ def main():
         ns = a.cpu_sample or max(1, min(B, int(round(64 * 26.6 / per_img_gflop)) or 1))
         xs = si.round_to_bf16(si.tokens(0, B, N, D)[:ns]).astype(np.float64)
         wts = [{k: si.round_to_bf16(v) for k, v in si.block_weights(0, l, D, Dm).items()} for l in range(L)]
+        op = {"mlp": 0, "attn": 1, "block": 2}[wl.get("op", "mlp")]   # the op codes are the same on both sides
         t0 = time.perf_counter()
         for l, (n_in, n_keep) in enumerate(sched):
-            r = oracle.block_pruned(xs, wts[l], H, P, n_keep, op=op)   # the op codes are the same on both sides
+            r = oracle.block_pruned(xs, wts[l], H, P, n_keep, op=op)
             xs = r["y"]
         tc = time.perf_counter() - t0
         out["cpu_baseline"] = {"value": round(ns / tc, 3), "unit": "images/s", "cores": oracle.num_threads(),
