@@ -237,6 +237,27 @@ RS_API rs_status rs_block_fwd(const rs_block_cfg *cfg, const rs_block_weights *w
                        const void *x, void *y, int32_t *kept_idx, float *scores,
                        void *workspace, size_t workspace_bytes, void *hip_stream);
 
+/*
+ * rs_block_fwd for callers that cannot allocate device memory or hand over a workspace: code
+ * under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same
+ * computation, same kernels and bit-identical outputs as rs_block_fwd; the scratch tensors live
+ * in a buffer of rs_block_static_scratch_size() bytes (64 MiB) that is part of the library's
+ * device code: every GPU the library runs on holds its own copy from the first use until the
+ * process ends.  The call allocates nothing and frees nothing.
+ *   - cfg must satisfy rs_block_workspace_size(cfg) <= rs_block_static_scratch_size(), else
+ *     RS_ERR_UNSUPPORTED (a ViT-B/16 block in bf16 fits up to 16 images of 197 tokens; larger
+ *     batches go through rs_block_fwd).
+ *   - x, y, kept_idx, scores: as in rs_block_fwd, caller-owned.
+ *   - All calls on one GPU share that GPU's buffer: calls that overlap in time on one GPU (two
+ *     streams, two host threads) race on it and give undefined results; calls on one stream are
+ *     ordered and safe.  Nothing in the buffer has to start at zero, so a call leaves nothing
+ *     behind that the next one depends on.
+ */
+RS_API size_t rs_block_static_scratch_size(void);
+RS_API rs_status rs_block_fwd_static(const rs_block_cfg *cfg, const rs_block_weights *w,
+                                     const void *x, void *y, int32_t *kept_idx, float *scores,
+                                     void *hip_stream);
+
 #ifdef __cplusplus
 }
 #endif

@@ -25,7 +25,7 @@ RS_EPI_BIAS, RS_EPI_BIAS_GELU, RS_EPI_BIAS_RES = 0, 1, 2
 EXPORTS = ("rs_last_error", "rs_version", "rs_build_info", "rs_profile_enable", "rs_profile_read",
            "rs_profile_class_name", "rs_attention_fwd", "rs_shift_topk_workspace_size",
            "rs_shift_topk", "rs_grid_line_prune", "rs_pack_linear", "rs_linear_fwd", "rs_packed_weights_size", "rs_pack_weights", "rs_block_workspace_size",
-           "rs_block_fwd")
+           "rs_block_fwd", "rs_block_static_scratch_size", "rs_block_fwd_static")
 
 _vp = ctypes.c_void_p
 _i32 = ctypes.c_int32
@@ -94,6 +94,11 @@ def lib():
         L.rs_block_fwd.argtypes = [ctypes.POINTER(RsBlockCfg), ctypes.POINTER(RsBlockWeights),
                                    _vp, _vp, _vp, _vp, _vp, ctypes.c_size_t, _vp]
         L.rs_block_fwd.restype = ctypes.c_int
+        L.rs_block_static_scratch_size.argtypes = []
+        L.rs_block_static_scratch_size.restype = ctypes.c_size_t
+        L.rs_block_fwd_static.argtypes = [ctypes.POINTER(RsBlockCfg), ctypes.POINTER(RsBlockWeights),
+                                          _vp, _vp, _vp, _vp, _vp]
+        L.rs_block_fwd_static.restype = ctypes.c_int
         _lib = L
     return _lib
 
@@ -228,3 +233,13 @@ def rs_block_fwd(cfg: RsBlockCfg, weights: RsBlockWeights, x, y, kept_idx, score
     ws_bytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
     _check(lib().rs_block_fwd(ctypes.byref(cfg), ctypes.byref(weights), _ptr(x), _ptr(y), _ptr(kept_idx),
                               _ptr(scores), _ptr(workspace), ws_bytes, _stream(stream)))
+
+
+def rs_block_static_scratch_size() -> int:
+    return int(lib().rs_block_static_scratch_size())
+
+
+def rs_block_fwd_static(cfg: RsBlockCfg, weights: RsBlockWeights, x, y, kept_idx, scores, stream=None) -> None:
+    """rs_block_fwd on the library's own static scratch buffer (no workspace, no allocation)."""
+    _check(lib().rs_block_fwd_static(ctypes.byref(cfg), ctypes.byref(weights), _ptr(x), _ptr(y), _ptr(kept_idx),
+                                     _ptr(scores), _stream(stream)))

@@ -188,6 +188,35 @@ static rs_status block_fwd(const rs_block_cfg* cfg, const rs_block_weights* w, c
                            int32_t* kept_idx, float* scores, void* workspace, size_t workspace_bytes,
                            void* hip_stream);
 
+// ---- scratch of rs_block_fwd_static ------------------------------------------------------
+// One buffer per GPU, part of the loaded code object: it exists from the moment the library's
+// device code is loaded on a GPU until the process ends, and no call ever allocates it.  The
+// name below is a host-side handle, not a device address; the address on the current device comes
+// from hipGetSymbolAddress, once per device, and only that pointer is handed to kernels.
+constexpr size_t kStaticScratchBytes = (size_t)64 << 20;
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
+
+static rs_status static_scratch(void** out) {
+    constexpr int kMaxDevices = 64;
+    static std::mutex mu;
+    static void* ptrs[kMaxDevices] = {};
+    int dev = -1;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return device_error("hipGetDevice", e);
+    RS_REQUIRE(dev >= 0 && dev < kMaxDevices, RS_ERR_UNSUPPORTED, "device index %d beyond %d", dev, kMaxDevices - 1);
+    std::lock_guard<std::mutex> lk(mu);
+    if (!ptrs[dev]) {
+        void* p = nullptr;
+        e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+        if (e != hipSuccess) return device_error("hipGetSymbolAddress(scratch)", e);
+        RS_REQUIRE(p != nullptr && (reinterpret_cast<uintptr_t>(p) & 255u) == 0, RS_ERR_DEVICE,
+                   "static scratch buffer has no usable device address");
+        ptrs[dev] = p;
+    }
+    *out = ptrs[dev];
+    return RS_OK;
+}
+
 extern "C" {
 
 const char* rs_last_error(void) { return g_err; }
@@ -413,6 +442,23 @@ rs_status rs_block_fwd(const rs_block_cfg* cfg, const rs_block_weights* w, const
                        void* hip_stream) {
     return block_fwd(cfg, w, x, y, kept_idx, scores, workspace, workspace_bytes, hip_stream);
 }
+
+rs_status rs_block_fwd_static(const rs_block_cfg* cfg, const rs_block_weights* w, const void* x, void* y,
+                              int32_t* kept_idx, float* scores, void* hip_stream) {
+    rs_status st = check_cfg(cfg);
+    if (st != RS_OK) return st;
+    const size_t need = block_layout(cfg).total;
+    RS_REQUIRE(need <= kStaticScratchBytes, RS_ERR_UNSUPPORTED,
+               "this block needs %zu bytes of scratch, the static buffer holds %zu: use rs_block_fwd with a workspace",
+               need, kStaticScratchBytes);
+    if (cfg->B == 0 || cfg->N == 0) return RS_OK;
+    void* scratch_ptr = nullptr;
+    st = static_scratch(&scratch_ptr);
+    if (st != RS_OK) return st;
+    return block_fwd(cfg, w, x, y, kept_idx, scores, scratch_ptr, kStaticScratchBytes, hip_stream);
+}
+
+size_t rs_block_static_scratch_size(void) { return kStaticScratchBytes; }
 
 }  // extern "C"
 

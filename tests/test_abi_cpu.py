@@ -186,6 +186,24 @@ def test_linear_rejects_bad_arguments():
     assert call(M=0, a=None) == rs.RS_OK
 
 
+def test_static_scratch_entry_validates_before_any_device_call():
+    """rs_block_fwd_static: the size check and the configuration checks come before the first HIP call."""
+    L = rs.lib()
+    w = _weights()
+    assert rs.rs_block_static_scratch_size() == 64 << 20
+    big = _cfg(B=64, N=197, D=768, H=12, Dm=3072, n_keep=100)
+    assert rs.rs_block_workspace_size(big) > rs.rs_block_static_scratch_size()
+    assert L.rs_block_fwd_static(ctypes.byref(big), ctypes.byref(w), FAKE, 2 * FAKE, 3 * FAKE, None, None) == \
+        rs.RS_ERR_UNSUPPORTED
+    assert "static buffer" in rs.rs_last_error()
+    bad = _cfg(H=3)
+    assert L.rs_block_fwd_static(ctypes.byref(bad), ctypes.byref(w), FAKE, 2 * FAKE, 3 * FAKE, None, None) == \
+        rs.RS_ERR_INVALID_ARG
+    assert L.rs_block_fwd_static(None, ctypes.byref(w), FAKE, 2 * FAKE, 3 * FAKE, None, None) == rs.RS_ERR_INVALID_ARG
+    empty = _cfg(B=0)
+    assert L.rs_block_fwd_static(ctypes.byref(empty), ctypes.byref(w), None, None, None, None, None) == rs.RS_OK
+
+
 def test_pack_weights_validation():
     cfg = _cfg()
     # four bf16 matrices plus, for the two LayerNorms folded into W_qkv and W_fc1, an fp32 column-sum
