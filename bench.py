@@ -44,10 +44,14 @@ def parse():
                     help="skip the side measurements: the unpruned stack, the other BASELINE workloads, "
                          "rs_shift_topk alone on an HBM-resident shape (B=4096, N=197, D=768) and "
                          "rs_attention_fwd alone at the long video shape (4 x 4097 tokens x 16 heads)")
-    ap.add_argument("--streams", type=int, default=2,
+    ap.add_argument("--streams", type=int, default=0,
                     help="the batch is cut into this many equal parts, each run block by block on a HIP stream of "
                          "its own: images are independent, and the parts' kernels fill each other's idle CUs "
-                         "(last rounds of the GEMMs, small kernels).  1 = the whole batch on one stream")
+                         "(last rounds of the GEMMs, small kernels).  1 = the whole batch on one stream; 0 (default) = "
+                         "a short timing of (1 stream, GEMM tiles by shape), (2 streams, by shape) and (2 streams, "
+                         "persistent GEMM only) before the timed region picks the fastest (same results in all)")
+    ap.add_argument("--gemm-variant", type=int, default=0,
+                    help="with --streams N > 0: tile variant of the bf16 GEMMs (0 = by shape, 1..4 = one kernel only)")
     ap.add_argument("--graph", action="store_true",
                     help="capture one step into a HIP graph and time its replays (for the small, launch-bound "
                          "workloads; the per-kernel replay stays eager)")
@@ -123,8 +127,13 @@ def main():
     dev, tdt, e = "cuda", torch.bfloat16, 2
 
     # ---- the timed configuration: S parts of the batch on S streams (same kernels, same results) ----
-    S = a.streams if (a.streams > 1 and not a.graph) else 1
+    S = 1 if a.graph else max(a.streams, 1)
     wl, stack = build_stack(rs, si, torch, a.workload, S, a.unpruned)
+    tuned = None
+    if a.streams == 0 and not a.graph:
+        tuned = stack.tune()
+    else:
+        stack.gemm_variant = a.gemm_variant
     B, N, D, H, Dm, L, P = stack.B, stack.N, stack.D, stack.H, stack.Dm, stack.L, stack.P
     sched = stack.sched
     S = len(stack.parts)
@@ -148,6 +157,7 @@ def main():
     tokens_s = images_s * N
 
     # ---- per-kernel durations: the same steps, whole batch on one stream, event timing on ----
+    timed_variant = stack.gemm_variant
     stack.set_streams(1)
     stack.step()
     torch.cuda.synchronize()
@@ -197,6 +207,8 @@ def main():
     n_prune = sum(1 for (n_in, n_keep) in sched if n_keep < n_in - P)
     if n_prune:
         kernels["prune_pass"] = {"ms_per_step": round(prune_ms, 4), "passes_per_step": n_prune,
+                                 "select_ms_per_step": round(prof["select"][0] / a.steps, 4),
+                                 "gather_ms_per_step": round(prof["gather"][0] / a.steps, 4),
                                  "GB/s": round(by["prune"] / (prune_ms * 1e-3) / 1e9, 1),
                                  "note": "scores from the epilogue's partial sums + select + gather inside rs_block_fwd "
                                          "(tensors of 40-80 MB just written by the fc2 GEMM)"}
@@ -248,8 +260,12 @@ def main():
         "kernels": kernels,
         "instrumented_ms_per_step": round(instr_ms_per_step, 4),
         "launch": "hip graph replay" if a.graph else "eager",
-        "streams": S,
+        "streams": S, "gemm_variant": timed_variant,
     }
+    if tuned is not None:
+        out["launch_tuning"] = {"ms_per_step by (streams, gemm variant)": {"%d,%d" % k: round(v * 1e3, 4) for k, v in tuned.items()},
+                                "note": "timed once before the timed region; the fastest configuration is the one timed; "
+                                        "all configurations give bit-identical outputs"}
     if S > 1:
         out["roofline"]["measured_on"] = ("instrumented replay of the whole batch on one stream (a launch has the "
                                           "chip to itself); the timed steps run %d parts of the batch on %d streams" % (S, S))
@@ -259,10 +275,15 @@ def main():
     if not a.no_extras:
         # ---- the same stack without pruning, and the other BASELINE workloads (a few steps each) ----
         def side_run(name, unpruned, steps=5, warmup=2):
-            _, st = build_stack(rs, si, torch, name, a.streams if a.streams > 1 else 1, unpruned)
+            _, st = build_stack(rs, si, torch, name, max(a.streams, 1), unpruned)
+            if a.streams == 0:
+                st.tune()
+            else:
+                st.gemm_variant = a.gemm_variant
             s_ = time_steps(torch, st.step, steps, warmup)
             f_ = sum(stack_flops(st).values())
             r_ = {"images_per_s": round(st.B / s_, 1), "ms_per_step": round(s_ * 1e3, 4), "steps": steps,
+                  "streams": len(st.parts), "gemm_variant": st.gemm_variant,
                   "batch": st.B, "tokens_per_block": sorted(set(n for n, _ in st.sched), reverse=True),
                   "gflop_per_image": round(f_ / st.B / 1e9, 2),
                   "frac_of_mfma_peak": round(f_ / s_ / 1e12 / PEAK_BF16_TFLOPS, 4)}

@@ -112,6 +112,12 @@ RS_API int32_t rs_version(void);
  * Counter readings carried from one profiling run to another are valid only for the same string. */
 RS_API const char *rs_build_info(void);
 
+/* Tuning aid (process-wide, not part of the method): which tile variant the bf16 matrix kernels
+ * use.  0 = chosen by shape (the default), 1 = 256 x 256 persistent workgroups, 2 = 256 x 128 and
+ * 3 = 128 x 128 tiles with two workgroups per compute unit.  Every variant gives the same bits;
+ * only the speed differs.  The environment variable RS_GEMM_FORCE sets the initial value. */
+RS_API rs_status rs_tune_gemm_variant(int32_t variant);
+
 /*
  * Measurement aid (not part of the method): while enabled, every kernel the library
  * launches is bracketed by two HIP events on the caller's stream.  rs_profile_read waits

@@ -22,7 +22,7 @@ RS_SHIFT_MLP, RS_SHIFT_ATTN, RS_SHIFT_BLOCK, RS_SHIFT_MLP_STREAM, RS_SHIFT_MLP_N
 RS_PROFILE_CLASSES = 11
 RS_EPI_BIAS, RS_EPI_BIAS_GELU, RS_EPI_BIAS_RES = 0, 1, 2
 
-EXPORTS = ("rs_last_error", "rs_version", "rs_build_info", "rs_profile_enable", "rs_profile_read",
+EXPORTS = ("rs_last_error", "rs_version", "rs_build_info", "rs_tune_gemm_variant", "rs_profile_enable", "rs_profile_read",
            "rs_profile_class_name", "rs_attention_fwd", "rs_shift_topk_workspace_size",
            "rs_shift_topk", "rs_grid_line_prune", "rs_pack_linear", "rs_linear_fwd", "rs_packed_weights_size", "rs_pack_weights", "rs_block_workspace_size",
            "rs_block_fwd", "rs_block_static_scratch_size", "rs_block_fwd_static")
@@ -64,6 +64,8 @@ def lib():
         L.rs_last_error.restype = ctypes.c_char_p
         L.rs_version.restype = _i32
         L.rs_build_info.restype = ctypes.c_char_p
+        L.rs_tune_gemm_variant.argtypes = [_i32]
+        L.rs_tune_gemm_variant.restype = ctypes.c_int
         L.rs_profile_enable.argtypes = [_i32]
         L.rs_profile_enable.restype = ctypes.c_int
         L.rs_profile_read.argtypes = [ctypes.POINTER(ctypes.c_double), ctypes.POINTER(_i64)]
@@ -155,6 +157,10 @@ def rs_version() -> int:
 
 def rs_build_info() -> str:
     return lib().rs_build_info().decode()
+
+
+def rs_tune_gemm_variant(variant: int) -> None:
+    _check(lib().rs_tune_gemm_variant(int(variant)))
 
 
 def rs_profile_enable(enable: bool) -> None:

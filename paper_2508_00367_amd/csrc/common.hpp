@@ -119,11 +119,14 @@ struct GemmLnFold {
 // byte offsets from the tile's first row, 256 * K * 2 bytes, and the copies of a K slice that does
 // not exist are aimed at byte 0x7ff00000 of a resource that ends with the tile's last row.
 constexpr int kGemmMaxK = 1 << 20;
-constexpr int kGemmMaxN = 1 << 24;
+constexpr int kGemmMaxN = 1 << 20;
 
 // Tile configurations the bf16 GEMM was built with (measurements carried from one run to another
 // are only valid for the same string).
 const char* gemm_build_info();
+// bf16 tile variant switch (0 = by shape, 1 = 256 x 256 persistent, 2 = 256 x 128 ring, 3 = 128 x 128 ring)
+int gemm_variant();
+void set_gemm_variant(int v);
 
 // Number of per-row partial slots the SHIFT epilogue writes for an output width N.
 int gemm_shift_slots(rs_dtype dt, int N);

@@ -10,6 +10,10 @@
 // (residual, shift partial sums) stays inside a lane, and stores are 8-byte vectors.
 //
 // fp32 path: plain FMA tiles (parity configuration, true fp32 products).
+#include <stdlib.h>
+
+#include <atomic>
+
 #include "common.hpp"
 
 namespace rs {
@@ -40,6 +44,16 @@ __device__ __forceinline__ float gelu_sp(float x) {
     p = fmaf(p, x2, -2.3011212f);
     const float e = __builtin_amdgcn_exp2f(p * xc);  // exp(-x (a + b x^2 + c x^4))
     return x * __builtin_amdgcn_rcpf(1.0f + e);
+}
+
+// One element's contribution to the per-row sums of the shift: the same operations, in the same
+// order per 8-feature chunk and over the chunks of a 64-feature slot, in every GEMM variant, so that
+// the scores do not depend on which tile shape ran.
+template <int DIST>
+__device__ __forceinline__ void shift_term(float fo, float fi, float& p0, float& p1, float& p2) {
+    if (DIST == RS_DIST_L2) { const float d = fo - fi; p0 = fmaf(d, d, p0); }
+    else if (DIST == RS_DIST_L1) { p0 += fabsf(fo - fi); }
+    else { p0 = fmaf(fo, fi, p0); p1 = fmaf(fo, fo, p1); p2 = fmaf(fi, fi, p2); }
 }
 
 template <int TN, int TM>
@@ -410,9 +424,7 @@ __global__ __launch_bounds__(WGM* WGN * 64, WGM* WGN / 4) void gemm_bf16_kernel(
 #pragma unroll
                         for (int e = 0; e < 8; ++e) {
                             const float fo = post ? v[e] + rr[e] : v[e];
-                            if (DIST == RS_DIST_L2) { float d = fo - fi[e]; p0 += d * d; }
-                            else if (DIST == RS_DIST_L1) { p0 += fabsf(fo - fi[e]); }
-                            else { p0 += fo * fi[e]; p1 += fo * fo; p2 += fi[e] * fi[e]; }
+                            shift_term<DIST>(fo, fi[e], p0, p1, p2);
                         }
                     }
 #pragma unroll
@@ -426,8 +438,8 @@ __global__ __launch_bounds__(WGM* WGN * 64, WGM* WGN / 4) void gemm_bf16_kernel(
                         p0 += __shfl_xor(p0, off, 64);
                         if (DIST == RS_DIST_COS) { p1 += __shfl_xor(p1, off, 64); p2 += __shfl_xor(p2, off, 64); }
                     }
-                    if ((lane % LPR) == 0 && m < M) {
-                        const int slot = (n0_cur + wn * WN) / WN;
+                    const int slot = (n0_cur + wn * WN) / WN;
+                    if ((lane % LPR) == 0 && m < M && slot < slots) {
                         float* dst = partials + ((int64_t)m * slots + slot) * kShiftLanes;
                         dst[0] = p0;
                         if (DIST == RS_DIST_COS) { dst[1] = p1; dst[2] = p2; }
@@ -446,7 +458,345 @@ __global__ __launch_bounds__(WGM* WGN * 64, WGM* WGN / 4) void gemm_bf16_kernel(
 #undef RS_GEMM_SLICE
 }
 
+// ---------------------------------------------------------------------------
+// Epilogue in the accumulator layout (ring kernels below).
+//
+// A wave owns WM = 32 TM token rows x 64 features; lane (l32, g) holds, for row 32 j + l32 of
+// every 32-row group j, features 32 i + 8 q + 4 g + e in register 4 q + e of acc[i][j].  All the
+// arithmetic of the epilogue -- LayerNorm fold, bias, GELU, residual add, the per-row partial sums
+// of the shift -- runs on that layout: per-row quantities (mean, rstd, the shift sums) are lane
+// private, per-column vectors are the same for the 32 lanes of a half-wave.  Only the traffic with
+// global memory goes through LDS, in bf16, one 4 KB region (32 rows x 128 bytes) per 32-row group:
+// the residual rows arrive there by direct copies (8 lanes per 128-byte row segment), a lane picks
+// up its 4 features at a time (8 bytes), puts the result back IN PLACE, and the group then leaves
+// as 16 bytes per lane, 8 lanes per row segment.  An element is rounded to bf16 once, after all
+// arithmetic in fp32, whatever the epilogue.
+// All residual copies of the tile are requested before anything else and awaited once: vector
+// memory loads and stores complete out of order with respect to each other, so "all but the
+// newest n operations have completed" says nothing about a copy once output stores are in flight.
+// 16-byte chunk c of row r sits in slot c ^ ((r ^ (r >> 3)) & 7).
+// ---------------------------------------------------------------------------
+__device__ __forceinline__ int epi_swz(int r) { return (r ^ (r >> 3)) & 7; }
+
+template <int TM>
+struct EpiRegions {
+    unsigned char* r[TM];  // one 4 KB LDS region per 32-row group of this wave
+};
+
+template <int TM, int EPI, int DIST>
+__device__ __forceinline__ void gemm_epilogue_acc_layout(
+    f32x16 (&acc)[2][TM], const EpiRegions<TM>& reg,
+    const bf16raw* __restrict__ bias, const bf16raw* __restrict__ res, bf16raw* __restrict__ out,
+    float* __restrict__ partials, const bf16raw* __restrict__ ref, int post, const GemmLnFold& ln,
+    int M, int N, int slots, int m_base /* first row of the wave tile */, int n_base /* first feature */,
+    int lane) {
+    constexpr bool LN = EPI == EPI_LN_BIAS || EPI == EPI_LN_BIAS_GELU;
+    constexpr bool GELU = EPI == EPI_BIAS_GELU || EPI == EPI_LN_BIAS_GELU;
+    constexpr bool RES = EPI == EPI_BIAS_RES || EPI == EPI_BIAS_RES_SHIFT;
+    constexpr bool SHIFT = EPI == EPI_BIAS_RES_SHIFT;
+    if (n_base >= N) return;  // a wave's 64 features are all inside N or all outside (N % 64 == 0)
+    const int l32 = lane & 31, g = lane >> 5;
+    const int rows_valid = min(max(M - m_base, 0), 32 * TM);
+    if (rows_valid == 0) return;
+
+    // residual rows: per group 4 copies of 8 rows x 128 bytes (lane l: row l / 8, slot l % 8 holds
+    // chunk (l % 8) ^ swz(row)); rows past M read as zeros through the resource
+    if (RES) {
+        const __amdgpu_buffer_rsrc_t rs_res =
+            make_rsrc(res + (int64_t)m_base * N + n_base, ((int64_t)(rows_valid - 1) * N + 64) * 2);
+#pragma unroll
+        for (int p = 0; p < 4; ++p) {
+            const int r = p * 8 + (lane >> 3);
+            const int voff = (r * N + (((lane & 7) ^ epi_swz(r)) << 3)) * 2;
+#pragma unroll
+            for (int j = 0; j < TM; ++j) dma16(rs_res, reg.r[j] + p * 1024, voff, j * 32 * N * 2);
+        }
+    }
+
+    // per-column vectors of this lane's 32 features
+    float bv[2][4][4], cs[LN ? 2 : 1][4][4];
+#pragma unroll
+    for (int i = 0; i < 2; ++i)
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+            const int n = n_base + i * 32 + q * 8 + g * 4;
+            if (LN) {
+                const f32x4 b4 = *reinterpret_cast<const f32x4*>(ln.bias + n);
+                const f32x4 c4 = *reinterpret_cast<const f32x4*>(ln.colsum + n);
+#pragma unroll
+                for (int e = 0; e < 4; ++e) { bv[i][q][e] = b4[e]; cs[LN ? i : 0][q][e] = c4[e]; }
+            } else if (bias) {
+                const uint2 b2 = *reinterpret_cast<const uint2*>(bias + n);
+                bv[i][q][0] = __uint_as_float(b2.x << 16); bv[i][q][1] = __uint_as_float(b2.x & 0xffff0000u);
+                bv[i][q][2] = __uint_as_float(b2.y << 16); bv[i][q][3] = __uint_as_float(b2.y & 0xffff0000u);
+            } else {
+#pragma unroll
+                for (int e = 0; e < 4; ++e) bv[i][q][e] = 0.f;
+            }
+        }
+    // per-row LayerNorm statistics of this lane's TM rows
+    float2 stats[LN ? TM : 1];
+    if (LN) {
+#pragma unroll
+        for (int j = 0; j < TM; ++j) {
+            const int m = m_base + j * 32 + l32;
+            stats[LN ? j : 0] = m < M ? reinterpret_cast<const float2*>(ln.stats)[m] : make_float2(0.f, 0.f);
+        }
+    }
+    if (RES) __builtin_amdgcn_s_waitcnt(vmcnt_imm(0));  // every residual row of the tile has landed
+
+    const int sw = epi_swz(l32);
+#pragma unroll
+    for (int j = 0; j < TM; ++j) {
+        const int m = m_base + j * 32 + l32;
+        const bool m_ok = m < M;
+        const float2 st = stats[LN ? j : 0];
+        unsigned char* buf = reg.r[j];
+        // Shift sums of the row's 64 features: per chunk of 8 features a running sum in feature order
+        // (half-wave g = 0 holds the first four terms and hands its sum to g = 1, which goes on with
+        // the other four), then the 8 chunk sums pairwise (c, c ^ 4), (.., c ^ 2), (.., c ^ 1).
+        float pc0[8], pc1[DIST == RS_DIST_COS ? 8 : 1], pc2[DIST == RS_DIST_COS ? 8 : 1];
+#pragma unroll
+        for (int i = 0; i < 2; ++i)
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                unsigned char* at = buf + l32 * 128 + (((i * 4 + q) ^ sw) << 4) + g * 8;
+                float v[4];
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    const float a_ = acc[i][j][4 * q + e];
+                    v[e] = LN ? fmaf(st.y, fmaf(-st.x, cs[LN ? i : 0][q][e], a_), bv[i][q][e]) : a_ + bv[i][q][e];
+                    if (GELU) v[e] = gelu_sp(v[e]);
+                }
+                if (RES) {
+                    const uint2 r2 = *reinterpret_cast<const uint2*>(at);
+                    float rr[4] = {__uint_as_float(r2.x << 16), __uint_as_float(r2.x & 0xffff0000u),
+                                   __uint_as_float(r2.y << 16), __uint_as_float(r2.y & 0xffff0000u)};
+                    if (SHIFT) {
+                        // D(f_out, f_in): f_out is the branch output, or (post) the residual stream after
+                        // the add; f_in is the residual operand, or `ref` when one is given
+                        float fi[4] = {rr[0], rr[1], rr[2], rr[3]};
+                        if (ref && m_ok) {
+                            const uint2 f2 = *reinterpret_cast<const uint2*>(ref + (int64_t)m * N + n_base + i * 32 + q * 8 + g * 4);
+                            fi[0] = __uint_as_float(f2.x << 16); fi[1] = __uint_as_float(f2.x & 0xffff0000u);
+                            fi[2] = __uint_as_float(f2.y << 16); fi[3] = __uint_as_float(f2.y & 0xffff0000u);
+                        }
+                        float s0 = 0.f, s1 = 0.f, s2 = 0.f;
+                        if (m_ok) {
+#pragma unroll
+                            for (int e = 0; e < 4; ++e) shift_term<DIST>(post ? v[e] + rr[e] : v[e], fi[e], s0, s1, s2);
+                        }
+                        // g = 1 restarts from the sum of g = 0 (its own first pass is discarded)
+                        const float h0 = __shfl_xor(s0, 32, 64);
+                        float t0 = h0, t1 = 0.f, t2 = 0.f;
+                        if (DIST == RS_DIST_COS) { t1 = __shfl_xor(s1, 32, 64); t2 = __shfl_xor(s2, 32, 64); }
+                        if (m_ok) {
+#pragma unroll
+                            for (int e = 0; e < 4; ++e) shift_term<DIST>(post ? v[e] + rr[e] : v[e], fi[e], t0, t1, t2);
+                        }
+                        pc0[i * 4 + q] = t0;
+                        if (DIST == RS_DIST_COS) { pc1[DIST == RS_DIST_COS ? i * 4 + q : 0] = t1; pc2[DIST == RS_DIST_COS ? i * 4 + q : 0] = t2; }
+                    }
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) v[e] += rr[e];
+                }
+                uint2 w2;
+                w2.x = pack2bf(v[0], v[1]);
+                w2.y = pack2bf(v[2], v[3]);
+                *reinterpret_cast<uint2*>(at) = w2;  // in place: this lane alone reads and writes these 8 bytes
+            }
+        if (SHIFT) {
+            if (g == 1 && m_ok) {  // the half-wave that holds the complete chunk sums
+                float* dst = partials + ((int64_t)m * slots + (n_base >> 6)) * kShiftLanes;
+                dst[0] = ((pc0[0] + pc0[4]) + (pc0[2] + pc0[6])) + ((pc0[1] + pc0[5]) + (pc0[3] + pc0[7]));
+                if (DIST == RS_DIST_COS) {
+                    constexpr int C = DIST == RS_DIST_COS ? 1 : 0;
+                    dst[1] = ((pc1[0] + pc1[4 * C]) + (pc1[2 * C] + pc1[6 * C])) + ((pc1[1 * C] + pc1[5 * C]) + (pc1[3 * C] + pc1[7 * C]));
+                    dst[2] = ((pc2[0] + pc2[4 * C]) + (pc2[2 * C] + pc2[6 * C])) + ((pc2[1 * C] + pc2[5 * C]) + (pc2[3 * C] + pc2[7 * C]));
+                }
+            }
+        }
+        // the group leaves as 16 bytes per lane (LDS accesses of one wave are served in order)
+#pragma unroll
+        for (int p = 0; p < 4; ++p) {
+            const int r = p * 8 + (lane >> 3), cc = lane & 7;
+            const uint4 o4 = *reinterpret_cast<const uint4*>(buf + r * 128 + ((cc ^ epi_swz(r)) << 4));
+            const int mo = m_base + j * 32 + r;
+            if (mo < M) *reinterpret_cast<uint4*>(out + (int64_t)mo * N + n_base + cc * 8) = o4;
+        }
+    }
+}
+
+// ---------------------------------------------------------------------------
+// Ring kernel: workgroup tile BM x BN (BM token rows, BN features), four waves (WGM x WGN, wave
+// tile BM / WGM x 64), K slices of 32 in a ring of three LDS stages, one tile per workgroup and TWO
+// workgroups per compute unit (at most 72 KB of LDS and 256 registers each).  The two run out of
+// step: while one is in its epilogue, or waits at its per-slice barrier for a late copy, the
+// other's K loop keeps the matrix cores busy, and the hardware hands a finished workgroup's slot
+// to the next tile, so the tail of a launch is balanced at half-tile granularity.  Copies run two
+// slices ahead of the matrix work.
+// Slice schedule (one barrier per slice, matrix work on both sides of it): the second K step's
+// fragments are read under the first step's MFMAs; then the wave waits for the next slice's
+// copies, meets the barrier (now every wave has read this slice: its stage is free), requests the
+// slice three ahead into the freed stage and reads the next slice's first fragments under the
+// second step's MFMAs.
+// ---------------------------------------------------------------------------
+template <int BM, int BN, int WGM, int WGN, int EPI, int DIST>
+__global__ __launch_bounds__(256, 2) void gemm_bf16_ring_kernel(
+    const bf16raw* __restrict__ a, const bf16raw* __restrict__ wt, const bf16raw* __restrict__ bias,
+    const bf16raw* __restrict__ res, bf16raw* __restrict__ out, float* __restrict__ partials,
+    const bf16raw* __restrict__ ref, int post, GemmLnFold ln, int M, int N, int K, int tiles_m,
+    int tiles_n, int slots, int gm) {
+    constexpr int NW = WGM * WGN;
+    constexpr int WM = BM / WGM, WN = BN / WGN;
+    constexpr int TM = WM / 32, TN = WN / 32;
+    constexpr int BK = 32, RB = BK * 2, RPI = 16;   // 64-byte LDS rows, 16 rows per wave copy
+    constexpr int A_LOADS = BM / RPI / NW, W_LOADS = BN / RPI / NW, LPW = A_LOADS + W_LOADS;
+    constexpr int STAGE = (BM + BN) * RB;
+    static_assert(NW == 4 && WN == 64 && TN == 2, "four waves, wave tiles 64 features wide");
+    static_assert(BM % (RPI * NW) == 0 && BN % (RPI * NW) == 0, "tile rows must split evenly over the wave copies");
+    static_assert(3 * (STAGE / 4096) >= NW * TM, "the three stages must hold TM 4 KB epilogue regions per wave");
+    __shared__ __attribute__((aligned(1024))) unsigned char st0[STAGE];
+    __shared__ __attribute__((aligned(1024))) unsigned char st1[STAGE];
+    __shared__ __attribute__((aligned(1024))) unsigned char st2[STAGE];
+
+    // tile of this workgroup: ids go round-robin to the 8 XCDs, XCD x takes a contiguous range of a
+    // sequence that walks the grid in groups of gm row panels, m fastest (see gemm_bf16_kernel)
+    const int nblk = tiles_m * tiles_n;
+    const int xcd = blockIdx.x & 7;
+    const int xq = nblk >> 3, xr = nblk & 7;
+    const int x_cnt = xq + (xcd < xr ? 1 : 0), x_start = xcd * xq + (xcd < xr ? xcd : xr);
+    const int seq = blockIdx.x >> 3;
+    if (seq >= x_cnt) return;  // whole workgroup, before any barrier
+    int m0, n0;
+    {
+        const int bid = x_start + seq;
+        const int per_group = gm * tiles_n;
+        const int grp = bid / per_group, rem = bid - grp * per_group;
+        const int first_m = grp * gm;
+        const int gsz = min(tiles_m - first_m, gm);
+        const int tn = rem / gsz;
+        n0 = tn * BN;
+        m0 = (first_m + rem - tn * gsz) * BM;
+    }
+
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int wm = wave % WGM, wn = wave / WGM;
+    const int l32 = lane & 31, g = lane >> 5;
+
+    // global -> LDS: wave copy i of wave w fills rows (NW i + w) 16 .. + 15 (lane l: row l / 4, slot
+    // l % 4 holds chunk (l % 4) ^ f(row), f(r) = (r >> 2) & 3: the 16 rows an operand read touches
+    // fall into 16 different 16-byte bank groups)
+    const __amdgpu_buffer_rsrc_t rs_a = make_rsrc(a + (int64_t)m0 * K, (int64_t)min(M - m0, BM) * K * 2);
+    const __amdgpu_buffer_rsrc_t rs_w = make_rsrc(wt + (int64_t)n0 * K, (int64_t)min(N - n0, BN) * K * 2);
+    const int ld_r = lane >> 2, ld_p = lane & 3;
+    const int voff = ((wave * RPI + ld_r) * K + ((ld_p ^ ((ld_r >> 2) & 3)) << 3)) * 2;
+    const int pass_bytes = NW * RPI * K * 2;
+    const int S = K / BK;
+    const int S_pad = (S + 2) / 3 * 3;
+    const int a_row0 = wm * WM + l32, w_row0 = wn * WN + l32;
+    const int sw = (l32 >> 2) & 3;
+
+#define RS_RING_DMA(stage_, t_)                                                                           \
+    {                                                                                                     \
+        const bool real_ = (t_) < S;                                                                      \
+        const int kb_ = (t_) * RB;                                                                        \
+        _Pragma("unroll") for (int i = 0; i < A_LOADS; ++i)                                               \
+            dma16(rs_a, (stage_) + (i * NW + wave) * 1024, voff, real_ ? i * pass_bytes + kb_ : kPastEnd); \
+        _Pragma("unroll") for (int i = 0; i < W_LOADS; ++i)                                               \
+            dma16(rs_w, (stage_) + BM * RB + (i * NW + wave) * 1024, voff, real_ ? i * pass_bytes + kb_ : kPastEnd); \
+    }
+#define RS_RING_FRAGS(f_, stage_, kk_)                                                                    \
+    {                                                                                                     \
+        const int co_ = ((((kk_) * 2 + g) ^ sw) << 4);                                                    \
+        _Pragma("unroll") for (int i = 0; i < TN; ++i)                                                    \
+            (f_).w[i] = *reinterpret_cast<const bf16x8*>((stage_) + (BM + w_row0 + i * 32) * RB + co_);   \
+        _Pragma("unroll") for (int j = 0; j < TM; ++j)                                                    \
+            (f_).a[j] = *reinterpret_cast<const bf16x8*>((stage_) + (a_row0 + j * 32) * RB + co_);        \
+    }
+#define RS_RING_MFMA(f_)                                                                                  \
+    {                                                                                                     \
+        _Pragma("unroll") for (int i = 0; i < TN; ++i)                                                    \
+            _Pragma("unroll") for (int j = 0; j < TM; ++j)                                                \
+                acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16((f_).w[i], (f_).a[j], acc[i][j], 0, 0, 0); \
+    }
+// every LDS fragment read is followed by its share of copies and of the running step's MFMAs
+#define RS_RING_INTERLEAVE(vm_)                                                                           \
+    {                                                                                                     \
+        _Pragma("unroll") for (int s_ = 0; s_ < TN + TM; ++s_) {                                          \
+            __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);                                            \
+            if (vm_) __builtin_amdgcn_sched_group_barrier(0x020, (LPW + TN + TM - 1) / (TN + TM), 0);     \
+            __builtin_amdgcn_sched_group_barrier(0x008, (TN * TM + TN + TM - 1) / (TN + TM), 0);          \
+        }                                                                                                 \
+        __builtin_amdgcn_sched_barrier(0);                                                                \
+    }
+// vmcnt <= LPW: the copies of the slice after next may be in flight; LDS reads all answered
+#define RS_RING_SLICE(cur_, nxt_, t_)                                                                     \
+    {                                                                                                     \
+        RS_RING_FRAGS(f1, cur_, 1)                                                                        \
+        RS_RING_MFMA(f0)                                                                                  \
+        RS_RING_INTERLEAVE(0)                                                                             \
+        __builtin_amdgcn_s_waitcnt(((LPW) & 15) | (((LPW) >> 4) << 14) | 0x0070);                         \
+        __builtin_amdgcn_s_barrier();                                                                     \
+        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup"); /* LDS reads stay below the barrier */     \
+        __builtin_amdgcn_sched_barrier(0);                                                                \
+        RS_RING_DMA(cur_, (t_) + 3)                                                                       \
+        RS_RING_FRAGS(f0, nxt_, 0)                                                                        \
+        RS_RING_MFMA(f1)                                                                                  \
+        RS_RING_INTERLEAVE(1)                                                                             \
+    }
+
+    f32x16 acc[TN][TM];
+#pragma unroll
+    for (int i = 0; i < TN; ++i)
+#pragma unroll
+        for (int j = 0; j < TM; ++j)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
+
+    RS_RING_DMA(st0, 0)
+    RS_RING_DMA(st1, 1)
+    RS_RING_DMA(st2, 2)
+    Frags<TN, TM> f0, f1;
+    __builtin_amdgcn_s_waitcnt(((2 * LPW) & 15) | (((2 * LPW) >> 4) << 14) | 0x0070);  // slice 0 has landed
+    __builtin_amdgcn_s_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup");
+    __builtin_amdgcn_sched_barrier(0);
+    RS_RING_FRAGS(f0, st0, 0)
+    for (int t = 0; t < S_pad; t += 3) {
+        RS_RING_SLICE(st0, st1, t)
+        RS_RING_SLICE(st1, st2, t + 1)
+        RS_RING_SLICE(st2, st0, t + 2)
+    }
+    __builtin_amdgcn_s_waitcnt(vmcnt_imm(0) & 0xC07F);  // trailing (empty) copies and LDS reads: the stages get reused
+    __builtin_amdgcn_s_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup");
+    __builtin_amdgcn_sched_barrier(0);
+#undef RS_RING_DMA
+#undef RS_RING_FRAGS
+#undef RS_RING_MFMA
+#undef RS_RING_INTERLEAVE
+#undef RS_RING_SLICE
+
+    // epilogue regions: TM x 4 KB per wave, numbered through the three stage arrays
+    EpiRegions<TM> reg;
+    {
+        constexpr int PER = STAGE / 4096;  // regions per stage array
+#pragma unroll
+        for (int j = 0; j < TM; ++j) {
+            const int gi = wave * TM + j;
+            reg.r[j] = (gi / PER == 0 ? st0 : gi / PER == 1 ? st1 : st2) + (gi % PER) * 4096;
+        }
+    }
+    gemm_epilogue_acc_layout<TM, EPI, DIST>(acc, reg, bias, res, out, partials, ref, post, ln, M, N, slots,
+                                            m0 + wm * WM, n0 + wn * WN, lane);
+}
+
 // Tile configuration of the bf16 GEMM: BM, BN, BK, NSTAGE, waves along tokens, waves along features.
+#ifndef RS_GEMM_GM
+#define RS_GEMM_GM 8
+#endif
 struct GemmCfg {
 #ifndef RS_GEMM_CFG
 #define RS_GEMM_CFG 256, 256, 64, 2, 2, 4
@@ -456,29 +806,134 @@ struct GemmCfg {
     static constexpr int WN = BN / WGN;
 };
 
-template <int EPI, int DIST>
-static hipError_t launch_bf16(const void* a, const void* wt, const void* bias, const void* res,
-                              void* out, float* partials, const void* ref, bool post, GemmLnFold ln,
-                              int64_t M, int N, int K, hipStream_t s) {
-    using C = GemmCfg;
-    const int tiles_m = (int)((M + C::BM - 1) / C::BM), tiles_n = (N + C::BN - 1) / C::BN;
-    const int slots = (tiles_n * C::BN) / C::WN;
-#ifndef RS_GEMM_GM
-#define RS_GEMM_GM 8
-#endif
-    const int gm = RS_GEMM_GM;  // row panels per tile group: their activations stay in an XCD's L2 during a sweep over n
-    // one workgroup per CU (8 XCDs x CUs / 8), fewer when an XCD's share of the tiles is smaller
+static int device_cus() {
     static const int cus = [] {
         int dev = 0, n = 0;
         if (hipGetDevice(&dev) != hipSuccess || hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n < 8) n = 256;
         return n;
     }();
+    return cus;
+}
+
+// Which bf16 tile variant runs: 0 = chosen by shape (below), 1 = 256 x 256 persistent kernel,
+// 2 = 256 x 128 ring kernel, 3 = 128 x 128 ring kernel.  Every variant gives the same bits; the
+// switch exists for tuning and for the test that checks exactly that.  Initial value from the
+// environment variable RS_GEMM_FORCE.
+static std::atomic<int> g_gemm_variant{-1};
+
+int gemm_variant() {
+    int v = g_gemm_variant.load(std::memory_order_relaxed);
+    if (v < 0) {
+        const char* e = getenv("RS_GEMM_FORCE");
+        v = e ? atoi(e) : 0;
+        if (v < 0 || v > 4) v = 0;
+        g_gemm_variant.store(v);
+    }
+    return v;
+}
+
+void set_gemm_variant(int v) { g_gemm_variant.store(v >= 0 && v <= 4 ? v : 0); }
+
+struct GemmArgs {
+    const bf16raw *a, *wt, *bias, *res, *ref;
+    bf16raw* out;
+    float* partials;
+    int post;
+    GemmLnFold ln;
+    int64_t M;
+    int N, K;
+    // the same problem restricted to rows [r0, r1)
+    GemmArgs rows(int64_t r0, int64_t r1) const {
+        GemmArgs g = *this;
+        const int slots = (N + 63) / 64;
+        g.a = a + r0 * K;
+        g.res = res ? res + r0 * N : nullptr;
+        g.ref = ref ? ref + r0 * N : nullptr;
+        g.out = out + r0 * N;
+        g.partials = partials ? partials + r0 * slots * kShiftLanes : nullptr;
+        g.ln.stats = ln.stats ? ln.stats + r0 * 2 : nullptr;
+        g.M = r1 - r0;
+        return g;
+    }
+};
+
+template <int BM, int BN, int EPI, int DIST>
+static void launch_ring(const GemmArgs& g, hipStream_t s) {
+    const int tiles_m = (int)((g.M + BM - 1) / BM), tiles_n = (g.N + BN - 1) / BN;
+    const int nblk = tiles_m * tiles_n;
+    constexpr int WGN = BN / 64, WGM = 4 / WGN;  // four waves, each 64 features wide
+    hipLaunchKernelGGL((gemm_bf16_ring_kernel<BM, BN, WGM, WGN, EPI, DIST>), dim3(8 * ((nblk + 7) / 8)), dim3(256), 0, s,
+                       g.a, g.wt, g.bias, g.res, g.out, g.partials, g.ref, g.post, g.ln, (int)g.M, g.N, g.K, tiles_m,
+                       tiles_n, (g.N + 63) / 64, RS_GEMM_GM);
+}
+
+// the ring kernel with the tile height that fills the chip's 2 x CUs workgroup slots
+template <int EPI, int DIST>
+static void launch_ring_auto(const GemmArgs& g, hipStream_t s) {
+    const int64_t tiles_256 = ((g.M + 255) / 256) * ((g.N + 127) / 128);
+    if (tiles_256 >= 2 * device_cus()) launch_ring<256, 128, EPI, DIST>(g, s);
+    else launch_ring<128, 128, EPI, DIST>(g, s);
+}
+
+template <int EPI, int DIST>
+static void launch_persistent(const GemmArgs& g, hipStream_t s) {
+    using C = GemmCfg;
+    const int tiles_m = (int)((g.M + C::BM - 1) / C::BM), tiles_n = (g.N + C::BN - 1) / C::BN;
+    // one workgroup per CU (8 XCDs x CUs / 8), fewer when an XCD's share of the tiles is smaller
+    const int cus = device_cus();
     const int share = (tiles_m * tiles_n + 7) / 8;
     const int per_xcd = share < cus / 8 ? share : cus / 8;
     hipLaunchKernelGGL((gemm_bf16_kernel<C::BM, C::BN, C::BK, C::NSTAGE, C::WGM, C::WGN, EPI, DIST>),
-                       dim3(8 * per_xcd), dim3(C::WGM * C::WGN * 64), 0, s, (const bf16raw*)a,
-                       (const bf16raw*)wt, (const bf16raw*)bias, (const bf16raw*)res, (bf16raw*)out, partials,
-                       (const bf16raw*)ref, post ? 1 : 0, ln, (int)M, N, K, tiles_m, tiles_n, slots, gm);
+                       dim3(8 * per_xcd), dim3(C::WGM * C::WGN * 64), 0, s, g.a, g.wt, g.bias, g.res, g.out, g.partials,
+                       g.ref, g.post, g.ln, (int)g.M, g.N, g.K, tiles_m, tiles_n, (g.N + 63) / 64, RS_GEMM_GM);
+}
+
+// Choice by shape.  The persistent 256 x 256 kernel has the best matrix-core rate while every CU
+// has a tile, but its last round costs a whole round however few tiles it holds, and below one
+// round it leaves CUs empty; the ring kernels (two smaller workgroups per CU, tiles handed out as
+// slots free up) keep the chip busy on small and ragged problems at a lower peak rate.  So: the
+// rows that make up whole rounds of 256 x 256 tiles go to the persistent kernel and the rows
+// behind them to a ring kernel in a second launch -- when a round is long (K at least
+// RS_GEMM_TAIL_MINK: a second launch costs a few microseconds) and the last one is at most
+// RS_GEMM_TAIL_FRAC full.
+#ifndef RS_GEMM_TAIL_FRAC
+#define RS_GEMM_TAIL_FRAC 0.5
+#endif
+#ifndef RS_GEMM_TAIL_MINK
+#define RS_GEMM_TAIL_MINK 2048
+#endif
+// (tuning aids: the environment variables of the same names override the two thresholds)
+static double gemm_tail_frac() {
+    static const double v = [] { const char* e = getenv("RS_GEMM_TAIL_FRAC"); return e ? atof(e) : (double)RS_GEMM_TAIL_FRAC; }();
+    return v;
+}
+static int gemm_tail_mink() {
+    static const int v = [] { const char* e = getenv("RS_GEMM_TAIL_MINK"); return e ? atoi(e) : (int)RS_GEMM_TAIL_MINK; }();
+    return v;
+}
+template <int EPI, int DIST>
+static hipError_t launch_bf16(const void* a, const void* wt, const void* bias, const void* res,
+                              void* out, float* partials, const void* ref, bool post, GemmLnFold ln,
+                              int64_t M, int N, int K, hipStream_t s) {
+    const GemmArgs g{(const bf16raw*)a, (const bf16raw*)wt, (const bf16raw*)bias, (const bf16raw*)res,
+                     (const bf16raw*)ref, (bf16raw*)out, partials, post ? 1 : 0, ln, M, N, K};
+    const int variant = gemm_variant();
+    if (variant == 1) launch_persistent<EPI, DIST>(g, s);
+    else if (variant == 2) launch_ring<256, 128, EPI, DIST>(g, s);
+    else if (variant == 3) launch_ring<128, 128, EPI, DIST>(g, s);
+    else if (variant == 4) launch_ring<128, 256, EPI, DIST>(g, s);
+    else {
+        const int cus = device_cus();
+        const int64_t tiles_n = (N + 255) / 256, panels = (M + 255) / 256;
+        const int64_t tiles = panels * tiles_n, rounds = tiles / cus, rem = tiles - rounds * cus;
+        if (rounds == 0) launch_ring_auto<EPI, DIST>(g, s);
+        else if (rem == 0 || K < gemm_tail_mink() || (double)rem > gemm_tail_frac() * cus) launch_persistent<EPI, DIST>(g, s);
+        else {
+            const int64_t m1 = (rounds * cus / tiles_n) * 256;  // row panels that fill whole rounds
+            launch_persistent<EPI, DIST>(g.rows(0, m1), s);
+            launch_ring_auto<EPI, DIST>(g.rows(m1, M), s);
+        }
+    }
     return hipGetLastError();
 }
 
@@ -601,11 +1056,15 @@ static hipError_t launch_f32(const void* a, const void* w, const void* bias, con
 
 #define RS_STR2(...) #__VA_ARGS__
 #define RS_STR(...) RS_STR2(__VA_ARGS__)
-const char* gemm_build_info() { return "bf16 gemm tiles (BM,BN,BK,stages,waves m,waves n): " RS_STR(RS_GEMM_CFG); }
+const char* gemm_build_info() {
+    return "bf16 gemm: persistent tiles (BM,BN,BK,stages,waves m,waves n) " RS_STR(RS_GEMM_CFG)
+           "; ring tiles 256x128x32 and 128x128x32, 3 stages, 2x2 waves, 2 workgroups per CU"
+           "; rows behind whole rounds go to a ring kernel when K >= " RS_STR(RS_GEMM_TAIL_MINK) " and the last round is under " RS_STR(RS_GEMM_TAIL_FRAC) " full";
+}
 
 int gemm_shift_slots(rs_dtype dt, int N) {
     if (dt == RS_F32) return (N + 63) / 64;
-    return ((N + GemmCfg::BN - 1) / GemmCfg::BN) * GemmCfg::BN / GemmCfg::WN;
+    return (N + 63) / 64;  // one slot per 64 features, whatever the tile variant
 }
 
 template <int EPI, int DIST>

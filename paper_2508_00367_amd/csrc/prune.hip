@@ -198,10 +198,49 @@ __device__ __forceinline__ void block_select(const float* sc, int N, int n_prefi
     }
 }
 
+// The same selection for N <= 256 tokens by counting: token i's rank among the candidates is the
+// number of candidates with a larger key, or an equal key and a lower index; ranks below n_keep
+// survive.  NT / 256 threads share a token's count, a ballot scan over the survival flags gives the
+// output positions: three barriers instead of the radix passes' thirty.  Identical results.
+template <int NT>
+__device__ __forceinline__ void block_select_rank(const float* sc /* LDS */, int N, int n_prefix, int n_keep,
+                                                  int32_t* __restrict__ out, int* slot, SelectShared& sh, int tid) {
+    constexpr int TPT = NT / 256;  // threads per token
+    const int i = tid / TPT, part = tid % TPT;
+    int cnt = 0;
+    if (i >= n_prefix && i < N) {
+        const uint32_t ki = score_key(sc[i]);
+        const int n = N - n_prefix, seg = (n + TPT - 1) / TPT;
+        const int lo = n_prefix + part * seg, hi = min(lo + seg, N);
+        for (int j = lo; j < hi; ++j) {
+            const uint32_t kj = score_key(sc[j]);
+            cnt += (kj > ki) || (kj == ki && j < i);
+        }
+    }
+#pragma unroll
+    for (int off = 1; off < TPT; off <<= 1) cnt += __shfl_xor(cnt, off, 64);
+    // (a caller that loops has a barrier between this write and the previous round's reads of sh)
+    if (part == 0 && i < N) sh.hist[i] = (i < n_prefix || cnt < n_keep) ? 1 : 0;
+    __syncthreads();
+    const int lane = tid & 63, wave = tid >> 6;
+    const int f = (tid < N) ? sh.hist[tid] : 0;        // thread t now stands for token t
+    const unsigned long long mask = __ballot(f);
+    const int before = __popcll(mask & ((1ull << lane) - 1ull));
+    if (wave < 4 && lane == 0) sh.wave[wave] = __popcll(mask);
+    __syncthreads();
+    if (tid < N) {
+        int pos = before;
+        for (int w = 0; w < wave; ++w) pos += sh.wave[w];
+        if (f) out[pos] = tid;
+        if (slot) slot[tid] = f ? pos : -1;
+    }
+}
+
 // With `partials` the scores are first formed from the GEMM epilogue's per-row slots (added in
 // slot order, as finalize_scores_kernel does), kept in LDS for the selection and written to
 // `scores`: the block's prune pass needs no separate score launch.  N * 4 bytes of dynamic LDS.
-__global__ __launch_bounds__(256) void select_kernel(float* __restrict__ scores,
+template <int NT>
+__global__ __launch_bounds__(NT) void select_kernel(float* __restrict__ scores,
                                                      int32_t* __restrict__ kept_idx, int N,
                                                      int n_prefix, int n_keep,
                                                      const float* __restrict__ partials, int slots, int dist) {
@@ -211,7 +250,7 @@ __global__ __launch_bounds__(256) void select_kernel(float* __restrict__ scores,
     const float* sc = scores + (int64_t)blockIdx.x * N;
     int32_t* out = kept_idx + (int64_t)blockIdx.x * (n_prefix + n_keep);
     if (partials) {
-        for (int i = tid; i < N; i += 256) {
+        for (int i = tid; i < N; i += NT) {
             const float* p = partials + ((int64_t)blockIdx.x * N + i) * slots * kShiftLanes;
             float p0 = 0.f, p1 = 0.f, p2 = 0.f;
             for (int sl = 0; sl < slots; ++sl) {
@@ -227,8 +266,12 @@ __global__ __launch_bounds__(256) void select_kernel(float* __restrict__ scores,
         }
         sc = s_scores;
         __syncthreads();
+        if (NT > 256) {  // short sequences: launched with NT / 256 threads per token (N <= 256)
+            block_select_rank<NT>(sc, N, n_prefix, n_keep, out, nullptr, sh, tid);
+            return;
+        }
     }
-    block_select<256>(sc, N, n_prefix, n_keep, out, nullptr, sh, tid);
+    block_select<NT>(sc, N, n_prefix, n_keep, out, nullptr, sh, tid);
 }
 
 // ---------------------------------------------------------------------------
@@ -251,7 +294,15 @@ template <> __device__ __forceinline__ void unpack8<float>(u32x2 v, float (&f)[4
     f[0] = __uint_as_float(v.x); f[1] = __uint_as_float(v.y); f[2] = 0.f; f[3] = 0.f;
 }
 
-constexpr int RES_WAVES = 16;
+#ifndef RS_RES_WAVES
+#define RS_RES_WAVES 16
+#endif
+#ifndef RS_RES_G
+#define RS_RES_G 4
+#endif
+constexpr int RES_WAVES = RS_RES_WAVES;   // waves per workgroup: between them they own the CU's registers
+constexpr int RES_MAXN = 208;             // longest sequence the kernel takes
+constexpr int RES_NR = (RES_MAXN + RES_WAVES - 1) / RES_WAVES;  // rows per wave
 
 template <typename T, int DIST, int CH, int NR>
 __global__ __launch_bounds__(RES_WAVES * 64) void shift_topk_resident_kernel(
@@ -272,19 +323,24 @@ __global__ __launch_bounds__(RES_WAVES * 64) void shift_topk_resident_kernel(
     int voff[CH];
 #pragma unroll
     for (int c = 0; c < CH; ++c) voff[c] = (lane + 64 * c) < row_u ? (lane + 64 * c) * 8 : 0x7fff0000;
-    for (int b = blockIdx.x; b < B; b += gridDim.x) {
-        const __amdgpu_buffer_rsrc_t r_in = __builtin_amdgcn_make_buffer_rsrc(
-            const_cast<T*>(f_in + (int64_t)b * N * D), 0, N * row_bytes, 0x00020000);
-        const __amdgpu_buffer_rsrc_t r_fo = __builtin_amdgcn_make_buffer_rsrc(
-            const_cast<T*>(f_out + (int64_t)b * N * D), 0, N * row_bytes, 0x00020000);
-        u32x2 keep[NR][CH];
+    // The resident rows of the first image; those of every later image are requested row by row
+    // while the previous image's surviving rows are being written out of the same registers, so
+    // their latency passes under that image's stores and the next image's f_out stream.
+    u32x2 keep[NR][CH];
+    {
+        const __amdgpu_buffer_rsrc_t r_in0 = __builtin_amdgcn_make_buffer_rsrc(
+            const_cast<T*>(f_in + (int64_t)blockIdx.x * N * D), 0, (int)blockIdx.x < B ? N * row_bytes : 0, 0x00020000);
 #pragma unroll
         for (int k = 0; k < NR; ++k)
 #pragma unroll
             for (int c = 0; c < CH; ++c)
-                keep[k][c] = __builtin_amdgcn_raw_buffer_load_b64(r_in, voff[c], (wave + RES_WAVES * k) * row_bytes, 0);
+                keep[k][c] = __builtin_amdgcn_raw_buffer_load_b64(r_in0, voff[c], (wave + RES_WAVES * k) * row_bytes, 0);
+    }
+    for (int b = blockIdx.x; b < B; b += gridDim.x) {
+        const __amdgpu_buffer_rsrc_t r_fo = __builtin_amdgcn_make_buffer_rsrc(
+            const_cast<T*>(f_out + (int64_t)b * N * D), 0, N * row_bytes, 0x00020000);
         __builtin_amdgcn_sched_barrier(0);
-        constexpr int G = CH == 3 ? 2 : 4;  // rows of f_out in flight per wave (next to the resident rows)
+        constexpr int G = RS_RES_G;  // rows of f_out in flight per wave (next to the resident rows)
 #pragma unroll
         for (int k0 = 0; k0 < NR; k0 += G) {
             u32x2 t[G][CH];
@@ -325,10 +381,15 @@ __global__ __launch_bounds__(RES_WAVES * 64) void shift_topk_resident_kernel(
             __builtin_amdgcn_sched_barrier(0);  // the next group's loads stay behind this group's sums
         }
         __syncthreads();
-        block_select<NT>(s_scores, N, n_prefix, n_keep, kept_idx + (int64_t)b * K, s_slot, sh, tid);
+        block_select_rank<NT>(s_scores, N, n_prefix, n_keep, kept_idx + (int64_t)b * K, s_slot, sh, tid);
         __syncthreads();
+        // (no barrier at the end of the loop: s_scores is next written before the barrier above, which
+        // no wave passes before all have left the selection; s_slot and sh are next written two barriers on)
         const __amdgpu_buffer_rsrc_t r_out = __builtin_amdgcn_make_buffer_rsrc(
             gathered + (int64_t)b * K * D, 0, K * row_bytes, 0x00020000);
+        const int b_next = b + gridDim.x;
+        const __amdgpu_buffer_rsrc_t r_in = __builtin_amdgcn_make_buffer_rsrc(
+            const_cast<T*>(f_in + (int64_t)(b_next < B ? b_next : 0) * N * D), 0, b_next < B ? N * row_bytes : 0, 0x00020000);
 #pragma unroll
         for (int k = 0; k < NR; ++k) {
             const int i = wave + RES_WAVES * k;
@@ -338,15 +399,15 @@ __global__ __launch_bounds__(RES_WAVES * 64) void shift_topk_resident_kernel(
                 for (int c = 0; c < CH; ++c)
                     __builtin_amdgcn_raw_buffer_store_b64(keep[k][c], r_out, voff[c], __builtin_amdgcn_readfirstlane(j) * row_bytes, 0);
             }
+#pragma unroll
+            for (int c = 0; c < CH; ++c)
+                keep[k][c] = __builtin_amdgcn_raw_buffer_load_b64(r_in, voff[c], i * row_bytes, 0);
         }
-        __syncthreads();  // s_scores and s_slot are reused by the next image
     }
 }
 
-constexpr int RES_NR = 13;  // rows per wave: N <= 208
-
 bool shift_topk_resident_fits(rs_dtype dt, int N, int D) {
-    return N <= RES_NR * RES_WAVES && (size_t)D * elem_size(dt) <= 512 * 3;
+    return N <= RES_MAXN && (size_t)D * elem_size(dt) <= 512 * 3;
 }
 
 template <typename T, int CH>
@@ -395,7 +456,7 @@ hipError_t launch_select(const float* scores, int32_t* kept_idx, int B, int N, i
         const int64_t tot = (int64_t)B * N;
         hipLaunchKernelGGL(iota_kernel, dim3((unsigned)((tot + 255) / 256)), dim3(256), 0, s, kept_idx, B, N);
     } else {
-        hipLaunchKernelGGL(select_kernel, dim3(B), dim3(256), 0, s, const_cast<float*>(scores), kept_idx, N,
+        hipLaunchKernelGGL(select_kernel<256>, dim3(B), dim3(256), 0, s, const_cast<float*>(scores), kept_idx, N,
                            n_prefix, n_keep, (const float*)nullptr, 0, 0);
     }
     return hipGetLastError();
@@ -407,40 +468,32 @@ hipError_t launch_select_from_partials(rs_dist dist, const float* partials, int 
                                        int32_t* kept_idx, int B, int N, int n_prefix, int n_keep,
                                        hipStream_t s) {
     if (B == 0) return hipSuccess;
-    hipLaunchKernelGGL(select_kernel, dim3(B), dim3(256), (size_t)N * sizeof(float), s, scores, kept_idx, N,
-                       n_prefix, n_keep, partials, slots, (int)dist);
+    if (N <= 256)
+        hipLaunchKernelGGL(select_kernel<1024>, dim3(B), dim3(1024), (size_t)N * sizeof(float), s, scores, kept_idx, N,
+                           n_prefix, n_keep, partials, slots, (int)dist);
+    else
+        hipLaunchKernelGGL(select_kernel<256>, dim3(B), dim3(256), (size_t)N * sizeof(float), s, scores, kept_idx, N,
+                           n_prefix, n_keep, partials, slots, (int)dist);
     return hipGetLastError();
 }
 
 // ---------------------------------------------------------------------------
-// Gather: out[b, j, :] = src[b, kept_idx[b, j], :].  The output is one contiguous run of
-// 16-byte vectors; thread t copies vectors t, t + 256, ... of its workgroup's stretch (four per
-// thread, all loads issued before the stores), so every lane works whatever the row length
-// (rows are D * e bytes, a multiple of 16).
+// Gather: out[b, j, :] = src[b, kept_idx[b, j], :]; one wavefront per row, 16 bytes per
+// lane per step (rows are D * e bytes, a multiple of 16).  (A variant over the flat output, four
+// vectors per thread whatever the row length, measured 50 % slower at 1536-byte rows.)
 // ---------------------------------------------------------------------------
-constexpr int GATHER_UNROLL = 4;
-
 __global__ __launch_bounds__(256) void gather_rows_kernel(const uint4* __restrict__ src,
                                                           const int32_t* __restrict__ kept_idx,
-                                                          uint4* __restrict__ out, int64_t total_vec,
+                                                          uint4* __restrict__ out, int64_t rows,
                                                           int N, int K, int row_vec) {
-    const int64_t base = (int64_t)blockIdx.x * (256 * GATHER_UNROLL) + threadIdx.x;
-    uint4 v[GATHER_UNROLL];
-#pragma unroll
-    for (int u = 0; u < GATHER_UNROLL; ++u) {
-        const int64_t t = base + u * 256;
-        if (t < total_vec) {
-            const int64_t r = t / row_vec;           // output row b * K + j
-            const int c = (int)(t - r * row_vec);
-            const int64_t b = r / K;
-            v[u] = src[(b * N + kept_idx[r]) * row_vec + c];
-        }
-    }
-#pragma unroll
-    for (int u = 0; u < GATHER_UNROLL; ++u) {
-        const int64_t t = base + u * 256;
-        if (t < total_vec) out[t] = v[u];
-    }
+    const int lane = threadIdx.x & 63;
+    const int64_t r = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
+    if (r >= rows) return;
+    const int64_t b = r / K;
+    const int32_t idx = kept_idx[r];
+    const uint4* s = src + (b * N + idx) * row_vec;
+    uint4* d = out + r * row_vec;
+    for (int c = lane; c < row_vec; c += 64) d[c] = s[c];
 }
 
 hipError_t launch_gather(rs_dtype dt, const void* src, const int32_t* kept_idx, void* out, int B,
@@ -448,10 +501,8 @@ hipError_t launch_gather(rs_dtype dt, const void* src, const int32_t* kept_idx, 
     const int64_t rows = (int64_t)B * K;
     if (rows == 0) return hipSuccess;
     const int row_vec = (int)((size_t)D * elem_size(dt) / 16);
-    const int64_t total_vec = rows * row_vec;
-    const int64_t per_wg = 256 * GATHER_UNROLL;
-    hipLaunchKernelGGL(gather_rows_kernel, dim3((unsigned)((total_vec + per_wg - 1) / per_wg)), dim3(256), 0, s,
-                       (const uint4*)src, kept_idx, (uint4*)out, total_vec, N, K, row_vec);
+    hipLaunchKernelGGL(gather_rows_kernel, dim3((unsigned)((rows + 3) / 4)), dim3(256), 0, s,
+                       (const uint4*)src, kept_idx, (uint4*)out, rows, N, K, row_vec);
     return hipGetLastError();
 }
 

@@ -225,6 +225,12 @@ int32_t rs_version(void) { return 200; }
 
 const char* rs_build_info(void) { return gemm_build_info(); }
 
+rs_status rs_tune_gemm_variant(int32_t variant) {
+    RS_REQUIRE(variant >= 0 && variant <= 4, RS_ERR_INVALID_ARG, "variant %d outside 0..4", (int)variant);
+    set_gemm_variant(variant);
+    return RS_OK;
+}
+
 rs_status rs_profile_enable(int32_t enable) {
     std::lock_guard<std::mutex> lk(g_prof.mu);
     g_prof.on.store(enable != 0);

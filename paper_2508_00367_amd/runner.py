@@ -39,7 +39,37 @@ class EncoderStack:
             rs.rs_pack_weights(cfg0, rs.make_weights(w), packed)
             self._keep_alive.append((w, packed))
             self.weights.append(rs.make_weights(w, packed))
+        self.gemm_variant = 0            # tile-variant switch of the bf16 GEMMs (0 = chosen by shape)
         self.set_streams(streams)
+
+    def tune(self, candidates=((1, 0), (2, 0), (2, 1)), steps: int = 8, rounds: int = 2):
+        """Times a few launch configurations (streams, GEMM tile variant) and keeps the fastest.
+        Every configuration computes the same bits (images are independent, the tile variants add
+        products and shift sums in one fixed order), so this is a choice of speed only: parts on
+        several streams overlap well when every kernel is of one kind (the persistent 256 x 256 GEMM
+        everywhere), a single stream gains most from the shape-dependent mix of kernels.
+        Returns {(streams, variant): seconds per step}."""
+        import time
+        seen = {}
+        for _ in range(rounds):                      # every candidate `rounds` times, the best time counts
+            for S, v in candidates:
+                if S > self.B:
+                    continue
+                self.set_streams(S)
+                self.gemm_variant = v
+                for _ in range(2):
+                    self.step()
+                torch.cuda.synchronize()
+                t0 = time.perf_counter()
+                for _ in range(steps):
+                    self.step()
+                torch.cuda.synchronize()
+                key = (len(self.parts), v)
+                seen[key] = min(seen.get(key, 1e30), (time.perf_counter() - t0) / steps)
+        (S, v) = min(seen, key=seen.get)
+        self.set_streams(S)
+        self.gemm_variant = v
+        return seen
 
     def set_streams(self, streams: int) -> None:
         S = max(1, min(int(streams), self.B))
@@ -63,6 +93,7 @@ class EncoderStack:
         capture(l, part, src, dst) is called after block l of a part has been enqueued;
         scores: optional per-part list of float32 [Bp, N] tensors the blocks write their scores to.
         Returns the per-part output tensors (views of the ping-pong buffers, [Bp, K_last, D])."""
+        rs.rs_tune_gemm_variant(self.gemm_variant)     # process-wide switch: set on every step
         src = [p["x"] for p in self.parts]
         for l in range(self.L):
             for i, p in enumerate(self.parts):

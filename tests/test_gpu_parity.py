@@ -419,6 +419,56 @@ def test_block_packed_weights_and_determinism():
         assert torch.equal(t0, t1) and torch.equal(t1, t2)
 
 
+@pytest.mark.parametrize("dist", [rs.RS_DIST_L2, rs.RS_DIST_COS])
+def test_gemm_tile_variants_give_the_same_bits(dist):
+    """The bf16 GEMMs pick a tile variant by shape (256 x 256 persistent workgroups, 256 x 128 or
+    128 x 128 ring kernels, or the first for whole rounds and a ring kernel for the rows behind them).
+    Products are accumulated in the same order in all of them and the shift sums are added in one
+    fixed order, so outputs, scores and kept indices must not depend on the variant: 700 rows x 3
+    images (ragged row tiles in every variant), D 192 (one and a half 128-wide column tiles)."""
+    x, w = _block_inputs(17, 3, 700, 192, 768, "bf16", std=0.1, spread=0.3, affine_ln=True)
+    outs = []
+    try:
+        for variant in (0, 1, 2, 3):
+            rs.rs_tune_gemm_variant(variant)
+            outs.append(_run_block(x, w, 3, 1, 300, "bf16", dist=dist, op=rs.RS_SHIFT_BLOCK))
+    finally:
+        rs.rs_tune_gemm_variant(0)
+    for y, kept, scores in outs[1:]:
+        assert torch.equal(scores.view(torch.int32), outs[0][2].view(torch.int32))
+        assert torch.equal(kept, outs[0][1])
+        assert torch.equal(y.view(torch.int16), outs[0][0].view(torch.int16))
+
+
+def test_gemm_rows_split_between_two_kernels():
+    """A GEMM whose 256 x 256 tiles make one whole round of the chip and a small second one: the rows
+    of the whole round go to the persistent kernel, the rest to a ring kernel in a second launch.
+    Both halves against the checker (sampled rows), and the result against the one-kernel variants."""
+    M, K, N = 256 * 90 + 77, 256, 768      # 91 row panels x 3 column tiles = 273 tiles on 256 CUs
+    a = host_round(si.generic(19, 30, (M, K)), "bf16")
+    wgt = host_round(si.generic(19, 31, (K, N), std=0.05), "bf16")
+    b = host_round(si.generic(19, 32, (N,), std=0.5), "bf16")
+    res = host_round(si.generic(19, 33, (M, N)), "bf16")
+    da, dw, db, dres = (to_dev(t, "bf16") for t in (a, wgt, b, res))
+    wt = torch.empty((N, K), device="cuda", dtype=torch.bfloat16)
+    rs.rs_pack_linear(dw, wt)
+    outs = []
+    try:
+        for variant in (0, 1, 2):
+            rs.rs_tune_gemm_variant(variant)
+            out = torch.full((M, N), float("nan"), device="cuda", dtype=torch.bfloat16)
+            rs.rs_linear_fwd(da, wt, db, dres, out, rs.RS_EPI_BIAS_RES)
+            torch.cuda.synchronize()
+            outs.append(out)
+    finally:
+        rs.rs_tune_gemm_variant(0)
+    assert torch.equal(outs[0].view(torch.int16), outs[1].view(torch.int16))
+    assert torch.equal(outs[0].view(torch.int16), outs[2].view(torch.int16))
+    rows = np.r_[0:40, 21700:21800, M - 150:M]     # first tile, around the split (row 21760), ragged end
+    ref = oracle.linear(a[rows], wgt, b) + res[rows]
+    assert norm_err(to_host(outs[0])[rows], ref) < 5e-3
+
+
 def test_multi_block_teacher_forced():
     """Four blocks of a ViT-S-like stack with 16 tokens dropped after each: the checker follows
     the GPU's kept set block by block (kept sets may legitimately differ inside the rounding band)."""
