@@ -193,6 +193,38 @@ def grid_gather(src, kept_rows, kept_cols):
     return out
 
 
+def grid_token_prune(f_out, f_in, src, keep_rows, keep_cols, dist=DIST_L2):
+    """Token-wise pruning of a [B, H, W, C] grid (Sec. 4.2, "CNN and SSM", variant (i): the least
+    important tokens are removed from each row and column).  Reading taken: first every ROW loses
+    its W - keep_cols lowest-shift positions and closes up to the left (the grid becomes H x
+    keep_cols, position j of row h being that row's j-th survivor); then every COLUMN of that
+    compacted grid loses its H - keep_rows lowest-shift positions and closes up upwards.  Ties: the
+    lower index survives; survivors keep their order.  `src` (f_out when None) is cut down the same way.
+
+    Returns scores [B,H,W], kept_cols [B,H,Q] (per row, original column indices), col_scores [B,Q,H]
+    (shift of the row-compacted grid, column by column), kept_rows [B,Q,R] (per compacted column, row
+    indices), gathered [B,R,Q,C] with gathered[b,i,j] = src[b, r, kept_cols[b,r,j]], r = kept_rows[b,j,i]."""
+    a, b = _d(f_out), _d(f_in)
+    B, H, W, C = a.shape
+    R, Q = int(keep_rows), int(keep_cols)
+    s = shift_scores(a, b, dist)                                        # [B, H, W]
+    kc = topk(s.reshape(B * H, W), 0, Q).reshape(B, H, Q)               # step 1: per row
+    cs = np.empty((B, Q, H), np.float64)
+    for b_ in range(B):
+        for h in range(H):
+            for j in range(Q):
+                cs[b_, j, h] = s[b_, h, kc[b_, h, j]]
+    kr = topk(cs.reshape(B * Q, H), 0, R).reshape(B, Q, R)              # step 2: per compacted column
+    g = np.empty((B, R, Q, C), np.float64)
+    sr = a if src is None else _d(src)
+    for b_ in range(B):
+        for i in range(R):
+            for j in range(Q):
+                r = kr[b_, j, i]
+                g[b_, i, j] = sr[b_, r, kc[b_, r, j]]
+    return s, kc, cs, kr, g
+
+
 def block(x, w, H, ln_eps=1e-6, attn_scale=None, dist=DIST_L2, op=OP_MLP):
     """One encoder block on x [B, N, D] with weight dict `w` (missing/None bias = 0).
 

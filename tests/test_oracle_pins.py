@@ -473,3 +473,71 @@ def test_grid_line_prune_against_numpy_sort():
             np.testing.assert_array_equal(kr[b], np.sort(np.argsort(-want.mean(axis=2)[b], kind="stable")[:4]))
             np.testing.assert_array_equal(kc[b], np.sort(np.argsort(-want.mean(axis=1)[b], kind="stable")[:3]))
             np.testing.assert_array_equal(g[b], src[b][kr[b]][:, kc[b]])
+
+
+# ----------------------------------------------------------------------------
+# token-wise pruning of a 2-D grid (Sec. 4.2, CNN variant (i))
+# ----------------------------------------------------------------------------
+def _grid_case(seed, B, H, W, C):
+    rng = np.random.default_rng(seed)
+    f_in = rng.standard_normal((B, H, W, C))
+    f_out = f_in + rng.standard_normal((B, H, W, C)) * np.exp(rng.standard_normal((B, H, W, 1)))
+    return f_out, f_in
+
+
+def test_grid_token_prune_against_sorting_by_hand():
+    """Brute force with Python's sort on (-score, index) keys, written without the checker's own
+    selection routine: per row keep the Q highest, then per compacted column the R highest."""
+    B, H, W, C, R, Q = 2, 6, 7, 5, 4, 3
+    f_out, f_in = _grid_case(1, B, H, W, C)
+    s, kc, cs, kr, g = oracle.grid_token_prune(f_out, f_in, None, R, Q)
+    for b in range(B):
+        sc = np.sqrt(((f_out[b] - f_in[b]) ** 2).sum(-1))
+        np.testing.assert_allclose(s[b], sc, rtol=1e-12)
+        cols = [sorted(sorted(range(W), key=lambda w: (-sc[h, w], w))[:Q]) for h in range(H)]
+        np.testing.assert_array_equal(kc[b], np.array(cols))
+        for j in range(Q):
+            col = [sc[h, cols[h][j]] for h in range(H)]
+            np.testing.assert_allclose(cs[b, j], col, rtol=1e-12)
+            rows = sorted(sorted(range(H), key=lambda h: (-col[h], h))[:R])
+            np.testing.assert_array_equal(kr[b, j], rows)
+            for i, r in enumerate(rows):
+                np.testing.assert_array_equal(g[b, i, j], f_out[b, r, cols[r][j]])
+
+
+def test_grid_token_prune_closed_forms():
+    B, H, W, C = 1, 5, 6, 4
+    f_in = np.zeros((B, H, W, C))
+    # shift that depends on the column only: every row keeps the same columns (the Q largest
+    # amplitudes), every compacted column then ties over the rows -> the first R rows survive
+    amp = np.array([3.0, 1.0, 5.0, 2.0, 6.0, 4.0])
+    f_out = np.zeros((B, H, W, C))
+    f_out[..., 0] = amp[None, None, :]
+    s, kc, cs, kr, g = oracle.grid_token_prune(f_out, f_in, None, 3, 4)
+    np.testing.assert_array_equal(kc[0], np.tile([0, 2, 4, 5], (H, 1)))
+    np.testing.assert_array_equal(kr[0], np.tile([0, 1, 2], (4, 1)))
+    np.testing.assert_array_equal(g[0, :, :, 0], np.tile(amp[[0, 2, 4, 5]], (3, 1)))
+    # shift that depends on the row only: rows tie inside -> the first Q columns; then the R largest rows
+    ramp = np.array([2.0, 9.0, 1.0, 7.0, 3.0])
+    f_out = np.zeros((B, H, W, C))
+    f_out[..., 1] = ramp[None, :, None]
+    s, kc, cs, kr, g = oracle.grid_token_prune(f_out, f_in, None, 2, 3)
+    np.testing.assert_array_equal(kc[0], np.tile([0, 1, 2], (H, 1)))
+    np.testing.assert_array_equal(kr[0], np.tile([1, 3], (3, 1)))
+    # the same answer as the line-wise variant in these two separable cases
+    s2, r2, c2, kr2, kc2, g2 = oracle.grid_line_prune(f_out, f_in, None, 2, 3)
+    np.testing.assert_array_equal(g, g2)
+    # keep everything: identity
+    f_out, f_in = _grid_case(2, 2, 4, 3, 8)
+    s, kc, cs, kr, g = oracle.grid_token_prune(f_out, f_in, None, 4, 3)
+    np.testing.assert_array_equal(g, f_out)
+    np.testing.assert_array_equal(kc, np.tile(np.arange(3), (2, 4, 1)))
+    # a position with a large shift in an otherwise weak row survives step 1 and step 2, which
+    # line-wise pruning would have dropped with its row
+    f_in = np.zeros((1, 4, 4, 2))
+    f_out = np.zeros((1, 4, 4, 2))
+    f_out[0, :, :, 0] = np.array([[5, 5, 5, 5], [5, 5, 5, 5], [0.1, 0.1, 9.0, 0.1], [5, 5, 5, 5]])
+    s, kc, cs, kr, g = oracle.grid_token_prune(f_out, f_in, None, 3, 3)
+    assert 9.0 in g[0, :, :, 0]
+    s2, r2, c2, kr2, kc2, g2 = oracle.grid_line_prune(f_out, f_in, None, 3, 3)
+    assert 9.0 not in g2[0, :, :, 0]
