@@ -192,14 +192,35 @@ RS_API rs_status rs_pack_weights(const rs_block_cfg *cfg, const rs_block_weights
  *   scores [B,H,W], row_scores [B,H], col_scores [B,W] : fp32 outputs, all required.
  *   kept_rows [B, keep_rows], kept_cols [B, keep_cols] : int32 outputs.
  *   gathered [B, keep_rows, keep_cols, C] or NULL; must not alias src.
- * C % 8 == 0.  No workspace.  Deterministic.  The token-wise variant (i) of the same passage
- * is not built.
+ * C % 8 == 0.  No workspace.  Deterministic.
  */
 RS_API rs_status rs_grid_line_prune(const void *f_out, const void *f_in, const void *src, int32_t B,
                                     int32_t H, int32_t W, int32_t C, int32_t keep_rows,
                                     int32_t keep_cols, rs_dist dist, rs_dtype dtype, float *scores,
                                     float *row_scores, float *col_scores, int32_t *kept_rows,
                                     int32_t *kept_cols, void *gathered, void *hip_stream);
+
+/*
+ * Token-wise pruning of a 2-D token grid (Sec. 4.2, "CNN and SSM", variant (i): "removing the least
+ * important tokens from each row and column").  The passage does not say how the grid stays
+ * rectangular; the reading built here: every ROW first loses its W - keep_cols lowest-shift positions
+ * and closes up (position j of row h is then that row's j-th survivor), after which every COLUMN of
+ * the compacted H x keep_cols grid loses its H - keep_rows lowest-shift positions and closes up.
+ * Ties: the lower index survives; survivors keep their order.
+ *   f_out, f_in, src : as in rs_grid_line_prune ([B, H, W, C], src NULL = f_out).
+ *   scores     [B, H, W]                 fp32 out: shift per position.
+ *   kept_cols  [B, H, keep_cols]         int32 out: per row, the surviving column indices, ascending.
+ *   col_scores [B, keep_cols, H]         fp32 out: shift of the row-compacted grid, column by column.
+ *   kept_rows  [B, keep_cols, keep_rows] int32 out: per compacted column, surviving row indices, ascending.
+ *   gathered   [B, keep_rows, keep_cols, C] or NULL:
+ *              gathered[b, i, j, :] = src[b, r, kept_cols[b, r, j], :] with r = kept_rows[b, j, i].
+ * C % 8 == 0, B*H <= 2^31 - 1 grid rows.  No workspace.  Deterministic.
+ */
+RS_API rs_status rs_grid_token_prune(const void *f_out, const void *f_in, const void *src, int32_t B,
+                                     int32_t H, int32_t W, int32_t C, int32_t keep_rows,
+                                     int32_t keep_cols, rs_dist dist, rs_dtype dtype, float *scores,
+                                     int32_t *kept_cols, float *col_scores, int32_t *kept_rows,
+                                     void *gathered, void *hip_stream);
 
 /*
  * One linear layer of the block with its fused elementwise tail (the four contractions of

@@ -24,7 +24,7 @@ RS_EPI_BIAS, RS_EPI_BIAS_GELU, RS_EPI_BIAS_RES = 0, 1, 2
 
 EXPORTS = ("rs_last_error", "rs_version", "rs_build_info", "rs_tune_gemm_variant", "rs_profile_enable", "rs_profile_read",
            "rs_profile_class_name", "rs_attention_fwd", "rs_shift_topk_workspace_size",
-           "rs_shift_topk", "rs_grid_line_prune", "rs_pack_linear", "rs_linear_fwd", "rs_packed_weights_size", "rs_pack_weights", "rs_block_workspace_size",
+           "rs_shift_topk", "rs_grid_line_prune", "rs_grid_token_prune", "rs_pack_linear", "rs_linear_fwd", "rs_packed_weights_size", "rs_pack_weights", "rs_block_workspace_size",
            "rs_block_fwd", "rs_block_static_scratch_size", "rs_block_fwd_static")
 
 _vp = ctypes.c_void_p
@@ -85,6 +85,9 @@ def lib():
         L.rs_grid_line_prune.argtypes = [_vp, _vp, _vp, _i32, _i32, _i32, _i32, _i32, _i32, ctypes.c_int, ctypes.c_int,
                                          _vp, _vp, _vp, _vp, _vp, _vp, _vp]
         L.rs_grid_line_prune.restype = ctypes.c_int
+        L.rs_grid_token_prune.argtypes = [_vp, _vp, _vp, _i32, _i32, _i32, _i32, _i32, _i32, ctypes.c_int, ctypes.c_int,
+                                          _vp, _vp, _vp, _vp, _vp, _vp]
+        L.rs_grid_token_prune.restype = ctypes.c_int
         L.rs_linear_fwd.argtypes = [_vp, _vp, _vp, _vp, _vp, _i64, _i32, _i32, ctypes.c_int, ctypes.c_int, _vp]
         L.rs_linear_fwd.restype = ctypes.c_int
         L.rs_packed_weights_size.argtypes = [ctypes.POINTER(RsBlockCfg)]
@@ -206,6 +209,15 @@ def rs_grid_line_prune(f_out, f_in, src, keep_rows, keep_cols, scores, row_score
     _check(lib().rs_grid_line_prune(_ptr(f_out), _ptr(f_in), _ptr(src), B, H, W, C, keep_rows, keep_cols, dist,
                                     dtype_code(f_in.dtype), _ptr(scores), _ptr(row_scores), _ptr(col_scores),
                                     _ptr(kept_rows), _ptr(kept_cols), _ptr(gathered), _stream(stream)))
+
+
+def rs_grid_token_prune(f_out, f_in, src, keep_rows, keep_cols, scores, kept_cols, col_scores, kept_rows, gathered,
+                        dist=RS_DIST_L2, stream=None) -> None:
+    """Token-wise pruning of a [B, H, W, C] grid: rows lose their lowest positions, then the compacted columns."""
+    B, H, W, C = f_in.shape
+    _check(lib().rs_grid_token_prune(_ptr(f_out), _ptr(f_in), _ptr(src), B, H, W, C, keep_rows, keep_cols, dist,
+                                     dtype_code(f_in.dtype), _ptr(scores), _ptr(kept_cols), _ptr(col_scores),
+                                     _ptr(kept_rows), _ptr(gathered), _stream(stream)))
 
 
 def rs_pack_linear(w, wt, stream=None) -> None:

@@ -186,4 +186,11 @@ hipError_t launch_grid_line_scores(const float* scores, float* row_scores, float
 hipError_t launch_grid_gather(rs_dtype dt, const void* src, const int32_t* kept_rows, const int32_t* kept_cols,
                               void* out, int B, int H, int W, int R, int Q, int C, hipStream_t s);
 
+// token-wise grid pruning: col_scores[b, j, h] = scores[b, h, kept_cols[b, h, j]]
+hipError_t launch_grid_compact_scores(const float* scores, const int32_t* kept_cols, float* col_scores, int B, int H,
+                                      int W, int Q, hipStream_t s);
+// out[b, i, j, :] = src[b, r, kept_cols[b, r, j], :], r = kept_rows[b, j, i]
+hipError_t launch_grid_token_gather(rs_dtype dt, const void* src, const int32_t* kept_cols, const int32_t* kept_rows,
+                                    void* out, int B, int H, int W, int R, int Q, int C, hipStream_t s);
+
 }  // namespace rs

@@ -562,4 +562,60 @@ hipError_t launch_grid_gather(rs_dtype dt, const void* src, const int32_t* kept_
     return hipGetLastError();
 }
 
+// ---------------------------------------------------------------------------
+// Token-wise pruning of a 2-D token grid (Sec. 4.2, "CNN and SSM", variant (i)): every row first
+// keeps its Q highest-shift positions (select_kernel, one grid row as one "image"), the rows close
+// up, and every column of the compacted H x Q grid then keeps its R highest-shift positions.
+// col_scores[b, j, h] = scores[b, h, kept_cols[b, h, j]] feeds the second selection.
+// ---------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void grid_compact_scores_kernel(const float* __restrict__ scores,
+                                                                  const int32_t* __restrict__ kept_cols,
+                                                                  float* __restrict__ col_scores, int64_t total,
+                                                                  int H, int W, int Q) {
+    const int64_t t = (int64_t)blockIdx.x * 256 + threadIdx.x;  // index into [B, Q, H]
+    if (t >= total) return;
+    const int h = (int)(t % H);
+    const int64_t bj = t / H;
+    const int j = (int)(bj % Q);
+    const int64_t b = bj / Q;
+    col_scores[t] = scores[(b * H + h) * W + kept_cols[(b * H + h) * Q + j]];
+}
+
+// out[b, i, j, :] = src[b, r, kept_cols[b, r, j], :] with r = kept_rows[b, j, i]; one wavefront per position
+__global__ __launch_bounds__(256) void grid_token_gather_kernel(const uint4* __restrict__ src,
+                                                                const int32_t* __restrict__ kept_cols,
+                                                                const int32_t* __restrict__ kept_rows,
+                                                                uint4* __restrict__ out, int64_t positions, int H,
+                                                                int W, int R, int Q, int vec) {
+    const int lane = threadIdx.x & 63;
+    const int64_t p = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
+    if (p >= positions) return;
+    const int64_t b = p / ((int64_t)R * Q);
+    const int ij = (int)(p - b * R * Q);
+    const int i = ij / Q, j = ij - i * Q;
+    const int r = kept_rows[(b * Q + j) * R + i];
+    const int c = kept_cols[(b * H + r) * Q + j];
+    const int64_t sp = (b * H + r) * W + c;
+    for (int v = lane; v < vec; v += 64) out[p * vec + v] = src[sp * vec + v];
+}
+
+hipError_t launch_grid_compact_scores(const float* scores, const int32_t* kept_cols, float* col_scores, int B, int H,
+                                      int W, int Q, hipStream_t s) {
+    const int64_t total = (int64_t)B * Q * H;
+    if (total == 0) return hipSuccess;
+    hipLaunchKernelGGL(grid_compact_scores_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, s, scores,
+                       kept_cols, col_scores, total, H, W, Q);
+    return hipGetLastError();
+}
+
+hipError_t launch_grid_token_gather(rs_dtype dt, const void* src, const int32_t* kept_cols, const int32_t* kept_rows,
+                                    void* out, int B, int H, int W, int R, int Q, int C, hipStream_t s) {
+    const int64_t positions = (int64_t)B * R * Q;
+    if (positions == 0) return hipSuccess;
+    const int vec = (int)((size_t)C * elem_size(dt) / 16);
+    hipLaunchKernelGGL(grid_token_gather_kernel, dim3((unsigned)((positions + 3) / 4)), dim3(256), 0, s,
+                       (const uint4*)src, kept_cols, kept_rows, (uint4*)out, positions, H, W, R, Q, vec);
+    return hipGetLastError();
+}
+
 }  // namespace rs

@@ -362,6 +362,42 @@ rs_status rs_grid_line_prune(const void* f_out, const void* f_in, const void* sr
     return RS_OK;
 }
 
+rs_status rs_grid_token_prune(const void* f_out, const void* f_in, const void* src, int32_t B, int32_t H,
+                              int32_t W, int32_t C, int32_t keep_rows, int32_t keep_cols, rs_dist dist,
+                              rs_dtype dtype, float* scores, int32_t* kept_cols, float* col_scores,
+                              int32_t* kept_rows, void* gathered, void* hip_stream) {
+    RS_REQUIRE(dtype == RS_F32 || dtype == RS_BF16, RS_ERR_INVALID_ARG, "unknown dtype %d", (int)dtype);
+    RS_REQUIRE(dist == RS_DIST_L2 || dist == RS_DIST_L1 || dist == RS_DIST_COS, RS_ERR_INVALID_ARG,
+               "unknown distance %d", (int)dist);
+    RS_REQUIRE(B >= 0 && H >= 0 && W >= 0, RS_ERR_INVALID_ARG, "negative B, H or W");
+    RS_REQUIRE(C > 0 && C % 8 == 0, RS_ERR_INVALID_ARG, "C must be a positive multiple of 8");
+    RS_REQUIRE(keep_rows >= 0 && keep_rows <= H && keep_cols >= 0 && keep_cols <= W, RS_ERR_INVALID_ARG,
+               "need 0 <= keep_rows <= H and 0 <= keep_cols <= W");
+    RS_REQUIRE((int64_t)B * H * W < (int64_t)1 << 31, RS_ERR_UNSUPPORTED, "B*H*W does not fit 31 bits");
+    if (B == 0 || H == 0 || W == 0) return RS_OK;
+    RS_REQUIRE(f_out && f_in && scores, RS_ERR_INVALID_ARG, "f_out, f_in and scores must not be NULL");
+    RS_REQUIRE(kept_cols || keep_cols == 0, RS_ERR_INVALID_ARG, "kept_cols must not be NULL");
+    RS_REQUIRE((col_scores && kept_rows) || keep_cols == 0 || keep_rows == 0, RS_ERR_INVALID_ARG,
+               "col_scores and kept_rows must not be NULL");
+    const void* s = src ? src : f_out;
+    RS_REQUIRE(aligned16(f_out) && aligned16(f_in) && aligned16(s) && aligned16(gathered), RS_ERR_INVALID_ARG,
+               "tensors must be 16-byte aligned");
+    RS_REQUIRE(gathered == nullptr || gathered != s, RS_ERR_INVALID_ARG, "gathered must not alias src");
+    hipStream_t st = (hipStream_t)hip_stream;
+    RS_LAUNCH_K(K_SCORE, st, launch_shift_scores(dtype, dist, f_out, f_in, scores, (int64_t)B * H * W, C, st));
+    if (keep_cols == 0) return RS_OK;
+    // step 1: every grid row is one selection problem over its W positions
+    RS_LAUNCH_K(K_SELECT, st, launch_select(scores, kept_cols, B * H, W, 0, keep_cols, st));
+    if (keep_rows == 0) return RS_OK;
+    // step 2: every column of the row-compacted grid is one selection problem over H positions
+    RS_LAUNCH_K(K_SCORE, st, launch_grid_compact_scores(scores, kept_cols, col_scores, B, H, W, keep_cols, st));
+    RS_LAUNCH_K(K_SELECT, st, launch_select(col_scores, kept_rows, B * keep_cols, H, 0, keep_rows, st));
+    if (gathered)
+        RS_LAUNCH_K(K_GATHER, st, launch_grid_token_gather(dtype, s, kept_cols, kept_rows, gathered, B, H, W, keep_rows,
+                                                         keep_cols, C, st));
+    return RS_OK;
+}
+
 size_t rs_packed_weights_size(const rs_block_cfg* cfg) {
     if (!cfg || cfg->D <= 0 || cfg->Dm <= 0) return 0;
     return packed_bytes(cfg);

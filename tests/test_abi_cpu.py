@@ -204,6 +204,26 @@ def test_static_scratch_entry_validates_before_any_device_call():
     assert L.rs_block_fwd_static(ctypes.byref(empty), ctypes.byref(w), None, None, None, None, None) == rs.RS_OK
 
 
+def test_grid_token_prune_rejects_bad_arguments():
+    L = rs.lib()
+
+    def call(fo=FAKE, fi=2 * FAKE, src=None, B=2, H=6, W=5, C=16, R=4, Q=3, dist=0, dt=rs.RS_BF16,
+             sc=3 * FAKE, kc=4 * FAKE, cs=5 * FAKE, kr=6 * FAKE, g=8 * FAKE):
+        return L.rs_grid_token_prune(fo, fi, src, B, H, W, C, R, Q, dist, dt, sc, kc, cs, kr, g, None)
+
+    assert call(C=20) == rs.RS_ERR_INVALID_ARG
+    assert call(R=7) == rs.RS_ERR_INVALID_ARG
+    assert call(Q=6) == rs.RS_ERR_INVALID_ARG
+    assert call(fo=None) == rs.RS_ERR_INVALID_ARG
+    assert call(sc=None) == rs.RS_ERR_INVALID_ARG
+    assert call(kc=None) == rs.RS_ERR_INVALID_ARG
+    assert call(cs=None) == rs.RS_ERR_INVALID_ARG
+    assert call(kr=None) == rs.RS_ERR_INVALID_ARG
+    assert call(g=FAKE) == rs.RS_ERR_INVALID_ARG           # gathered aliases src (= f_out)
+    assert call(dist=5) == rs.RS_ERR_INVALID_ARG
+    assert call(B=0, fo=None) == rs.RS_OK
+
+
 def test_pack_weights_validation():
     cfg = _cfg()
     # four bf16 matrices plus, for the two LayerNorms folded into W_qkv and W_fc1, an fp32 column-sum

@@ -589,6 +589,46 @@ def test_grid_line_prune(dtype, dist, B, H, W, C, R, Q):
     np.testing.assert_array_equal(to_host(g), oracle.grid_gather(src, kr_h, kc_h))
 
 
+@pytest.mark.parametrize("dtype", ["bf16", "f32"])
+@pytest.mark.parametrize("dist", [rs.RS_DIST_L2, rs.RS_DIST_L1])
+@pytest.mark.parametrize("B,H,W,C,R,Q", GRID_CASES + [(2, 300, 9, 16, 280, 9), (1, 6, 7, 8, 0, 3)])
+def test_grid_token_prune(dtype, dist, B, H, W, C, R, Q):
+    """Token-wise pruning of a grid (rows lose their lowest positions, then the compacted columns)."""
+    _say("grid token-wise", dtype, dist, B, H, W, C, R, Q)
+    f_in = host_round(si.generic(12, 1, (B, H, W, C)), dtype)
+    f_out = host_round(f_in + si.generic(12, 2, (B, H, W, C), std=0.3) * np.exp(si.generic(12, 3, (B, H, W, 1), std=0.7)), dtype)
+    src = host_round(si.generic(12, 4, (B, H, W, C)), dtype)
+    s_ref, kc_ref, cs_ref, kr_ref, g_ref = oracle.grid_token_prune(f_out, f_in, src, R, Q, dist)
+    d_out, d_in, d_src = (to_dev(t, dtype) for t in (f_out, f_in, src))
+    scores = torch.full((B, H, W), float("nan"), device="cuda", dtype=torch.float32)
+    kc = torch.full((B, H, Q), -1, device="cuda", dtype=torch.int32)
+    cs = torch.full((B, Q, H), float("nan"), device="cuda", dtype=torch.float32)
+    kr = torch.full((B, Q, R), -1, device="cuda", dtype=torch.int32)
+    g = torch.full((B, R, Q, C), float("nan"), device="cuda", dtype=d_in.dtype)
+    rs.rs_grid_token_prune(d_out, d_in, d_src, R, Q, scores, kc, cs, kr, g, dist=dist)
+    torch.cuda.synchronize()
+    s, kc_h, cs_h, kr_h = to_host(scores), kc.cpu().numpy(), to_host(cs), kr.cpu().numpy()
+    assert norm_err(s, s_ref) < 1e-5
+    # step 1: exact on the GPU's own scores, admissible against the checker's
+    np.testing.assert_array_equal(kc_h.reshape(B * H, Q), oracle.topk(s.reshape(B * H, W), 0, Q))
+    check_kept_admissible(kc_h.reshape(B * H, Q), s.reshape(B * H, W), s_ref.reshape(B * H, W), 0, Q)
+    if Q == 0 or R == 0:
+        return
+    # step 2 on the GPU's compacted grid: the scores are the selected ones, the selection is exact
+    want_cs = np.take_along_axis(s, kc_h.astype(np.int64), axis=2).transpose(0, 2, 1)
+    np.testing.assert_array_equal(cs_h, want_cs)
+    np.testing.assert_array_equal(kr_h.reshape(B * Q, R), oracle.topk(cs_h.reshape(B * Q, H), 0, R))
+    # gathered rows are copies of src at the selected positions
+    got = to_host(g)
+    for b in range(B):
+        for j in range(Q):
+            rows = kr_h[b, j]
+            np.testing.assert_array_equal(got[b, :, j], src[b, rows, kc_h[b, rows, j]].astype(np.float64))
+    # where both selections agree with the checker's, so does everything
+    if np.array_equal(kc_h, kc_ref) and np.array_equal(kr_h, kr_ref):
+        np.testing.assert_array_equal(got, g_ref)
+
+
 def test_batch_parts_on_streams_equal_the_whole_batch():
     """bench.py runs the batch as parts on separate HIP streams.  Images are independent and every
     kernel's arithmetic per row is the same whatever the batch size, so the parts must reproduce
