@@ -111,6 +111,28 @@ def attention(q, k, v, scale):
     return o
 
 
+def attention_map(q, k, v, scale):
+    """Standard (unfused) attention with the attention map written out, Sec. 3.1:
+    A = Softmax(Q K^T * scale) per image and head, O = A V.
+    q, k, v: [B, N, H, dh] -> (o [B, N, H, dh], A [B, H, N, N]).  numpy matmuls in fp64."""
+    q, k, v = _d(q), _d(k), _d(v)
+    S = np.einsum("bnhd,bmhd->bhnm", q, k) * float(scale)
+    S = S - S.max(axis=-1, keepdims=True)
+    P = np.exp(S)
+    A = P / P.sum(axis=-1, keepdims=True)
+    return np.einsum("bhnm,bmhd->bnhd", A, v), A
+
+
+def attention_scores(A, cls_index=0):
+    """Attention-based token importance from the map A [B, H, N, N] (Sec. 3.1):
+    Eq. (2): the class token's attention row, s_j = A[cls, j];
+    Eq. (3): the attentiveness summed over all queries, s_j = (1/N) sum_i A[i, j].
+    The paper writes both for one head; with H heads the mean over heads is taken.
+    Returns (s_cls [B, N], s_mean [B, N])."""
+    A = _d(A)
+    return A[:, :, cls_index, :].mean(axis=1), A.mean(axis=(1, 2))
+
+
 def shift_scores(f_out, f_in, dist=DIST_L2):
     """f_out, f_in: [..., D] -> scores [...]."""
     a, b = _d(f_out), _d(f_in)

@@ -541,3 +541,55 @@ def test_grid_token_prune_closed_forms():
     assert 9.0 in g[0, :, :, 0]
     s2, r2, c2, kr2, kc2, g2 = oracle.grid_line_prune(f_out, f_in, None, 3, 3)
     assert 9.0 not in g2[0, :, :, 0]
+
+
+# ----------------------------------------------------------------------------
+# materialised attention map and attention-based scores (Sec. 3.1, Eqs. (2), (3))
+# ----------------------------------------------------------------------------
+def test_attention_map_and_scores():
+    rng = np.random.default_rng(5)
+    B, N, H, dh = 2, 9, 3, 8
+    q, k, v = (rng.standard_normal((B, N, H, dh)) for _ in range(3))
+    o, A = oracle.attention_map(q, k, v, 0.3)
+    # the output is the fused definition's (the C routine, written independently of the numpy one)
+    np.testing.assert_allclose(o, oracle.attention(q, k, v, 0.3), rtol=1e-12, atol=1e-14)
+    np.testing.assert_allclose(A.sum(-1), 1.0, rtol=1e-13)
+    s_cls, s_mean = oracle.attention_scores(A, cls_index=0)
+    # each row of A is a distribution over keys, so both scores are distributions over tokens
+    np.testing.assert_allclose(s_cls.sum(-1), 1.0, rtol=1e-13)
+    np.testing.assert_allclose(s_mean.sum(-1), 1.0, rtol=1e-13)
+    # written out by hand for one token
+    b, j = 1, 4
+    want_cls = np.mean([A[b, h, 0, j] for h in range(H)])
+    want_mean = np.mean([A[b, h, i, j] for h in range(H) for i in range(N)])
+    assert abs(s_cls[b, j] - want_cls) < 1e-15 and abs(s_mean[b, j] - want_mean) < 1e-15
+    # another class-token position
+    s_cls3, _ = oracle.attention_scores(A, cls_index=3)
+    np.testing.assert_allclose(s_cls3, A[:, :, 3, :].mean(1), rtol=1e-15)
+
+
+def test_attention_scores_closed_forms():
+    B, N, H, dh = 1, 6, 2, 4
+    rng = np.random.default_rng(6)
+    q = rng.standard_normal((B, N, H, dh))
+    v = rng.standard_normal((B, N, H, dh))
+    # identical keys: uniform attention, every token scores 1/N under both definitions
+    k = np.broadcast_to(rng.standard_normal((B, 1, H, dh)), (B, N, H, dh)).copy()
+    _, A = oracle.attention_map(q, k, v, 0.5)
+    s_cls, s_mean = oracle.attention_scores(A)
+    np.testing.assert_allclose(s_cls, 1.0 / N, rtol=1e-12)
+    np.testing.assert_allclose(s_mean, 1.0 / N, rtol=1e-12)
+    # hand-worked two-key case: logits ln 1 and ln 3 for every query -> P = [1/4, 3/4]
+    q2 = np.zeros((1, 2, 1, 2)); q2[..., 0] = 1.0
+    k2 = np.zeros((1, 2, 1, 2)); k2[0, 0, 0, 0] = np.log(1.0); k2[0, 1, 0, 0] = np.log(3.0)
+    _, A2 = oracle.attention_map(q2, k2, np.ones((1, 2, 1, 2)), 1.0)
+    s_cls, s_mean = oracle.attention_scores(A2)
+    np.testing.assert_allclose(s_cls[0], [0.25, 0.75], rtol=1e-13)
+    np.testing.assert_allclose(s_mean[0], [0.25, 0.75], rtol=1e-13)
+    # one key that every query prefers by a wide margin takes (almost) all of both scores
+    k3 = rng.standard_normal((B, N, H, dh)) * 0.01
+    q3 = np.ones((B, N, H, dh))
+    k3[0, 2] = 50.0
+    _, A3 = oracle.attention_map(q3, k3, v, 1.0)
+    s_cls, s_mean = oracle.attention_scores(A3)
+    assert s_cls[0, 2] > 1 - 1e-9 and s_mean[0, 2] > 1 - 1e-9
