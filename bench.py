@@ -340,6 +340,29 @@ def main():
                                   "frac_mfma": round(4.0 * Bi * Hi * Ni * Ni * 64 / ti / 1e12 / PEAK_BF16_TFLOPS, 4)}
         del qkv, oa
 
+    if not a.no_extras:
+        # ---- context: standard attention with the map written out (rs_attention_map_fwd) against the fused kernel,
+        # and the cost of the attention-based scores against the representation-shift score of the block ----
+        cmp_ = {}
+        for tag, (Bc, Nc, Hc) in {"image_256x197x12": (256, 197, 12), "video_8x1569x12": (8, 1569, 12)}.items():
+            qkv = torch.randn((Bc, Nc, 3, Hc, 64), device=dev, dtype=tdt)
+            oa = torch.empty((Bc, Nc, Hc, 64), device=dev, dtype=tdt)
+            amap = torch.empty(rs.rs_attention_map_size(Bc, Hc, Nc), dtype=torch.uint8, device=dev)
+            wsa = torch.empty(rs.rs_attention_map_workspace_size(Bc, Hc, Nc), dtype=torch.uint8, device=dev)
+            sm = torch.empty((Bc, Nc), device=dev, dtype=torch.float32)
+            t_f = time_steps(torch, lambda: rs.rs_attention_fwd(qkv[:, :, 0], qkv[:, :, 1], qkv[:, :, 2], oa, 0.125), 10, 2)
+            t_u = time_steps(torch, lambda: rs.rs_attention_map_fwd(qkv[:, :, 0], qkv[:, :, 1], qkv[:, :, 2], oa, 0.125,
+                                                                    amap, None, None, wsa), 10, 2)
+            t_s = time_steps(torch, lambda: rs.rs_attention_map_fwd(qkv[:, :, 0], qkv[:, :, 1], qkv[:, :, 2], oa, 0.125,
+                                                                    amap, sm, sm, wsa), 10, 2)
+            cmp_[tag] = {"fused_us": round(t_f * 1e6, 1), "map_written_us": round(t_u * 1e6, 1),
+                         "map_written_with_scores_us": round(t_s * 1e6, 1), "fused_speedup": round(t_u / t_f, 2),
+                         "map_MB": round(amap.numel() / 1e6, 1)}
+            del qkv, oa, amap, wsa
+        out["attention_fused_vs_map_written"] = dict(cmp_, note="context only (Sec. 3.1, Table 1): the comparison system "
+                                                     "with Eq. (2)/(3) scores; the representation-shift score costs no pass "
+                                                     "of its own (it falls out of the fc2 epilogue)")
+
     if a.calib_copy_mb:
         src_c = torch.empty(a.calib_copy_mb << 20, dtype=torch.uint8, device=dev).fill_(1)
         dst_c = torch.empty_like(src_c)

@@ -151,6 +151,33 @@ RS_API rs_status rs_attention_fwd(const void *q, const void *k, const void *v, v
                            float scale, rs_dtype dtype, void *hip_stream);
 
 /*
+ * Standard (unfused) attention with the attention map written to memory, and the attention-based
+ * token importance that needs it (Sec. 3.1, Eqs. (2), (3); the "Self-Attention" row of Table 1).
+ * This is the comparison system the method is measured against, kept out of the hot path: the
+ * fused call above never has the map.
+ *     A = Softmax(Q K^T * scale)            per image and head, written to attn_map
+ *     O = A V
+ *     s_cls[b, j]  = mean over heads of A[b, h, cls_index, j]                  Eq. (2)
+ *     s_mean[b, j] = mean over heads of (1/N) sum_i A[b, h, i, j]              Eq. (3)
+ *   (the paper writes both scores for one head; with H heads the mean over heads is taken)
+ *   q, k, v, o, strides, dh, scale : as in rs_attention_fwd.   dtype : RS_BF16 only.
+ *   attn_map : bf16 [B, H, N, Np] out, Np = N rounded up to a multiple of 64 (columns past N are
+ *              zero), rs_attention_map_size bytes.
+ *   s_cls, s_mean : float [B, N] out, either may be NULL.    cls_index in [0, N).
+ *   workspace : rs_attention_map_workspace_size bytes, 256-byte aligned (packed heads, column sums).
+ *   B * H <= 65535.  Deterministic.
+ */
+RS_API size_t rs_attention_map_size(int32_t B, int32_t H, int32_t N);
+RS_API size_t rs_attention_map_workspace_size(int32_t B, int32_t H, int32_t N);
+RS_API rs_status rs_attention_map_fwd(const void *q, const void *k, const void *v, void *o,
+                               int32_t B, int32_t H, int32_t N, int32_t dh,
+                               int64_t stride_b, int64_t stride_n, int64_t stride_h,
+                               int64_t o_stride_b, int64_t o_stride_n, int64_t o_stride_h,
+                               float scale, rs_dtype dtype, int32_t cls_index,
+                               void *attn_map, float *s_cls, float *s_mean,
+                               void *workspace, size_t workspace_bytes, void *hip_stream);
+
+/*
  * Representation shift score, selection and compaction (Eq. (4) of Sec. 3.2;
  * pruning of the lowest-score tokens, Secs. 3.1 and 3.2):
  *     scores[b, i] = D(f_out[b, i, :], f_in[b, i, :])

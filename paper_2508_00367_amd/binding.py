@@ -23,7 +23,8 @@ RS_PROFILE_CLASSES = 11
 RS_EPI_BIAS, RS_EPI_BIAS_GELU, RS_EPI_BIAS_RES = 0, 1, 2
 
 EXPORTS = ("rs_last_error", "rs_version", "rs_build_info", "rs_tune_gemm_variant", "rs_profile_enable", "rs_profile_read",
-           "rs_profile_class_name", "rs_attention_fwd", "rs_shift_topk_workspace_size",
+           "rs_profile_class_name", "rs_attention_fwd", "rs_attention_map_size",
+           "rs_attention_map_workspace_size", "rs_attention_map_fwd", "rs_shift_topk_workspace_size",
            "rs_shift_topk", "rs_grid_line_prune", "rs_grid_token_prune", "rs_pack_linear", "rs_linear_fwd", "rs_packed_weights_size", "rs_pack_weights", "rs_block_workspace_size",
            "rs_block_fwd", "rs_block_static_scratch_size", "rs_block_fwd_static")
 
@@ -75,6 +76,13 @@ def lib():
         L.rs_attention_fwd.argtypes = [_vp, _vp, _vp, _vp, _i32, _i32, _i32, _i32] + [_i64] * 6 + \
             [ctypes.c_float, ctypes.c_int, _vp]
         L.rs_attention_fwd.restype = ctypes.c_int
+        L.rs_attention_map_size.argtypes = [_i32, _i32, _i32]
+        L.rs_attention_map_size.restype = ctypes.c_size_t
+        L.rs_attention_map_workspace_size.argtypes = [_i32, _i32, _i32]
+        L.rs_attention_map_workspace_size.restype = ctypes.c_size_t
+        L.rs_attention_map_fwd.argtypes = [_vp, _vp, _vp, _vp, _i32, _i32, _i32, _i32] + [_i64] * 6 + \
+            [ctypes.c_float, ctypes.c_int, _i32, _vp, _vp, _vp, _vp, ctypes.c_size_t, _vp]
+        L.rs_attention_map_fwd.restype = ctypes.c_int
         L.rs_shift_topk_workspace_size.argtypes = [_i32, _i32, _i32, ctypes.c_int]
         L.rs_shift_topk_workspace_size.restype = ctypes.c_size_t
         L.rs_shift_topk.argtypes = [_vp, _vp, _vp, _i32, _i32, _i32, _i32, _i32, ctypes.c_int,
@@ -187,6 +195,26 @@ def rs_attention_fwd(q, k, v, o, scale, stream=None) -> None:
                                   q.stride(0), q.stride(1), q.stride(2),
                                   o.stride(0), o.stride(1), o.stride(2),
                                   float(scale), dtype_code(q.dtype), _stream(stream)))
+
+
+def rs_attention_map_size(B, H, N) -> int:
+    return int(lib().rs_attention_map_size(B, H, N))
+
+
+def rs_attention_map_workspace_size(B, H, N) -> int:
+    return int(lib().rs_attention_map_workspace_size(B, H, N))
+
+
+def rs_attention_map_fwd(q, k, v, o, scale, attn_map, s_cls, s_mean, workspace, cls_index=0, stream=None) -> None:
+    """Standard attention with the map written out: q, k, v, o as in rs_attention_fwd; attn_map bf16
+    [B, H, N, Np]; s_cls / s_mean float [B, N] or None."""
+    B, N, H, dh = q.shape
+    assert q.stride() == k.stride() == v.stride() and q.stride(3) == 1 and o.stride(3) == 1
+    ws_bytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
+    _check(lib().rs_attention_map_fwd(_ptr(q), _ptr(k), _ptr(v), _ptr(o), B, H, N, dh,
+                                      q.stride(0), q.stride(1), q.stride(2), o.stride(0), o.stride(1), o.stride(2),
+                                      float(scale), dtype_code(q.dtype), cls_index, _ptr(attn_map), _ptr(s_cls),
+                                      _ptr(s_mean), _ptr(workspace), ws_bytes, _stream(stream)))
 
 
 def rs_shift_topk_workspace_size(B, N, D, dtype) -> int:

@@ -629,3 +629,164 @@ hipError_t launch_attention(rs_dtype dt, const void* q, const void* k, const voi
 }
 
 }  // namespace rs
+
+// ---------------------------------------------------------------------------
+// Standard (unfused) attention, the comparison system of Sec. 3.1 / Table 1: the attention map
+// A = Softmax(Q K^T * scale) is written to memory, which is what the attention-based importance
+// scores of Eqs. (2), (3) need and what the fused kernels above avoid.  Steps: pack the heads
+// (q, k as [B H, Np, 64] with zero rows up to Np = N rounded up to 64, v transposed to
+// [B H, 64, Np]); S = Q K^T as a batched matrix-core GEMM; softmax over every row in place;
+// O = A V as a second batched GEMM; rows back to the caller's layout; column sums of the map.
+// ---------------------------------------------------------------------------
+namespace rs {
+
+// one workgroup per (image * head, 64-token tile)
+__global__ __launch_bounds__(256) void attn_pack_kernel(const bf16raw* __restrict__ q, const bf16raw* __restrict__ k,
+                                                        const bf16raw* __restrict__ v, bf16raw* __restrict__ qh,
+                                                        bf16raw* __restrict__ kh, bf16raw* __restrict__ vt, int H, int N,
+                                                        int Np, int64_t sb, int64_t sn, int64_t sh) {
+    __shared__ bf16raw tile[64][72];  // v rows of this tile, padded against bank conflicts
+    const int bh = blockIdx.y, b = bh / H, h = bh - b * H;
+    const int n0 = blockIdx.x * 64;
+    const int64_t base = (int64_t)b * sb + (int64_t)h * sh;
+    // 64 rows x 8 chunks of 16 bytes: two chunks per thread
+    for (int t = threadIdx.x; t < 512; t += 256) {
+        const int r = t >> 3, c = (t & 7) * 8;
+        const int n = n0 + r;
+        uint4 zq = make_uint4(0u, 0u, 0u, 0u), zk = zq, zv = zq;
+        if (n < N) {
+            zq = *reinterpret_cast<const uint4*>(q + base + (int64_t)n * sn + c);
+            zk = *reinterpret_cast<const uint4*>(k + base + (int64_t)n * sn + c);
+            zv = *reinterpret_cast<const uint4*>(v + base + (int64_t)n * sn + c);
+        }
+        *reinterpret_cast<uint4*>(qh + ((int64_t)bh * Np + n) * 64 + c) = zq;
+        *reinterpret_cast<uint4*>(kh + ((int64_t)bh * Np + n) * 64 + c) = zk;
+        *reinterpret_cast<uint4*>(&tile[r][c]) = zv;
+    }
+    __syncthreads();
+    // vt[bh][d][n0 + r]: thread (d, r-chunk of 8)
+    for (int t = threadIdx.x; t < 512; t += 256) {
+        const int d = t >> 3, r0 = (t & 7) * 8;
+        union { bf16raw e[8]; uint4 u; } w;
+#pragma unroll
+        for (int i = 0; i < 8; ++i) w.e[i] = tile[r0 + i][d];
+        *reinterpret_cast<uint4*>(vt + ((int64_t)bh * 64 + d) * Np + n0 + r0) = w.u;
+    }
+}
+
+hipError_t launch_attn_pack(const void* q, const void* k, const void* v, void* qh, void* kh, void* vt, int B, int H,
+                            int N, int Np, int64_t sb, int64_t sn, int64_t sh, hipStream_t s) {
+    hipLaunchKernelGGL(attn_pack_kernel, dim3(Np / 64, B * H), dim3(256), 0, s, (const bf16raw*)q, (const bf16raw*)k,
+                       (const bf16raw*)v, (bf16raw*)qh, (bf16raw*)kh, (bf16raw*)vt, H, N, Np, sb, sn, sh);
+    return hipGetLastError();
+}
+
+// one wavefront per row of the [rows, Np] score matrices: three passes over the row (maximum, sum,
+// normalised write), the columns past N become zero
+__global__ __launch_bounds__(256) void attn_softmax_rows_kernel(bf16raw* __restrict__ map, int64_t rows, int N, int Np,
+                                                                float scale_log2e) {
+    const int lane = threadIdx.x & 63;
+    const int64_t row = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
+    if (row >= rows) return;
+    bf16raw* p = map + row * Np;
+    float mx = -INFINITY;
+    for (int c = lane * 8; c < Np; c += 512) {
+        float x[8];
+        Elem<bf16raw>::load8(p + c, x);
+#pragma unroll
+        for (int i = 0; i < 8; ++i)
+            if (c + i < N) mx = fmaxf(mx, x[i]);
+    }
+#pragma unroll
+    for (int off = 32; off >= 1; off >>= 1) mx = fmaxf(mx, __shfl_xor(mx, off, 64));
+    const float mb = mx * scale_log2e;
+    float sum = 0.f;
+    for (int c = lane * 8; c < Np; c += 512) {
+        float x[8];
+        Elem<bf16raw>::load8(p + c, x);
+#pragma unroll
+        for (int i = 0; i < 8; ++i)
+            if (c + i < N) sum += __builtin_amdgcn_exp2f(fmaf(x[i], scale_log2e, -mb));
+    }
+    sum = wave_sum(sum);
+    const float inv = 1.0f / sum;
+    for (int c = lane * 8; c < Np; c += 512) {
+        float x[8];
+        Elem<bf16raw>::load8(p + c, x);
+#pragma unroll
+        for (int i = 0; i < 8; ++i) x[i] = c + i < N ? __builtin_amdgcn_exp2f(fmaf(x[i], scale_log2e, -mb)) * inv : 0.f;
+        Elem<bf16raw>::store8(p + c, x);
+    }
+}
+
+hipError_t launch_attn_softmax_rows(void* map, int64_t rows, int N, int Np, float scale_log2e, hipStream_t s) {
+    if (rows == 0) return hipSuccess;
+    hipLaunchKernelGGL(attn_softmax_rows_kernel, dim3((unsigned)((rows + 3) / 4)), dim3(256), 0, s, (bf16raw*)map, rows,
+                       N, Np, scale_log2e);
+    return hipGetLastError();
+}
+
+// partial[bh][j] = sum_i A[bh][i][j]  (thread j walks the rows in order: fixed order, coalesced)
+__global__ __launch_bounds__(256) void attn_colsum_kernel(const bf16raw* __restrict__ map, float* __restrict__ partial,
+                                                          int N, int Np) {
+    const int j = blockIdx.x * 256 + threadIdx.x;
+    const int bh = blockIdx.y;
+    if (j >= N) return;
+    const bf16raw* p = map + (int64_t)bh * N * Np + j;
+    float acc = 0.f;
+    for (int i = 0; i < N; ++i) acc += bf2f(p[(int64_t)i * Np]);
+    partial[(int64_t)bh * N + j] = acc;
+}
+
+// Eq. (2): s_cls[b][j] = mean_h A[b,h,cls,j];  Eq. (3): s_mean[b][j] = mean_h (1/N) sum_i A[b,h,i,j]
+__global__ __launch_bounds__(256) void attn_scores_kernel(const bf16raw* __restrict__ map, const float* __restrict__ partial,
+                                                          float* __restrict__ s_cls, float* __restrict__ s_mean, int H,
+                                                          int N, int Np, int cls_index) {
+    const int j = blockIdx.x * 256 + threadIdx.x;
+    const int b = blockIdx.y;
+    if (j >= N) return;
+    float c = 0.f, m = 0.f;
+    for (int h = 0; h < H; ++h) {
+        const int64_t bh = (int64_t)b * H + h;
+        c += bf2f(map[(bh * N + cls_index) * Np + j]);
+        m += partial[bh * N + j];
+    }
+    if (s_cls) s_cls[(int64_t)b * N + j] = c / (float)H;
+    if (s_mean) s_mean[(int64_t)b * N + j] = m / ((float)H * (float)N);
+}
+
+hipError_t launch_attn_map_scores(const void* map, float* partial, float* s_cls, float* s_mean, int B, int H, int N,
+                                  int Np, int cls_index, hipStream_t s) {
+    if (!s_cls && !s_mean) return hipSuccess;
+    if (s_mean)
+        hipLaunchKernelGGL(attn_colsum_kernel, dim3((N + 255) / 256, B * H), dim3(256), 0, s, (const bf16raw*)map, partial, N, Np);
+    hipLaunchKernelGGL(attn_scores_kernel, dim3((N + 255) / 256, B), dim3(256), 0, s, (const bf16raw*)map, partial,
+                       s_cls, s_mean, H, N, Np, cls_index);
+    return hipGetLastError();
+}
+
+// o[b, n, h, :] = oh[b h][n][:]; 8 lanes per 128-byte row
+__global__ __launch_bounds__(256) void attn_unpack_kernel(const bf16raw* __restrict__ oh, bf16raw* __restrict__ o, int H,
+                                                          int N, int64_t rows, int64_t osb, int64_t osn, int64_t osh) {
+    const int64_t t = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    const int64_t r = t >> 3;  // row index into [B H, N]
+    if (r >= rows) return;
+    const int c = (int)(t & 7) * 8;
+    const int64_t bh = r / N;
+    const int n = (int)(r - bh * N);
+    const int64_t b = bh / H;
+    const int h = (int)(bh - b * H);
+    *reinterpret_cast<uint4*>(o + b * osb + (int64_t)n * osn + (int64_t)h * osh + c) =
+        *reinterpret_cast<const uint4*>(oh + r * 64 + c);
+}
+
+hipError_t launch_attn_unpack(const void* oh, void* o, int B, int H, int N, int64_t osb, int64_t osn, int64_t osh,
+                              hipStream_t s) {
+    const int64_t rows = (int64_t)B * H * N;
+    if (rows == 0) return hipSuccess;
+    hipLaunchKernelGGL(attn_unpack_kernel, dim3((unsigned)((rows * 8 + 255) / 256)), dim3(256), 0, s, (const bf16raw*)oh,
+                       (bf16raw*)o, H, N, rows, osb, osn, osh);
+    return hipGetLastError();
+}
+
+}  // namespace rs

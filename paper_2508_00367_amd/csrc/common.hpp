@@ -141,6 +141,22 @@ hipError_t launch_gemm(rs_dtype dt, GemmEpilogue epi, rs_dist dist, const void* 
 hipError_t launch_gemm_ln(GemmEpilogue epi, const void* x, const void* w_folded, GemmLnFold ln, void* out,
                           int64_t M, int N, int K, hipStream_t s);
 
+// `count` independent bf16 products out_p[M, N] = a_p[M, K] @ wt_p[N, K]^T, problem p at element offset
+// p * stride from each base pointer (K % 32 == 0, N % 64 == 0; rows of wt_p past N must exist as zeros)
+hipError_t launch_gemm_batched(const void* a, const void* wt, void* out, int count, int64_t stride_a,
+                               int64_t stride_w, int64_t stride_out, int M, int N, int K, hipStream_t s);
+
+// Standard (unfused) attention with the map written to memory, the comparison system of Sec. 3.1:
+// pack q, k (zero-padded to Np rows) and v^T per head; softmax rows of the [N, Np] score matrices in
+// place; column sums of the map; output rows back to the caller's layout.
+hipError_t launch_attn_pack(const void* q, const void* k, const void* v, void* qh, void* kh, void* vt, int B, int H,
+                            int N, int Np, int64_t sb, int64_t sn, int64_t sh, hipStream_t s);
+hipError_t launch_attn_softmax_rows(void* map, int64_t rows, int N, int Np, float scale_log2e, hipStream_t s);
+hipError_t launch_attn_map_scores(const void* map, float* partial, float* s_cls, float* s_mean, int B, int H, int N,
+                                  int Np, int cls_index, hipStream_t s);
+hipError_t launch_attn_unpack(const void* oh, void* o, int B, int H, int N, int64_t osb, int64_t osn, int64_t osh,
+                              hipStream_t s);
+
 // bf16 [K, N] row-major -> [N, K] row-major; with `gamma` ([K] bf16) row k is scaled by gamma[k]
 // (product rounded to bf16).
 hipError_t launch_pack_transpose(const void* w, const void* gamma, void* wt, int K, int N, hipStream_t s);

@@ -56,6 +56,11 @@ __device__ __forceinline__ void shift_term(float fo, float fi, float& p0, float&
     else { p0 = fmaf(fo, fi, p0); p1 = fmaf(fo, fo, p1); p2 = fmaf(fi, fi, p2); }
 }
 
+// element strides between the problems of a batched launch (0 = one problem)
+struct GemmBatch {
+    int64_t a, w, out;
+};
+
 template <int TN, int TM>
 struct Frags {
     bf16x8 w[TN], a[TM];
@@ -646,11 +651,15 @@ __global__ __launch_bounds__(256, 2) void gemm_bf16_ring_kernel(
     const bf16raw* __restrict__ a, const bf16raw* __restrict__ wt, const bf16raw* __restrict__ bias,
     const bf16raw* __restrict__ res, bf16raw* __restrict__ out, float* __restrict__ partials,
     const bf16raw* __restrict__ ref, int post, GemmLnFold ln, int M, int N, int K, int tiles_m,
-    int tiles_n, int slots, int gm) {
+    int tiles_n, int slots, int gm, GemmBatch batch) {
     constexpr int NW = WGM * WGN;
     constexpr int WM = BM / WGM, WN = BN / WGN;
     constexpr int TM = WM / 32, TN = WN / 32;
     constexpr int BK = 32, RB = BK * 2, RPI = 16;   // 64-byte LDS rows, 16 rows per wave copy
+    // batched use (blockIdx.y = problem): the same shape at other addresses, plain epilogues only
+    a += (int64_t)blockIdx.y * batch.a;
+    wt += (int64_t)blockIdx.y * batch.w;
+    out += (int64_t)blockIdx.y * batch.out;
     constexpr int A_LOADS = BM / RPI / NW, W_LOADS = BN / RPI / NW, LPW = A_LOADS + W_LOADS;
     constexpr int STAGE = (BM + BN) * RB;
     static_assert(NW == 4 && WN == 64 && TN == 2, "four waves, wave tiles 64 features wide");
@@ -864,7 +873,7 @@ static void launch_ring(const GemmArgs& g, hipStream_t s) {
     constexpr int WGN = BN / 64, WGM = 4 / WGN;  // four waves, each 64 features wide
     hipLaunchKernelGGL((gemm_bf16_ring_kernel<BM, BN, WGM, WGN, EPI, DIST>), dim3(8 * ((nblk + 7) / 8)), dim3(256), 0, s,
                        g.a, g.wt, g.bias, g.res, g.out, g.partials, g.ref, g.post, g.ln, (int)g.M, g.N, g.K, tiles_m,
-                       tiles_n, (g.N + 63) / 64, RS_GEMM_GM);
+                       tiles_n, (g.N + 63) / 64, RS_GEMM_GM, GemmBatch{0, 0, 0});
 }
 
 // the ring kernel with the tile height that fills the chip's 2 x CUs workgroup slots
@@ -1060,6 +1069,29 @@ const char* gemm_build_info() {
     return "bf16 gemm: persistent tiles (BM,BN,BK,stages,waves m,waves n) " RS_STR(RS_GEMM_CFG)
            "; ring tiles 256x128x32 and 128x128x32, 3 stages, 2x2 waves, 2 workgroups per CU"
            "; rows behind whole rounds go to a ring kernel when K >= " RS_STR(RS_GEMM_TAIL_MINK) " and the last round is under " RS_STR(RS_GEMM_TAIL_FRAC) " full";
+}
+
+// `count` independent products out_p[M, N] = a_p[M, K] @ wt_p[N, K]^T (bf16, no bias), problem p at
+// element offsets p * stride from the base pointers; 128 x 128 tiles, grid.y = problem.
+hipError_t launch_gemm_batched(const void* a, const void* wt, void* out, int count, int64_t stride_a,
+                               int64_t stride_w, int64_t stride_out, int M, int N, int K, hipStream_t s) {
+    if (count == 0 || M == 0) return hipSuccess;
+    const GemmBatch gb{stride_a, stride_w, stride_out};
+    if (N <= 64) {  // one 64-wide wave column: 256 x 64 tiles, four waves along the rows
+        const int tiles_m = (M + 255) / 256;
+        hipLaunchKernelGGL((gemm_bf16_ring_kernel<256, 64, 4, 1, EPI_BIAS, 0>), dim3(8 * ((tiles_m + 7) / 8), count), dim3(256), 0, s,
+                           (const bf16raw*)a, (const bf16raw*)wt, (const bf16raw*)nullptr, (const bf16raw*)nullptr,
+                           (bf16raw*)out, (float*)nullptr, (const bf16raw*)nullptr, 0, GemmLnFold{}, M, N, K, tiles_m, 1,
+                           1, RS_GEMM_GM, gb);
+    } else {
+        const int tiles_m = (M + 127) / 128, tiles_n = (N + 127) / 128;
+        const int nblk = tiles_m * tiles_n;
+        hipLaunchKernelGGL((gemm_bf16_ring_kernel<128, 128, 2, 2, EPI_BIAS, 0>), dim3(8 * ((nblk + 7) / 8), count), dim3(256), 0, s,
+                           (const bf16raw*)a, (const bf16raw*)wt, (const bf16raw*)nullptr, (const bf16raw*)nullptr,
+                           (bf16raw*)out, (float*)nullptr, (const bf16raw*)nullptr, 0, GemmLnFold{}, M, N, K, tiles_m,
+                           tiles_n, (N + 63) / 64, RS_GEMM_GM, gb);
+    }
+    return hipGetLastError();
 }
 
 int gemm_shift_slots(rs_dtype dt, int N) {

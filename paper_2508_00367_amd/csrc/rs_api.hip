@@ -289,6 +289,81 @@ rs_status rs_attention_fwd(const void* q, const void* k, const void* v, void* o,
     return RS_OK;
 }
 
+// workspace of rs_attention_map_fwd: packed q, k [B H, Np, 64], v^T [B H, 64, Np], o [B H, N, 64], column sums
+struct AttnMapLayout {
+    size_t qh, kh, vt, oh, partial, total;
+    int Np;
+};
+
+static AttnMapLayout attn_map_layout(int64_t B, int64_t H, int64_t N) {
+    AttnMapLayout L;
+    L.Np = (int)((N + 63) / 64 * 64);
+    size_t off = 0;
+    auto take = [&](size_t bytes) { size_t o = off; off += align_up(bytes, 256); return o; };
+    const size_t BH = (size_t)(B * H);
+    L.qh = take(BH * L.Np * 64 * 2);
+    L.kh = take(BH * L.Np * 64 * 2);
+    L.vt = take(BH * 64 * L.Np * 2);
+    L.oh = take(BH * N * 64 * 2);
+    L.partial = take(BH * N * sizeof(float));
+    L.total = off;
+    return L;
+}
+
+size_t rs_attention_map_workspace_size(int32_t B, int32_t H, int32_t N) {
+    if (B <= 0 || H <= 0 || N <= 0) return 0;
+    return attn_map_layout(B, H, N).total;
+}
+
+size_t rs_attention_map_size(int32_t B, int32_t H, int32_t N) {
+    if (B <= 0 || H <= 0 || N <= 0) return 0;
+    return (size_t)B * H * N * ((N + 63) / 64 * 64) * 2;
+}
+
+rs_status rs_attention_map_fwd(const void* q, const void* k, const void* v, void* o, int32_t B, int32_t H, int32_t N,
+                               int32_t dh, int64_t stride_b, int64_t stride_n, int64_t stride_h, int64_t o_stride_b,
+                               int64_t o_stride_n, int64_t o_stride_h, float scale, rs_dtype dtype, int32_t cls_index,
+                               void* attn_map, float* s_cls, float* s_mean, void* workspace, size_t workspace_bytes,
+                               void* hip_stream) {
+    RS_REQUIRE(dtype == RS_F32 || dtype == RS_BF16, RS_ERR_INVALID_ARG, "unknown dtype %d", (int)dtype);
+    RS_REQUIRE(dtype == RS_BF16, RS_ERR_UNSUPPORTED, "the materialised-map attention is built for bf16 only");
+    RS_REQUIRE(B >= 0 && H >= 0 && N >= 0, RS_ERR_INVALID_ARG, "negative B, H or N");
+    RS_REQUIRE(dh > 0, RS_ERR_INVALID_ARG, "dh must be positive");
+    RS_REQUIRE(dh == 64, RS_ERR_UNSUPPORTED, "head width %d, only 64 is built", dh);
+    RS_REQUIRE((int64_t)B * H <= 65535, RS_ERR_UNSUPPORTED, "B * H is limited to 65535");
+    RS_REQUIRE(N <= (1 << 20), RS_ERR_UNSUPPORTED, "N is limited to 2^20");
+    RS_REQUIRE(scale > 0.f && scale < INFINITY, RS_ERR_INVALID_ARG, "scale must be positive and finite");
+    if (B == 0 || H == 0 || N == 0) return RS_OK;
+    RS_REQUIRE(cls_index >= 0 && cls_index < N, RS_ERR_INVALID_ARG, "cls_index %d outside [0, N)", (int)cls_index);
+    RS_REQUIRE(q && k && v && o && attn_map, RS_ERR_INVALID_ARG, "q, k, v, o and attn_map must not be NULL");
+    RS_REQUIRE(aligned16(q) && aligned16(k) && aligned16(v) && aligned16(o) && aligned16(attn_map), RS_ERR_INVALID_ARG,
+               "q, k, v, o and attn_map must be 16-byte aligned");
+    RS_REQUIRE(o != q && o != k && o != v, RS_ERR_INVALID_ARG, "o must not alias q, k or v");
+    const int64_t st6[6] = {stride_b, stride_n, stride_h, o_stride_b, o_stride_n, o_stride_h};
+    for (int i = 0; i < 6; ++i)
+        RS_REQUIRE(st6[i] >= 0 && st6[i] % 8 == 0, RS_ERR_INVALID_ARG, "strides must be non-negative multiples of 8 elements");
+    RS_REQUIRE(stride_n >= dh && o_stride_n >= dh, RS_ERR_INVALID_ARG, "token stride smaller than dh");
+    const AttnMapLayout L = attn_map_layout(B, H, N);
+    RS_REQUIRE(workspace_bytes >= L.total, RS_ERR_WORKSPACE_TOO_SMALL,
+               "workspace has %zu bytes, rs_attention_map_workspace_size needs %zu", workspace_bytes, L.total);
+    RS_REQUIRE(workspace != nullptr && (reinterpret_cast<uintptr_t>(workspace) & 255u) == 0, RS_ERR_INVALID_ARG,
+               "workspace must be a 256-byte aligned buffer");
+    hipStream_t s = (hipStream_t)hip_stream;
+    char* ws = (char*)workspace;
+    const int BH = B * H, Np = L.Np;
+    RS_LAUNCH_K(K_ATTN, s, launch_attn_pack(q, k, v, ws + L.qh, ws + L.kh, ws + L.vt, B, H, N, Np, stride_b, stride_n, stride_h, s));
+    // S = Q K^T per head, written out; then the row softmax in place: the map
+    RS_LAUNCH_K(K_ATTN, s, launch_gemm_batched(ws + L.qh, ws + L.kh, attn_map, BH, (int64_t)Np * 64, (int64_t)Np * 64,
+                                             (int64_t)N * Np, N, Np, 64, s));
+    RS_LAUNCH_K(K_ATTN, s, launch_attn_softmax_rows(attn_map, (int64_t)BH * N, N, Np, scale * 1.44269504088896340736f, s));
+    // O = A V per head
+    RS_LAUNCH_K(K_ATTN, s, launch_gemm_batched(attn_map, ws + L.vt, ws + L.oh, BH, (int64_t)N * Np, (int64_t)64 * Np,
+                                             (int64_t)N * 64, N, 64, Np, s));
+    RS_LAUNCH_K(K_ATTN, s, launch_attn_unpack(ws + L.oh, o, B, H, N, o_stride_b, o_stride_n, o_stride_h, s));
+    RS_LAUNCH_K(K_SCORE, s, launch_attn_map_scores(attn_map, (float*)(ws + L.partial), s_cls, s_mean, B, H, N, Np, cls_index, s));
+    return RS_OK;
+}
+
 size_t rs_shift_topk_workspace_size(int32_t B, int32_t N, int32_t D, rs_dtype dtype) {
     (void)B; (void)N; (void)D; (void)dtype;
     return 0;

@@ -130,6 +130,29 @@ def test_attention_rejects_bad_arguments():
     assert "stride" in rs.rs_last_error() or rs.rs_last_error() != ""
 
 
+def test_attention_map_rejects_bad_arguments():
+    L = rs.lib()
+    need = rs.rs_attention_map_workspace_size(1, 2, 70)
+    assert need > 0 and rs.rs_attention_map_size(1, 2, 70) == 1 * 2 * 70 * 128 * 2
+
+    def call(q=FAKE, k=2 * FAKE, v=3 * FAKE, o=4 * FAKE, B=1, H=2, N=70, dh=64, sn=128, scale=0.125, dt=rs.RS_BF16,
+             cls=0, amap=5 * FAKE, ws=16 * FAKE, wsb=None):
+        return L.rs_attention_map_fwd(q, k, v, o, B, H, N, dh, N * sn, sn, 64, N * sn, sn, 64, scale, dt, cls, amap,
+                                      None, None, ws, need if wsb is None else wsb, None)
+
+    assert call(dt=rs.RS_F32) == rs.RS_ERR_UNSUPPORTED
+    assert call(dh=32) == rs.RS_ERR_UNSUPPORTED
+    assert call(B=300, H=300) == rs.RS_ERR_UNSUPPORTED       # B * H beyond one grid axis
+    assert call(cls=70) == rs.RS_ERR_INVALID_ARG
+    assert call(amap=None) == rs.RS_ERR_INVALID_ARG
+    assert call(o=FAKE) == rs.RS_ERR_INVALID_ARG
+    assert call(sn=60) == rs.RS_ERR_INVALID_ARG
+    assert call(scale=-1.0) == rs.RS_ERR_INVALID_ARG
+    assert call(wsb=need - 1) == rs.RS_ERR_WORKSPACE_TOO_SMALL
+    assert call(ws=None) == rs.RS_ERR_INVALID_ARG
+    assert call(N=0, q=None) == rs.RS_OK
+
+
 def test_shift_topk_rejects_bad_arguments():
     L = rs.lib()
 

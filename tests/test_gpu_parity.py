@@ -163,6 +163,42 @@ def test_block_with_poisoned_workspace(N):
     assert norm_err(to_host(y), oracle.gather(ref["xhat"], kept_h)) < TOL["bf16"]
 
 
+@pytest.mark.parametrize("B,N,H,cls", [(2, 17, 3, 0), (1, 64, 2, 5), (2, 197, 3, 0), (1, 300, 2, 299), (1, 1060, 1, 0)])
+def test_attention_map_and_attention_scores(B, N, H, cls):
+    """The comparison system of Sec. 3.1: attention with the map written to memory, and the
+    importance scores of Eqs. (2), (3) taken from it, against the checker; its output must also
+    agree with the fused kernel's."""
+    _say("attention map", B, N, H, cls)
+    qkv = host_round(si.generic(15, 1, (B, N, 3, H, 64)), "bf16")
+    o_ref, A_ref = oracle.attention_map(qkv[:, :, 0], qkv[:, :, 1], qkv[:, :, 2], 0.125)
+    s_cls_ref, s_mean_ref = oracle.attention_scores(A_ref, cls)
+    d = to_dev(qkv, "bf16")
+    Np = (N + 63) // 64 * 64
+    o = torch.full((B, N, H, 64), float("nan"), device="cuda", dtype=torch.bfloat16)
+    amap = torch.full((B, H, N, Np), float("nan"), device="cuda", dtype=torch.bfloat16)
+    assert amap.numel() * 2 == rs.rs_attention_map_size(B, H, N)
+    s_cls = torch.full((B, N), float("nan"), device="cuda", dtype=torch.float32)
+    s_mean = torch.full((B, N), float("nan"), device="cuda", dtype=torch.float32)
+    ws = torch.full((rs.rs_attention_map_workspace_size(B, H, N),), 0xFF, dtype=torch.uint8, device="cuda")
+    rs.rs_attention_map_fwd(d[:, :, 0], d[:, :, 1], d[:, :, 2], o, 0.125, amap, s_cls, s_mean, ws, cls_index=cls)
+    o_fused = torch.empty_like(o)
+    rs.rs_attention_fwd(d[:, :, 0], d[:, :, 1], d[:, :, 2], o_fused, 0.125)
+    torch.cuda.synchronize()
+    A = to_host(amap)
+    assert np.isfinite(A).all() and (A[..., N:] == 0).all()
+    e_map = np.abs(A[..., :N] - A_ref).max() / A_ref.max()
+    e_o, e_f = norm_err(to_host(o), o_ref), norm_err(to_host(o_fused), o_ref)
+    e_c, e_m = norm_err(to_host(s_cls), s_cls_ref), norm_err(to_host(s_mean), s_mean_ref)
+    _say("  map err %.2e, o err %.2e (fused %.2e), s_cls err %.2e, s_mean err %.2e" % (e_map, e_o, e_f, e_c, e_m))
+    assert e_map < TOL["bf16"] and e_o < TOL["bf16"] and e_c < TOL["bf16"] and e_m < TOL["bf16"]
+    # the scores are the stated sums of the map the GPU wrote (fp32 sums of bf16 entries)
+    np.testing.assert_allclose(to_host(s_cls), A[:, :, cls, :N].mean(1), rtol=1e-5, atol=1e-8)
+    np.testing.assert_allclose(to_host(s_mean), A[..., :N].mean(axis=(1, 2)), rtol=1e-4, atol=1e-8)
+    # a selection by either score is exact on the GPU's scores (the prune pass takes any score vector)
+    kept = oracle.topk(to_host(s_mean), 1, N // 2)
+    check_kept_admissible(kept, to_host(s_mean), s_mean_ref, 1, N // 2)
+
+
 def test_attention_closed_forms_on_gpu():
     # identical keys -> mean of V; V = 1 -> 1
     B, N, H = 1, 100, 1
