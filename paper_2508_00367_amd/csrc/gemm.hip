@@ -880,7 +880,7 @@ static void launch_ring(const GemmArgs& g, hipStream_t s) {
 template <int EPI, int DIST>
 static void launch_ring_auto(const GemmArgs& g, hipStream_t s) {
     const int64_t tiles_256 = ((g.M + 255) / 256) * ((g.N + 127) / 128);
-    if (tiles_256 >= 2 * device_cus()) launch_ring<256, 128, EPI, DIST>(g, s);
+    if (tiles_256 >= 2 * device_cus()) launch_ring<128, 256, EPI, DIST>(g, s);  // (a little ahead of 256 x 128)
     else launch_ring<128, 128, EPI, DIST>(g, s);
 }
 
@@ -897,14 +897,16 @@ static void launch_persistent(const GemmArgs& g, hipStream_t s) {
                        g.ref, g.post, g.ln, (int)g.M, g.N, g.K, tiles_m, tiles_n, (g.N + 63) / 64, RS_GEMM_GM);
 }
 
-// Choice by shape.  The persistent 256 x 256 kernel has the best matrix-core rate while every CU
-// has a tile, but its last round costs a whole round however few tiles it holds, and below one
-// round it leaves CUs empty; the ring kernels (two smaller workgroups per CU, tiles handed out as
-// slots free up) keep the chip busy on small and ragged problems at a lower peak rate.  So: the
-// rows that make up whole rounds of 256 x 256 tiles go to the persistent kernel and the rows
-// behind them to a ring kernel in a second launch -- when a round is long (K at least
-// RS_GEMM_TAIL_MINK: a second launch costs a few microseconds) and the last one is at most
-// RS_GEMM_TAIL_FRAC full.
+// Choice by shape.  The persistent 256 x 256 kernel has the best matrix-core rate while most CUs
+// have a tile, but its last round costs a whole round however few tiles it holds, and well below
+// one round it leaves CUs empty; the ring kernels (two smaller workgroups per CU, tiles handed out
+// as slots free up, epilogues under the other workgroup's matrix work) keep the chip busy on
+// small and ragged problems at a lower peak rate.  Measured crossovers on MI355X: the ring kernels
+// win below about half a round of 256 x 256 tiles, and up to a round and a half when K is short
+// (K <= 512: a tile is mostly epilogue).  Beyond that: the rows that make up whole rounds go to the
+// persistent kernel and the rows behind them to a ring kernel in a second launch -- when a round
+// is long (K at least RS_GEMM_TAIL_MINK: a second launch costs a few microseconds) and the last
+// one is at most RS_GEMM_TAIL_FRAC full.
 #ifndef RS_GEMM_TAIL_FRAC
 #define RS_GEMM_TAIL_FRAC 0.5
 #endif
@@ -935,7 +937,9 @@ static hipError_t launch_bf16(const void* a, const void* wt, const void* bias, c
         const int cus = device_cus();
         const int64_t tiles_n = (N + 255) / 256, panels = (M + 255) / 256;
         const int64_t tiles = panels * tiles_n, rounds = tiles / cus, rem = tiles - rounds * cus;
-        if (rounds == 0) launch_ring_auto<EPI, DIST>(g, s);
+        const bool small = 20 * tiles <= 9 * cus || (K <= 512 && 2 * tiles <= 3 * cus);
+        if (small) launch_ring_auto<EPI, DIST>(g, s);
+        else if (rounds == 0) launch_persistent<EPI, DIST>(g, s);
         else if (rem == 0 || K < gemm_tail_mink() || (double)rem > gemm_tail_frac() * cus) launch_persistent<EPI, DIST>(g, s);
         else {
             const int64_t m1 = (rounds * cus / tiles_n) * 256;  // row panels that fill whole rounds
@@ -1067,7 +1071,7 @@ static hipError_t launch_f32(const void* a, const void* w, const void* bias, con
 #define RS_STR(...) RS_STR2(__VA_ARGS__)
 const char* gemm_build_info() {
     return "bf16 gemm: persistent tiles (BM,BN,BK,stages,waves m,waves n) " RS_STR(RS_GEMM_CFG)
-           "; ring tiles 256x128x32 and 128x128x32, 3 stages, 2x2 waves, 2 workgroups per CU"
+           "; ring tiles 128x256x32 and 128x128x32, 3 stages, 4 waves, 2 workgroups per CU, below 0.45 rounds (1.5 if K <= 512)"
            "; rows behind whole rounds go to a ring kernel when K >= " RS_STR(RS_GEMM_TAIL_MINK) " and the last round is under " RS_STR(RS_GEMM_TAIL_FRAC) " full";
 }
 
