@@ -5,6 +5,14 @@ package.  It shares no code with the HIP path and never imports it.
 
 Every function takes numpy arrays (any float dtype, widened to fp64 here) and
 returns fp64 / int32 numpy arrays.
+
+Every function is pinned in tests/test_oracle_pins.py / test_oracle_schedule.py against closed
+forms, hand-worked cases, brute force or library routines.  Two READINGS of the paper have no
+worked example to pin them against (the arithmetic of each reading is pinned, the choice is
+not): which pair of tensors "the MLP shift" compares (OP_MLP is the printed formula of
+"Operation choice"; OP_MLP_STREAM and OP_MLP_NORMED are the other two) -- parity unpinned --
+and how token-wise grid pruning (Sec. 4.2, variant (i)) keeps the grid rectangular
+(grid_token_prune) -- parity unpinned.
 """
 from __future__ import annotations
 
