@@ -5,8 +5,8 @@ in teacher-forced mode: the checker recomputes each checked block from the GPU's
 and is compared on the GPU's kept set (kept sets may differ legitimately inside the rounding band,
 after which the two forwards would no longer see the same tokens).
 
-Every check appends one JSON line of statistics to gpurun_out/parity_summary.jsonl when that folder
-can be written: score / output errors, per-element relative error with a floor, whether kept_idx
+With RS_PARITY_OUT=<folder> in the environment every check appends one JSON line of statistics to
+<folder>/parity_summary.jsonl: score / output errors, per-element relative error with a floor, whether kept_idx
 matched exactly, how many tokens differ, and the width of the admissible band (2 tau) relative to
 the median gap between neighbouring scores."""
 import json
@@ -32,7 +32,10 @@ def _say(*a):
 
 
 def _record(rec):
-    d = os.path.join(ROOT, "gpurun_out")
+    d = os.environ.get("RS_PARITY_OUT")
+    if not d:
+        return
+    d = d if os.path.isabs(d) else os.path.join(ROOT, d)
     try:
         os.makedirs(d, exist_ok=True)
         with open(os.path.join(d, "parity_summary.jsonl"), "a") as f:
