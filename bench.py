@@ -180,13 +180,18 @@ def main():
     fl = stack_flops(stack)
     by = {k: 0.0 for k in ("attention", "layernorm", "prune")}
     slots = D // 64                                    # score partial sums per row left by the GEMM epilogue
-    for (n_in, n_keep) in sched:
+    for l, (n_in, n_keep) in enumerate(sched):
         M = B * n_in
         by["attention"] += 4.0 * M * D * e            # read q, k, v once, write o
-        by["layernorm"] += 2 * (1.0 * M * D * e + 8.0 * M)   # two row-statistics passes: read the rows, write (mean, rstd)
-        if n_keep < n_in - P:                          # partial sums in, scores + kept_idx out, gather of K rows
+        # row-statistics passes (read the rows, write (mean, rstd)): always the one in front of the MLP;
+        # the one in front of the attention only in the first block, later blocks get the statistics the
+        # block before them left for its output: from its gather when it prunes, else from a pass over y
+        prunes = n_keep < n_in - P
+        n_stat = M * (2 if l == 0 else 1) + (B * (P + n_keep) if (not prunes and l + 1 < L) else 0)
+        by["layernorm"] += n_stat * (D * e + 8.0)
+        if prunes:                                     # partial sums in, scores + kept_idx out, gather of K rows (+ their statistics)
             K = P + n_keep
-            by["prune"] += B * (12.0 * slots * n_in + 8.0 * n_in + 4.0 * K + 2.0 * K * D * e)
+            by["prune"] += B * (12.0 * slots * n_in + 8.0 * n_in + 4.0 * K + 2.0 * K * D * e + (8.0 * K if l + 1 < L else 0.0))
     total_flops = sum(fl.values())
 
     def kern(name):
@@ -209,7 +214,8 @@ def main():
         kernels["row_statistics"] = {"avg_us": round(avg_s * 1e6, 2), "launches_per_step": per_step,
                                      "GB/s": round(by["layernorm"] / per_step / avg_s / 1e9, 1),
                                      "note": "the LayerNorms are folded into the GEMMs behind them; this pass reads "
-                                             "the rows once and writes (mean, rstd) per row"}
+                                             "the rows once and writes (mean, rstd) per row; after a pruning block "
+                                             "the gather leaves the statistics of the rows it writes instead"}
     prune_ms = sum(prof[k][0] for k in ("shift_score", "select", "gather")) / a.steps
     n_prune = sum(1 for (n_in, n_keep) in sched if n_keep < n_in - P)
     if n_prune:

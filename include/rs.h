@@ -292,6 +292,25 @@ RS_API rs_status rs_block_fwd(const rs_block_cfg *cfg, const rs_block_weights *w
                        void *workspace, size_t workspace_bytes, void *hip_stream);
 
 /*
+ * rs_block_fwd for a caller that runs a stack of blocks: the LayerNorm in front of a block's
+ * attention (Eq. (5)) needs the mean and variance of every input row, and the previous block has
+ * those rows in registers when it writes them.  Same computation and bit-identical y, kept_idx and
+ * scores as rs_block_fwd; the only difference is where the row statistics of x come from.
+ *   x_stats : float [B * N, 2] in, or NULL: (mean, 1 / sqrt(variance + ln_eps)) of every row of x,
+ *             population variance, exactly as a previous call wrote them to its y_stats with the
+ *             same D and ln_eps.  NULL: computed here, as rs_block_fwd does.  RS_F32 ignores it.
+ *   y_stats : float [B * K, 2] out, or NULL: the same statistics of every row of y.  With pruning
+ *             (bf16, D <= 4096) the gather writes them on its way; otherwise a statistics pass over
+ *             y runs at the end of the call.  May be the buffer x_stats points to.
+ *   x_stats and y_stats must be 8-byte aligned and lie outside the workspace; y_stats must not
+ *   overlap x, y, kept_idx or scores.  Everything else as in rs_block_fwd.
+ */
+RS_API rs_status rs_block_fwd_chained(const rs_block_cfg *cfg, const rs_block_weights *w,
+                                      const void *x, const float *x_stats, void *y, float *y_stats,
+                                      int32_t *kept_idx, float *scores, void *workspace,
+                                      size_t workspace_bytes, void *hip_stream);
+
+/*
  * rs_block_fwd for callers that cannot allocate device memory or hand over a workspace: code
  * under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same
  * computation, same kernels and bit-identical outputs as rs_block_fwd; the scratch tensors live

@@ -26,7 +26,7 @@ EXPORTS = ("rs_last_error", "rs_version", "rs_build_info", "rs_tune_gemm_variant
            "rs_profile_class_name", "rs_attention_fwd", "rs_attention_map_size",
            "rs_attention_map_workspace_size", "rs_attention_map_fwd", "rs_shift_topk_workspace_size",
            "rs_shift_topk", "rs_grid_line_prune", "rs_grid_token_prune", "rs_pack_linear", "rs_linear_fwd", "rs_packed_weights_size", "rs_pack_weights", "rs_block_workspace_size",
-           "rs_block_fwd", "rs_block_static_scratch_size", "rs_block_fwd_static")
+           "rs_block_fwd", "rs_block_fwd_chained", "rs_block_static_scratch_size", "rs_block_fwd_static")
 
 _vp = ctypes.c_void_p
 _i32 = ctypes.c_int32
@@ -107,6 +107,9 @@ def lib():
         L.rs_block_fwd.argtypes = [ctypes.POINTER(RsBlockCfg), ctypes.POINTER(RsBlockWeights),
                                    _vp, _vp, _vp, _vp, _vp, ctypes.c_size_t, _vp]
         L.rs_block_fwd.restype = ctypes.c_int
+        L.rs_block_fwd_chained.argtypes = [ctypes.POINTER(RsBlockCfg), ctypes.POINTER(RsBlockWeights),
+                                           _vp, _vp, _vp, _vp, _vp, _vp, _vp, ctypes.c_size_t, _vp]
+        L.rs_block_fwd_chained.restype = ctypes.c_int
         L.rs_block_static_scratch_size.argtypes = []
         L.rs_block_static_scratch_size.restype = ctypes.c_size_t
         L.rs_block_fwd_static.argtypes = [ctypes.POINTER(RsBlockCfg), ctypes.POINTER(RsBlockWeights),
@@ -279,6 +282,16 @@ def rs_block_fwd(cfg: RsBlockCfg, weights: RsBlockWeights, x, y, kept_idx, score
     ws_bytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
     _check(lib().rs_block_fwd(ctypes.byref(cfg), ctypes.byref(weights), _ptr(x), _ptr(y), _ptr(kept_idx),
                               _ptr(scores), _ptr(workspace), ws_bytes, _stream(stream)))
+
+
+def rs_block_fwd_chained(cfg: RsBlockCfg, weights: RsBlockWeights, x, x_stats, y, y_stats, kept_idx, scores,
+                         workspace, stream=None) -> None:
+    """rs_block_fwd that takes the row statistics of x from x_stats (float [B*N, 2] or None) and leaves
+    those of y in y_stats (float [B*K, 2] or None)."""
+    ws_bytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
+    _check(lib().rs_block_fwd_chained(ctypes.byref(cfg), ctypes.byref(weights), _ptr(x), _ptr(x_stats), _ptr(y),
+                                      _ptr(y_stats), _ptr(kept_idx), _ptr(scores), _ptr(workspace), ws_bytes,
+                                      _stream(stream)))
 
 
 def rs_block_static_scratch_size() -> int:

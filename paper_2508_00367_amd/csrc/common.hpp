@@ -74,6 +74,33 @@ __device__ __forceinline__ float wave_sum(float v) {
     return v;
 }
 
+// Statistics of a row a wave holds as MAXC chunks of 8 values per lane (lane l: chunks l, l + 64,
+// ...; chunks at or past nchunk are not read): (mean, 1 / sqrt(population variance + eps)), the
+// variance taken over the deviations from the mean.  One fixed order of additions, shared by
+// every kernel that produces LayerNorm statistics, so that they all give the same bits.
+template <int MAXC>
+__device__ __forceinline__ float2 wave_row_stats(const float (&v)[MAXC][8], int nchunk, int lane, int D, float eps) {
+    float sum = 0.f;
+#pragma unroll
+    for (int c = 0; c < MAXC; ++c)
+        if (lane + c * 64 < nchunk) {
+#pragma unroll
+            for (int i = 0; i < 8; ++i) sum += v[c][i];
+        }
+    const float mean = wave_sum(sum) / (float)D;
+    float sq = 0.f;
+#pragma unroll
+    for (int c = 0; c < MAXC; ++c)
+        if (lane + c * 64 < nchunk) {
+#pragma unroll
+            for (int i = 0; i < 8; ++i) {
+                const float d = v[c][i] - mean;
+                sq += d * d;
+            }
+        }
+    return make_float2(mean, rsqrtf(wave_sum(sq) / (float)D + eps));
+}
+
 // exact GELU: x * Phi(x)
 __device__ __forceinline__ float gelu_erf(float x) {
     return 0.5f * x * (1.0f + erff(x * 0.70710678118654752440f));
@@ -92,8 +119,9 @@ hipError_t launch_layernorm(rs_dtype dt, const void* x, const void* gamma, const
                             void* out, int64_t M, int D, float eps, hipStream_t s);
 
 // stats[M] = (mean, 1 / sqrt(population variance + eps)) of each row of x[M, D], as float pairs.
+// iota_out (optional): int32 [M], receives row % iota_n (the kept_idx of a block that keeps every token).
 hipError_t launch_rowstats(rs_dtype dt, const void* x, float* stats, int64_t M, int D, float eps,
-                           hipStream_t s);
+                           hipStream_t s, int32_t* iota_out = nullptr, int iota_n = 1);
 
 enum GemmEpilogue {
     EPI_BIAS = 0,            // out = acc + bias
@@ -187,6 +215,11 @@ hipError_t launch_select(const float* scores, int32_t* kept_idx, int B, int N, i
 // out[b, j, :] = src[b, kept_idx[b, j], :]
 hipError_t launch_gather(rs_dtype dt, const void* src, const int32_t* kept_idx, void* out, int B,
                          int N, int K, int D, hipStream_t s);
+// The gather for bf16 rows of at most 4096 elements that also writes stats[B * K] = (mean,
+// 1 / sqrt(variance + eps)) of every gathered row, bit-identical to launch_rowstats on `out`.
+bool gather_stats_fits(rs_dtype dt, int D);
+hipError_t launch_gather_stats(const void* src, const int32_t* kept_idx, void* out, float* stats, int B, int N,
+                               int K, int D, float eps, hipStream_t s);
 
 // scores, kept_idx and gathered = f_in[kept_idx] of every image in one launch that reads f_out and
 // f_in once (images whose f_in rows fit a compute unit's registers: shift_topk_resident_fits)

@@ -67,38 +67,24 @@ __global__ __launch_bounds__(256) void layernorm_kernel(const T* __restrict__ x,
 // normalisation in its epilogue (the normalised rows are never written).
 template <typename T, int MAXC>
 __global__ __launch_bounds__(256) void rowstats_kernel(const T* __restrict__ x, float2* __restrict__ stats,
-                                                       int64_t M, int D, float eps) {
+                                                       int64_t M, int D, float eps,
+                                                       int32_t* __restrict__ iota_out, int iota_n) {
     const int lane = threadIdx.x & 63;
     const int64_t row = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
     if (row >= M) return;
     const int nchunk = D >> 3;
     const T* xr = x + row * D;
     float v[MAXC][8];
-    float sum = 0.f;
 #pragma unroll
     for (int c = 0; c < MAXC; ++c) {
         const int ch = lane + c * 64;
-        if (ch < nchunk) {
-            Elem<T>::load8(xr + ch * 8, v[c]);
-#pragma unroll
-            for (int i = 0; i < 8; ++i) sum += v[c][i];
-        }
+        if (ch < nchunk) Elem<T>::load8(xr + ch * 8, v[c]);
     }
-    const float mean = wave_sum(sum) / (float)D;
-    float sq = 0.f;
-#pragma unroll
-    for (int c = 0; c < MAXC; ++c) {
-        const int ch = lane + c * 64;
-        if (ch < nchunk) {
-#pragma unroll
-            for (int i = 0; i < 8; ++i) {
-                const float d = v[c][i] - mean;
-                sq += d * d;
-            }
-        }
+    const float2 st = wave_row_stats<MAXC>(v, nchunk, lane, D, eps);
+    if (lane == 0) {
+        stats[row] = st;
+        if (iota_out) iota_out[row] = (int32_t)(row % iota_n);
     }
-    const float inv = rsqrtf(wave_sum(sq) / (float)D + eps);
-    if (lane == 0) stats[row] = make_float2(mean, inv);
 }
 
 // Narrow rows (D <= 8 G, G = 16 or 32 lanes): 64 / G rows per wave, so that the lanes of a wave
@@ -107,7 +93,8 @@ __global__ __launch_bounds__(256) void rowstats_kernel(const T* __restrict__ x, 
 // hold zeros), so the statistics are the same bits.
 template <typename T, int G>
 __global__ __launch_bounds__(256) void rowstats_narrow_kernel(const T* __restrict__ x, float2* __restrict__ stats,
-                                                              int64_t M, int D, float eps) {
+                                                              int64_t M, int D, float eps,
+                                                              int32_t* __restrict__ iota_out, int iota_n) {
     constexpr int RPW = 64 / G;  // rows per wave
     const int lane = threadIdx.x & 63, sub = lane % G;
     const int64_t row = ((int64_t)blockIdx.x * 4 + (threadIdx.x >> 6)) * RPW + lane / G;
@@ -132,26 +119,29 @@ __global__ __launch_bounds__(256) void rowstats_narrow_kernel(const T* __restric
     }
 #pragma unroll
     for (int off = G / 2; off >= 1; off >>= 1) sq += __shfl_xor(sq, off, kWave);
-    if (sub == 0 && row < M) stats[row] = make_float2(mean, rsqrtf(sq / (float)D + eps));
+    if (sub == 0 && row < M) {
+        stats[row] = make_float2(mean, rsqrtf(sq / (float)D + eps));
+        if (iota_out) iota_out[row] = (int32_t)(row % iota_n);
+    }
 }
 
 hipError_t launch_rowstats(rs_dtype dt, const void* x, float* stats, int64_t M, int D, float eps,
-                           hipStream_t s) {
+                           hipStream_t s, int32_t* iota_out, int iota_n) {
     if (M == 0) return hipSuccess;
     dim3 grid((unsigned)((M + 3) / 4)), block(256);
     float2* st = reinterpret_cast<float2*>(stats);
     if (dt == RS_BF16 && D <= 256) {
         const bf16raw* xb = (const bf16raw*)x;
-        if (D <= 128) hipLaunchKernelGGL((rowstats_narrow_kernel<bf16raw, 16>), dim3((unsigned)((M + 15) / 16)), block, 0, s, xb, st, M, D, eps);
-        else hipLaunchKernelGGL((rowstats_narrow_kernel<bf16raw, 32>), dim3((unsigned)((M + 7) / 8)), block, 0, s, xb, st, M, D, eps);
+        if (D <= 128) hipLaunchKernelGGL((rowstats_narrow_kernel<bf16raw, 16>), dim3((unsigned)((M + 15) / 16)), block, 0, s, xb, st, M, D, eps, iota_out, iota_n);
+        else hipLaunchKernelGGL((rowstats_narrow_kernel<bf16raw, 32>), dim3((unsigned)((M + 7) / 8)), block, 0, s, xb, st, M, D, eps, iota_out, iota_n);
         return hipGetLastError();
     }
     if (dt == RS_F32) {
-        if (D <= 2 * 512) hipLaunchKernelGGL((rowstats_kernel<float, 2>), grid, block, 0, s, (const float*)x, st, M, D, eps);
-        else hipLaunchKernelGGL((rowstats_kernel<float, 8>), grid, block, 0, s, (const float*)x, st, M, D, eps);
+        if (D <= 2 * 512) hipLaunchKernelGGL((rowstats_kernel<float, 2>), grid, block, 0, s, (const float*)x, st, M, D, eps, iota_out, iota_n);
+        else hipLaunchKernelGGL((rowstats_kernel<float, 8>), grid, block, 0, s, (const float*)x, st, M, D, eps, iota_out, iota_n);
     } else {
-        if (D <= 2 * 512) hipLaunchKernelGGL((rowstats_kernel<bf16raw, 2>), grid, block, 0, s, (const bf16raw*)x, st, M, D, eps);
-        else hipLaunchKernelGGL((rowstats_kernel<bf16raw, 8>), grid, block, 0, s, (const bf16raw*)x, st, M, D, eps);
+        if (D <= 2 * 512) hipLaunchKernelGGL((rowstats_kernel<bf16raw, 2>), grid, block, 0, s, (const bf16raw*)x, st, M, D, eps, iota_out, iota_n);
+        else hipLaunchKernelGGL((rowstats_kernel<bf16raw, 8>), grid, block, 0, s, (const bf16raw*)x, st, M, D, eps, iota_out, iota_n);
     }
     return hipGetLastError();
 }

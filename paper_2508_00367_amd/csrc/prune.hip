@@ -496,6 +496,58 @@ __global__ __launch_bounds__(256) void gather_rows_kernel(const uint4* __restric
     for (int c = lane; c < row_vec; c += 64) d[c] = s[c];
 }
 
+// The same gather for bf16 rows that also leaves the LayerNorm statistics of every row it writes
+// (mean, 1 / sqrt(variance + eps)): the wave has the row in registers anyway, and the block that
+// consumes the gathered rows then needs no statistics pass of its own.  Same arithmetic as the
+// statistics kernel (wave_row_stats), hence the same bits.
+template <int MAXC>
+__global__ __launch_bounds__(256) void gather_rows_stats_kernel(const bf16raw* __restrict__ src,
+                                                                const int32_t* __restrict__ kept_idx,
+                                                                bf16raw* __restrict__ out,
+                                                                float2* __restrict__ stats, int64_t rows, int N,
+                                                                int K, int D, float eps) {
+    const int lane = threadIdx.x & 63;
+    const int64_t r = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
+    if (r >= rows) return;
+    const int64_t b = r / K;
+    const bf16raw* s = src + (b * N + kept_idx[r]) * D;
+    bf16raw* d = out + r * D;
+    const int nchunk = D >> 3;
+    float v[MAXC][8];
+#pragma unroll
+    for (int c = 0; c < MAXC; ++c) {
+        const int ch = lane + c * 64;
+        if (ch < nchunk) {
+            const uint4 raw = *reinterpret_cast<const uint4*>(s + ch * 8);
+            *reinterpret_cast<uint4*>(d + ch * 8) = raw;
+            const uint32_t w[4] = {raw.x, raw.y, raw.z, raw.w};
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                v[c][2 * i] = __uint_as_float(w[i] << 16);
+                v[c][2 * i + 1] = __uint_as_float(w[i] & 0xffff0000u);
+            }
+        }
+    }
+    const float2 st = wave_row_stats<MAXC>(v, nchunk, lane, D, eps);
+    if (lane == 0) stats[r] = st;
+}
+
+bool gather_stats_fits(rs_dtype dt, int D) { return dt == RS_BF16 && D <= 8 * 64 * 8; }
+
+hipError_t launch_gather_stats(const void* src, const int32_t* kept_idx, void* out, float* stats, int B, int N,
+                               int K, int D, float eps, hipStream_t s) {
+    const int64_t rows = (int64_t)B * K;
+    if (rows == 0) return hipSuccess;
+    const dim3 grid((unsigned)((rows + 3) / 4)), block(256);
+    if (D <= 2 * 512)
+        hipLaunchKernelGGL(gather_rows_stats_kernel<2>, grid, block, 0, s, (const bf16raw*)src, kept_idx, (bf16raw*)out,
+                           reinterpret_cast<float2*>(stats), rows, N, K, D, eps);
+    else
+        hipLaunchKernelGGL(gather_rows_stats_kernel<8>, grid, block, 0, s, (const bf16raw*)src, kept_idx, (bf16raw*)out,
+                           reinterpret_cast<float2*>(stats), rows, N, K, D, eps);
+    return hipGetLastError();
+}
+
 hipError_t launch_gather(rs_dtype dt, const void* src, const int32_t* kept_idx, void* out, int B,
                          int N, int K, int D, hipStream_t s) {
     const int64_t rows = (int64_t)B * K;

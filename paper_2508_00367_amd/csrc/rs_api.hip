@@ -186,7 +186,7 @@ using namespace rs;
 
 static rs_status block_fwd(const rs_block_cfg* cfg, const rs_block_weights* w, const void* x, void* y,
                            int32_t* kept_idx, float* scores, void* workspace, size_t workspace_bytes,
-                           void* hip_stream);
+                           void* hip_stream, const float* x_stats = nullptr, float* y_stats = nullptr);
 
 // ---- scratch of rs_block_fwd_static ------------------------------------------------------
 // One buffer per GPU, part of the loaded code object: it exists from the moment the library's
@@ -560,6 +560,12 @@ rs_status rs_block_fwd(const rs_block_cfg* cfg, const rs_block_weights* w, const
     return block_fwd(cfg, w, x, y, kept_idx, scores, workspace, workspace_bytes, hip_stream);
 }
 
+rs_status rs_block_fwd_chained(const rs_block_cfg* cfg, const rs_block_weights* w, const void* x,
+                               const float* x_stats, void* y, float* y_stats, int32_t* kept_idx, float* scores,
+                               void* workspace, size_t workspace_bytes, void* hip_stream) {
+    return block_fwd(cfg, w, x, y, kept_idx, scores, workspace, workspace_bytes, hip_stream, x_stats, y_stats);
+}
+
 rs_status rs_block_fwd_static(const rs_block_cfg* cfg, const rs_block_weights* w, const void* x, void* y,
                               int32_t* kept_idx, float* scores, void* hip_stream) {
     rs_status st = check_cfg(cfg);
@@ -581,7 +587,7 @@ size_t rs_block_static_scratch_size(void) { return kStaticScratchBytes; }
 
 static rs_status block_fwd(const rs_block_cfg* cfg, const rs_block_weights* w, const void* x, void* y,
                            int32_t* kept_idx, float* scores, void* workspace, size_t workspace_bytes,
-                           void* hip_stream) {
+                           void* hip_stream, const float* x_stats, float* y_stats) {
     rs_status st = check_cfg(cfg);
     if (st != RS_OK) return st;
     st = check_weights(w);
@@ -606,6 +612,15 @@ static rs_status block_fwd(const rs_block_cfg* cfg, const rs_block_weights* w, c
                    !overlaps(workspace, L.total, kept_idx, (size_t)c.B * K * sizeof(int32_t)) &&
                    !overlaps(workspace, L.total, scores, M_ * sizeof(float)),
                    RS_ERR_INVALID_ARG, "x, y, kept_idx and scores must lie outside the workspace");
+        const size_t ys = (size_t)c.B * K * 2 * sizeof(float);
+        RS_REQUIRE(!overlaps(workspace, L.total, x_stats, M_ * 2 * sizeof(float)) && !overlaps(workspace, L.total, y_stats, ys),
+                   RS_ERR_INVALID_ARG, "x_stats and y_stats must lie outside the workspace");
+        RS_REQUIRE(!overlaps(y_stats, ys, x, M_ * c.D * e) && !overlaps(y_stats, ys, y, (size_t)c.B * K * c.D * e) &&
+                   !overlaps(y_stats, ys, kept_idx, (size_t)c.B * K * sizeof(int32_t)) &&
+                   !overlaps(y_stats, ys, scores, M_ * sizeof(float)),
+                   RS_ERR_INVALID_ARG, "y_stats must not overlap x, y, kept_idx or scores");
+        RS_REQUIRE((reinterpret_cast<uintptr_t>(x_stats) & 7u) == 0 && (reinterpret_cast<uintptr_t>(y_stats) & 7u) == 0,
+                   RS_ERR_INVALID_ARG, "x_stats and y_stats must be 8-byte aligned");
     }
 
     hipStream_t s = (hipStream_t)hip_stream;
@@ -639,7 +654,7 @@ static rs_status block_fwd(const rs_block_cfg* cfg, const rs_block_weights* w, c
         w1 = pk + P.w_fc1;
         w2 = pk + P.w_fc2;
         float* stats = (float*)(ws + L.stats);
-        ln1 = GemmLnFold{stats, (const float*)(pk + P.cs_qkv), (const float*)(pk + P.b_qkv)};
+        ln1 = GemmLnFold{x_stats ? x_stats : stats, (const float*)(pk + P.cs_qkv), (const float*)(pk + P.b_qkv)};
         ln2 = GemmLnFold{stats, (const float*)(pk + P.cs_fc1), (const float*)(pk + P.b_fc1)};
     }
     const float scale = c.attn_scale > 0.f ? c.attn_scale : 0.125f;  // 1/sqrt(64)
@@ -647,8 +662,9 @@ static rs_status block_fwd(const rs_block_cfg* cfg, const rs_block_weights* w, c
     // x1 = SA(LN(x)) + x                                                     Eq. (5)
     // bf16: the LayerNorm in front of a GEMM is a pass for the row statistics only; the GEMM reads
     // the raw rows against weights that carry the LayerNorm scale and normalises in its epilogue
+    // (a caller that chains blocks hands over the statistics the previous block left for its output)
     if (dt == RS_BF16) {
-        RS_LAUNCH_K(K_LN, s, launch_rowstats(dt, x, (float*)(ws + L.stats), M, D, c.ln_eps, s));
+        if (!x_stats) RS_LAUNCH_K(K_LN, s, launch_rowstats(dt, x, (float*)(ws + L.stats), M, D, c.ln_eps, s));
         RS_LAUNCH_K(K_GEMM_QKV, s, launch_gemm_ln(EPI_LN_BIAS, x, wq, ln1, qkv, M, 3 * D, D, s));
     } else {
         RS_LAUNCH_K(K_LN, s, launch_layernorm(dt, x, w->ln1_g, w->ln1_b, u, M, D, c.ln_eps, s));
@@ -666,8 +682,11 @@ static rs_status block_fwd(const rs_block_cfg* cfg, const rs_block_weights* w, c
                             partials, nullptr, false, M, D, D, s));
     // xhat = MLP(LN(x1)) + x1, with the shift partial sums of D(MLP(LN(x1)), x1)   Eq. (6), Eq. (4)
     const bool need_v = want_scores && c.op == RS_SHIFT_MLP_NORMED;  // LN(x1) itself is an operand of the score
+    // a block that keeps every token has kept_idx[b, j] = j: written by the statistics pass on its way
+    const bool iota_folded = dt == RS_BF16 && !prune && K > 0;
     if (dt == RS_BF16) {
-        RS_LAUNCH_K(K_LN, s, launch_rowstats(dt, x1, (float*)(ws + L.stats), M, D, c.ln_eps, s));
+        RS_LAUNCH_K(K_LN, s, launch_rowstats(dt, x1, (float*)(ws + L.stats), M, D, c.ln_eps, s,
+                                             iota_folded ? kept_idx : nullptr, c.N));
         if (need_v) RS_LAUNCH_K(K_LN, s, launch_layernorm(dt, x1, w->ln2_g, w->ln2_b, u, M, D, c.ln_eps, s));
         RS_LAUNCH_K(K_GEMM_FC1, s, launch_gemm_ln(EPI_LN_BIAS_GELU, x1, w1, ln2, hid, M, Dm, D, s));
     } else {
@@ -682,16 +701,26 @@ static rs_status block_fwd(const rs_block_cfg* cfg, const rs_block_weights* w, c
     const void* ref = c.op == RS_SHIFT_BLOCK ? x : c.op == RS_SHIFT_MLP_NORMED ? (const void*)u : nullptr;
     RS_LAUNCH_K(K_GEMM_FC2, s, launch_gemm(dt, fc2_scores ? EPI_BIAS_RES_SHIFT : EPI_BIAS_RES, c.dist, hid, w2, w->b_fc2, x1,
                           xhat, partials, ref, post, M, D, Dm, s));
+    // the survivors' rows, with the LayerNorm statistics the next block needs if the caller asks for them
+    auto gather_out = [&]() -> rs_status {
+        if (y_stats && gather_stats_fits(dt, D)) {
+            RS_LAUNCH_K(K_GATHER, s, launch_gather_stats(xhat, kept_idx, y, y_stats, c.B, c.N, K, D, c.ln_eps, s));
+        } else {
+            RS_LAUNCH_K(K_GATHER, s, launch_gather(dt, xhat, kept_idx, y, c.B, c.N, K, D, s));
+            if (y_stats) RS_LAUNCH_K(K_LN, s, launch_rowstats(dt, y, y_stats, (int64_t)c.B * K, D, c.ln_eps, s));
+        }
+        return RS_OK;
+    };
     if (prune && c.n_keep > 0 && select_from_partials_fits(c.N)) {
         // scores straight from the epilogue's partial sums inside the selection kernel
         RS_LAUNCH_K(K_SELECT, s, launch_select_from_partials(c.dist, partials, L.slots, sc, kept_idx, c.B, c.N, c.n_prefix,
                                                            c.n_keep, s));
-        RS_LAUNCH_K(K_GATHER, s, launch_gather(dt, xhat, kept_idx, y, c.B, c.N, K, D, s));
-        return RS_OK;
+        return gather_out();
     }
     if (want_scores) RS_LAUNCH_K(K_SCORE, s, launch_finalize_scores(c.dist, partials, L.slots, sc, M, s));
     // keep the n_keep highest-shift tokens (plus the prefix) and compact them
-    RS_LAUNCH_K(K_SELECT, s, launch_select(sc, kept_idx, c.B, c.N, c.n_prefix, c.n_keep, s));
-    if (prune) RS_LAUNCH_K(K_GATHER, s, launch_gather(dt, xhat, kept_idx, y, c.B, c.N, K, D, s));
+    if (!iota_folded) RS_LAUNCH_K(K_SELECT, s, launch_select(sc, kept_idx, c.B, c.N, c.n_prefix, c.n_keep, s));
+    if (prune) return gather_out();
+    if (y_stats) RS_LAUNCH_K(K_LN, s, launch_rowstats(dt, y, y_stats, M, D, c.ln_eps, s));
     return RS_OK;
 }

@@ -40,6 +40,7 @@ class EncoderStack:
             self._keep_alive.append((w, packed))
             self.weights.append(rs.make_weights(w, packed))
         self.gemm_variant = 0            # tile-variant switch of the bf16 GEMMs (0 = chosen by shape)
+        self.chain = True                # hand row statistics from block to block (same results either way)
         self.set_streams(streams)
 
     def tune(self, candidates=((1, 0), (2, 0), (2, 1)), steps: int = 8, rounds: int = 2):
@@ -84,6 +85,7 @@ class EncoderStack:
                 ws=torch.empty(max(rs.rs_block_workspace_size(c) for c in cfgs), dtype=torch.uint8, device=dev),
                 bufs=[torch.empty((Bp, self.N, self.D), device=dev, dtype=self.dtype) for _ in range(2)],
                 kept=torch.empty((Bp, self.N), device=dev, dtype=torch.int32),
+                stats=torch.empty((Bp * self.N, 2), device=dev, dtype=torch.float32),
                 stream=torch.cuda.Stream() if S > 1 else None))
             first += Bp
 
@@ -99,8 +101,11 @@ class EncoderStack:
             for i, p in enumerate(self.parts):
                 stream = p["stream"] if p["stream"] is not None else torch.cuda.current_stream()
                 dst = p["bufs"][l & 1]
-                rs.rs_block_fwd(p["cfgs"][l], self.weights[l], src[i], dst, p["kept"],
-                                None if scores is None else scores[i], p["ws"], stream)
+                # every block but the last leaves the row statistics of its output for the next
+                # block's first LayerNorm (written by the gather as it copies the surviving rows)
+                rs.rs_block_fwd_chained(p["cfgs"][l], self.weights[l], src[i], p["stats"] if l > 0 and self.chain else None,
+                                        dst, p["stats"] if l + 1 < self.L and self.chain else None, p["kept"],
+                                        None if scores is None else scores[i], p["ws"], stream)
                 if capture is not None:
                     capture(l, p, src[i], dst)
                 src[i] = dst

@@ -108,6 +108,31 @@ def test_block_rejects_bad_pointers_and_workspace():
     assert L.rs_block_fwd(ctypes.byref(cfg0), ctypes.byref(w), None, None, None, None, None, 0, None) == rs.RS_OK
 
 
+def test_chained_block_entry_validates_its_statistics_buffers():
+    """rs_block_fwd_chained: x_stats / y_stats are checked like the other tensors, before any launch."""
+    cfg = _cfg()
+    need = rs.rs_block_workspace_size(cfg)
+    L = rs.lib()
+    w = _weights()
+    ws0 = 1 << 30
+
+    def call(xs, ys, y=2 * FAKE, kept=3 * FAKE):
+        return L.rs_block_fwd_chained(ctypes.byref(cfg), ctypes.byref(w), FAKE, xs, y, ys, kept, None, ws0, need, None)
+
+    assert call(ws0 + 512, None) == rs.RS_ERR_INVALID_ARG          # x_stats inside the workspace
+    assert "outside the workspace" in rs.rs_last_error()
+    assert call(None, ws0 + need - 8) == rs.RS_ERR_INVALID_ARG     # y_stats inside the workspace
+    assert call(None, 2 * FAKE + 64) == rs.RS_ERR_INVALID_ARG      # y_stats overlaps y
+    assert "y_stats" in rs.rs_last_error()
+    assert call(None, 3 * FAKE) == rs.RS_ERR_INVALID_ARG           # y_stats overlaps kept_idx
+    assert call(None, FAKE + 16) == rs.RS_ERR_INVALID_ARG          # y_stats overlaps x
+    assert call(5 * FAKE + 4, None) == rs.RS_ERR_INVALID_ARG       # misaligned
+    assert call(None, 5 * FAKE + 4) == rs.RS_ERR_INVALID_ARG
+    cfg0 = _cfg(B=0)
+    assert L.rs_block_fwd_chained(ctypes.byref(cfg0), ctypes.byref(w), None, None, None, None, None, None, None, 0,
+                                  None) == rs.RS_OK
+
+
 def test_attention_rejects_bad_arguments():
     L = rs.lib()
 

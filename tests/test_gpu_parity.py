@@ -589,6 +589,76 @@ def test_block_stack_replays_from_a_hip_graph():
         assert torch.equal(kept.view(-1)[:n_k], want_kept), rep
 
 
+@pytest.mark.parametrize("D,H,Dm", [(192, 3, 768), (384, 6, 1536), (1152, 18, 1152)])
+def test_chained_blocks_equal_unchained_blocks(D, H, Dm):
+    """rs_block_fwd_chained hands the row statistics of a block's output to the next block (written by
+    the gather in pruning blocks, by a pass over y otherwise): outputs, kept indices and scores of a
+    pruning / non-pruning / pruning stack must equal rs_block_fwd's bit for bit, y_stats must be the
+    statistics of y, and a block that keeps every token must leave kept_idx[b, j] = j."""
+    B, N, P = 3, 77, 1
+    sched = [(77, 60), (61, 60), (61, 33)]
+    x0 = to_dev(host_round(si.tokens(21, B, N, D, 0.4), "bf16"), "bf16")
+    cfgs, wl = [], []
+    for l, (n_in, n_keep) in enumerate(sched):
+        w = {k: to_dev(host_round(v, "bf16"), "bf16") for k, v in si.block_weights(21, l, D, Dm, 0.05).items()}
+        cfgs.append(rs.make_cfg(B, n_in, D, H, Dm, P, n_keep, torch.bfloat16))
+        wl.append((w, rs.make_weights(w)))
+    ws = torch.empty(max(rs.rs_block_workspace_size(c) for c in cfgs), dtype=torch.uint8, device="cuda")
+
+    def run(chained):
+        bufs = [torch.zeros((B, N, D), device="cuda", dtype=torch.bfloat16) for _ in range(2)]
+        stats = torch.full((B * N, 2), float("nan"), device="cuda", dtype=torch.float32)
+        outs, src = [], x0
+        for l, (n_in, n_keep) in enumerate(sched):
+            K = P + n_keep
+            kept = torch.full((B, K), -1, device="cuda", dtype=torch.int32)
+            sc = torch.empty((B, n_in), device="cuda", dtype=torch.float32)
+            dst = bufs[l & 1]
+            if chained:
+                rs.rs_block_fwd_chained(cfgs[l], wl[l][1], src, stats if l > 0 else None, dst, stats, kept, sc, ws)
+            else:
+                rs.rs_block_fwd(cfgs[l], wl[l][1], src, dst, kept, sc, ws)
+            torch.cuda.synchronize()
+            y = dst.view(-1)[:B * K * D].view(B, K, D).clone()
+            outs.append((y, kept.clone(), sc.clone(), stats[:B * K].clone() if chained else None))
+            src = dst
+        return outs
+
+    plain, chain = run(False), run(True)
+    for l, ((y0, k0, s0, _), (y1, k1, s1, st)) in enumerate(zip(plain, chain)):
+        assert torch.equal(y0.view(torch.int16), y1.view(torch.int16)), l
+        assert torch.equal(k0, k1), l
+        assert torch.equal(s0, s1), l
+        yh = y1.float().cpu().numpy().astype(np.float64).reshape(-1, D)
+        mean, var = yh.mean(-1), yh.var(-1)
+        np.testing.assert_allclose(st[:, 0].cpu().numpy(), mean, rtol=0, atol=2e-6 * np.abs(yh).max())
+        np.testing.assert_allclose(st[:, 1].cpu().numpy(), 1.0 / np.sqrt(var + 1e-6), rtol=2e-5)
+    K1 = P + sched[1][1]
+    assert torch.equal(chain[1][1], torch.arange(K1, device="cuda", dtype=torch.int32).expand(B, K1))
+
+
+def test_chained_block_fp32_leaves_statistics_of_y():
+    """The fp32 parity configuration ignores x_stats and still fills y_stats."""
+    B, N, D, H, Dm, P, n_keep = 2, 50, 128, 2, 256, 1, 30
+    x = si.tokens(22, B, N, D)
+    w = si.block_weights(22, 0, D, Dm)
+    cfg = rs.make_cfg(B, N, D, H, Dm, P, n_keep, torch.float32)
+    dw = {k: to_dev(v, "f32") for k, v in w.items()}
+    ws = torch.empty(rs.rs_block_workspace_size(cfg), dtype=torch.uint8, device="cuda")
+    K = P + n_keep
+    y0, y1 = (torch.empty((B, K, D), device="cuda", dtype=torch.float32) for _ in range(2))
+    k0, k1 = (torch.empty((B, K), device="cuda", dtype=torch.int32) for _ in range(2))
+    stats = torch.empty((B * K, 2), device="cuda", dtype=torch.float32)
+    bogus = torch.full((B * N, 2), float("nan"), device="cuda", dtype=torch.float32)
+    rs.rs_block_fwd(cfg, rs.make_weights(dw), to_dev(x, "f32"), y0, k0, None, ws)
+    rs.rs_block_fwd_chained(cfg, rs.make_weights(dw), to_dev(x, "f32"), bogus, y1, stats, k1, None, ws)
+    torch.cuda.synchronize()
+    assert torch.equal(y0, y1) and torch.equal(k0, k1)
+    yh = y1.cpu().numpy().astype(np.float64).reshape(-1, D)
+    np.testing.assert_allclose(stats[:, 0].cpu().numpy(), yh.mean(-1), atol=1e-6 * np.abs(yh).max())
+    np.testing.assert_allclose(stats[:, 1].cpu().numpy(), 1.0 / np.sqrt(yh.var(-1) + 1e-6), rtol=1e-5)
+
+
 # ----------------------------------------------------------------------------
 # line-wise pruning of a 2-D grid
 # ----------------------------------------------------------------------------
