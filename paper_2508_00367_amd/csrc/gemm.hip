@@ -876,11 +876,15 @@ static void launch_ring(const GemmArgs& g, hipStream_t s) {
                        tiles_n, (g.N + 63) / 64, RS_GEMM_GM, GemmBatch{0, 0, 0});
 }
 
-// the ring kernel with the tile height that fills the chip's 2 x CUs workgroup slots
+// The ring kernel with the tile width that suits the grid.  128 x 128 tiles unless they would leave
+// some CUs two workgroups and others one (more than one workgroup per CU, at most two): then the
+// 128 x 256 tiles, half as many, give every CU one workgroup of the same length (fc2 at 6280 rows:
+// 58 -> 48 us); and for large grids, where the wider tile moves fewer bytes per flop.
 template <int EPI, int DIST>
 static void launch_ring_auto(const GemmArgs& g, hipStream_t s) {
-    const int64_t tiles_256 = ((g.M + 255) / 256) * ((g.N + 127) / 128);
-    if (tiles_256 >= 2 * device_cus()) launch_ring<128, 256, EPI, DIST>(g, s);  // (a little ahead of 256 x 128)
+    const int cus = device_cus();
+    const int64_t n128 = ((g.M + 127) / 128) * ((g.N + 127) / 128);  // workgroups of the 128 x 128 tiling
+    if ((n128 > cus && n128 <= 2 * cus) || n128 >= 4 * cus) launch_ring<128, 256, EPI, DIST>(g, s);
     else launch_ring<128, 128, EPI, DIST>(g, s);
 }
 
@@ -902,7 +906,7 @@ static void launch_persistent(const GemmArgs& g, hipStream_t s) {
 // one round it leaves CUs empty; the ring kernels (two smaller workgroups per CU, tiles handed out
 // as slots free up, epilogues under the other workgroup's matrix work) keep the chip busy on
 // small and ragged problems at a lower peak rate.  Measured crossovers on MI355X: the ring kernels
-// win below about half a round of 256 x 256 tiles, and up to a round and a half when K is short
+// win up to half a round of 256 x 256 tiles, and up to a round and a half when K is short
 // (K <= 512: a tile is mostly epilogue).  Beyond that: the rows that make up whole rounds go to the
 // persistent kernel and the rows behind them to a ring kernel in a second launch -- when a round
 // is long (K at least RS_GEMM_TAIL_MINK: a second launch costs a few microseconds) and the last
@@ -937,7 +941,7 @@ static hipError_t launch_bf16(const void* a, const void* wt, const void* bias, c
         const int cus = device_cus();
         const int64_t tiles_n = (N + 255) / 256, panels = (M + 255) / 256;
         const int64_t tiles = panels * tiles_n, rounds = tiles / cus, rem = tiles - rounds * cus;
-        const bool small = 20 * tiles <= 9 * cus || (K <= 512 && 2 * tiles <= 3 * cus);
+        const bool small = 2 * tiles <= cus || (K <= 512 && 2 * tiles <= 3 * cus);
         if (small) launch_ring_auto<EPI, DIST>(g, s);
         else if (rounds == 0) launch_persistent<EPI, DIST>(g, s);
         else if (rem == 0 || K < gemm_tail_mink() || (double)rem > gemm_tail_frac() * cus) launch_persistent<EPI, DIST>(g, s);
@@ -1071,7 +1075,7 @@ static hipError_t launch_f32(const void* a, const void* w, const void* bias, con
 #define RS_STR(...) RS_STR2(__VA_ARGS__)
 const char* gemm_build_info() {
     return "bf16 gemm: persistent tiles (BM,BN,BK,stages,waves m,waves n) " RS_STR(RS_GEMM_CFG)
-           "; ring tiles 128x256x32 and 128x128x32, 3 stages, 4 waves, 2 workgroups per CU, below 0.45 rounds (1.5 if K <= 512)"
+           "; ring tiles 128x256x32 and 128x128x32, 3 stages, 4 waves, 2 workgroups per CU, up to 0.5 rounds (1.5 if K <= 512)"
            "; rows behind whole rounds go to a ring kernel when K >= " RS_STR(RS_GEMM_TAIL_MINK) " and the last round is under " RS_STR(RS_GEMM_TAIL_FRAC) " full";
 }
 
