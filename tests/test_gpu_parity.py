@@ -589,6 +589,40 @@ def test_block_stack_replays_from_a_hip_graph():
         assert torch.equal(kept.view(-1)[:n_k], want_kept), rep
 
 
+def test_encoder_stack_replays_from_a_hip_graph():
+    """The launch sequence bench.py times (EncoderStack.step: chained blocks, ping-pong buffers) recorded
+    into one HIP graph: every replay, with eager work in between, equals the eager step bit for bit."""
+    wl = dict(B=6, N=65, D=192, H=3, Dm=384, blocks=4, n_prefix=1, prune=dict(kind="drop_pct", pct=20, after=[1, 3]))
+    x0 = to_dev(host_round(si.tokens(31, wl["B"], wl["N"], wl["D"], 0.3), "bf16"), "bf16")
+    w_dev = [{k: to_dev(host_round(v, "bf16"), "bf16") for k, v in si.block_weights(31, l, wl["D"], wl["Dm"], 0.05).items()}
+             for l in range(wl["blocks"])]
+    stack = rs.EncoderStack(wl, x0, w_dev, streams=1)
+    want = stack.step()[0].clone()
+    torch.cuda.synchronize()
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        stack.step()
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        out = stack.step()[0]
+    for rep in range(3):
+        for p in stack.parts:
+            for b_ in p["bufs"]:
+                b_.fill_(float(rep + 1))
+            p["stats"].fill_(float("nan"))
+            p["kept"].zero_()
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(out.view(torch.int16), want.view(torch.int16)), rep
+    # the unchained sequence gives the same bits
+    stack.chain = False
+    assert torch.equal(stack.step()[0].view(torch.int16), want.view(torch.int16))
+
+
 @pytest.mark.parametrize("D,H,Dm", [(192, 3, 768), (384, 6, 1536), (1152, 18, 1152)])
 def test_chained_blocks_equal_unchained_blocks(D, H, Dm):
     """rs_block_fwd_chained hands the row statistics of a block's output to the next block (written by
