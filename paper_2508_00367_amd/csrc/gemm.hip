@@ -87,15 +87,16 @@ constexpr int kPastEnd = 0x7ff00000;
 constexpr int vmcnt_imm(int n) { return (n & 15) | ((n >> 4) << 14) | 0x0F70; }
 
 // WGM x WGN waves; workgroup tile BM x BN, wave tile BM/WGM x BN/WGN, K slice BK (32 or 64).
-// A ring of NSTAGE LDS stages of (BM + BN) rows x 2*BK bytes: K slices stream from global
-// memory directly into LDS (buffer_load ... lds, no register staging), NSTAGE-1 slices ahead of
-// the one the matrix cores work on.  Loads return in order, so "slice t has landed" is
-// s_waitcnt vmcnt(<loads issued after it>); one workgroup barrier per slice.  The slice count is
-// padded to a multiple of NSTAGE with copies aimed past the end of the buffer resource (they
-// deliver zeros), which keeps the loop free of tail branches.  Operand fragments are double
-// buffered in registers and each LDS read is interleaved with its share of the previous K step's
-// MFMAs (sched_group_barrier).  One workgroup per CU; the register budget is that of NW / 4 waves
-// per SIMD.
+// A ring of LDS stages of (BM + BN) rows x 2*BK bytes (NSTAGE = 2), or three stages for the
+// activation rows and two for the weight rows (NSTAGE = 3, long K): K slices stream from global
+// memory directly into LDS (buffer_load ... lds, no register staging), one slice ahead of the
+// one the matrix cores work on (activation rows with NSTAGE = 3: two).  Loads return in order,
+// so "slice t has landed" is s_waitcnt vmcnt(<loads issued after it>); one workgroup barrier per
+// slice.  The slice count is padded to a multiple of the unrolled trip (2 or 6 slices) with copies
+// aimed past the end of the buffer resource (they deliver zeros), which keeps the loop free of
+// tail branches.  Operand fragments are double buffered in registers and each LDS read is
+// interleaved with its share of the previous K step's MFMAs (sched_group_barrier).  One
+// workgroup per CU; the register budget is that of NW / 4 waves per SIMD.
 template <int BM, int BN, int BK, int NSTAGE, int WGM, int WGN, int EPI, int DIST>
 __global__ __launch_bounds__(WGM* WGN * 64, WGM* WGN / 4) void gemm_bf16_kernel(
     const bf16raw* __restrict__ a, const bf16raw* __restrict__ wt, const bf16raw* __restrict__ bias,
@@ -116,15 +117,29 @@ __global__ __launch_bounds__(WGM* WGN * 64, WGM* WGN / 4) void gemm_bf16_kernel(
     static_assert(NW == 4 || NW == 8, "4 or 8 waves");
     static_assert(BM % (RPI * NW) == 0 && BN % (RPI * NW) == 0, "tile rows must split evenly over the wave copies");
     static_assert(BK == 32 || BK == 64, "K slice of 32 or 64");
-    static_assert(NSTAGE == 2, "two stages (deeper rings of narrower slices measured no better)");
+    static_assert(NSTAGE == 2 || NSTAGE == 3, "two stages, or three for the activation rows (deeper rings of narrower slices measured no better)");
 
-    // Epilogue staging: 32 fp32 rows of the wave tile + the wave's row statistics per wave.  It lives
-    // in the array of stage 1, which is made large enough for all waves: stage 0 receives the next
-    // tile's first K slice meanwhile, and being a different array the compiler knows that the
-    // epilogue's LDS traffic need not wait for those copies.
+    // LDS, NSTAGE = 2: two stages of (BM + BN) rows.  Epilogue staging (32 fp32 rows of the wave tile
+    // + the wave's row statistics per wave) lives in the array of stage 1, which is made large
+    // enough for all waves: stage 0 receives the next tile's first K slice meanwhile, and being a
+    // different array the compiler knows that the epilogue's LDS traffic need not wait for those
+    // copies.
+    // NSTAGE = 3 (long K): the activation rows of a slice and its weight rows live in arrays of
+    // their own, THREE for the activations (requested two slices ahead: they are the rows that
+    // come from HBM, and under load a CU's 64 KB request takes longer than one slice of matrix
+    // work) and two for the weights (shared by every row panel, they come from the L2): all 160
+    // KB.  Epilogue staging in activation stages 1, 2 and weight stage 1.
     constexpr int EPW = (32 * (WN * 4 + 16) + WM * 8 + 255) / 256 * 256;  // bytes per wave
-    __shared__ __attribute__((aligned(1024))) unsigned char stage0[STAGE];
-    __shared__ __attribute__((aligned(1024))) unsigned char stage1[STAGE > NW * EPW ? STAGE : NW * EPW];
+    constexpr int SA = BM * RB, SW = BN * RB;
+    constexpr bool DEEP = NSTAGE == 3;
+    static_assert(!DEEP || (NW == 8 && 3 * EPW <= SA && 2 * EPW <= SW), "staging of waves 0-2, 3-5, 6-7 in three stage arrays");
+    __shared__ __attribute__((aligned(1024))) unsigned char stage0[DEEP ? 16 : STAGE];
+    __shared__ __attribute__((aligned(1024))) unsigned char stage1[DEEP ? 16 : (STAGE > NW * EPW ? STAGE : NW * EPW)];
+    __shared__ __attribute__((aligned(1024))) unsigned char sa0[DEEP ? SA : 16];
+    __shared__ __attribute__((aligned(1024))) unsigned char sa1[DEEP ? SA : 16];
+    __shared__ __attribute__((aligned(1024))) unsigned char sa2[DEEP ? SA : 16];
+    __shared__ __attribute__((aligned(1024))) unsigned char sw0[DEEP ? SW : 16];
+    __shared__ __attribute__((aligned(1024))) unsigned char sw1[DEEP ? SW : 16];
 
     // Tile order.  Consecutive workgroup ids go round-robin to the 8 XCDs, each with its own
     // 4 MB L2, so XCD x takes a contiguous range of the tile sequence.  The sequence walks the tile
@@ -165,50 +180,58 @@ __global__ __launch_bounds__(WGM* WGN * 64, WGM* WGN / 4) void gemm_bf16_kernel(
     // 64 banks of 4 bytes and serves a 16-byte-per-lane read 16 lanes at a time, so the 16
     // consecutive rows those lanes read for one MFMA operand must fall into 16 different 16-byte
     // bank groups of a 256-byte line:
-    //   128-byte rows (BK 64): f(r) = (r ^ (r >> 3)) & 7   (row parity picks the half line, the XOR
-    //                          makes rows r and r + 8 differ; measured 0 SQ_LDS_BANK_CONFLICT,
-    //                          against every second cycle with the plain r & 7)
+    //   128-byte rows (BK 64): f(r) = (r & 7) ^ ((r >> 3) & 1)   (row parity picks the half line, the
+    //                          XOR makes rows r and r + 8 differ; the plain r & 7 conflicts every
+    //                          second cycle.  f has period 16 in r, so one set of lane offsets
+    //                          serves every 32-row MFMA tile of the wave)
     //    64-byte rows (BK 32): f(r) = (r >> 2) & 3         (r & 3 picks the quarter line)
     // global -> LDS: wave copy i of wave w fills rows (NW*i + w)*RPI .. +RPI-1 (lane l: row l / SPR,
     // slot l % SPR), so the lane fetches chunk (l % SPR) ^ f(row).
     __amdgpu_buffer_rsrc_t rs_a = make_rsrc(a + (int64_t)m0 * K, (int64_t)min(M - m0, BM) * K * 2);
     __amdgpu_buffer_rsrc_t rs_w = make_rsrc(wt + (int64_t)n0 * K, (int64_t)min(N - n0, BN) * K * 2);
     const int ld_r = lane / SPR, ld_p = lane % SPR;
-    int voff_e, voff_o;  // lane byte offset for even / odd copy index i
-    if (SPR == 8) {  // row >> 3 = NW*i + w
-        voff_e = ((wave * RPI + ld_r) * K + ((ld_p ^ ld_r ^ (wave & 7)) << 3)) * 2;
-        voff_o = ((wave * RPI + ld_r) * K + ((ld_p ^ ld_r ^ ((wave + NW) & 7)) << 3)) * 2;
-    } else {
-        voff_e = voff_o = ((wave * RPI + ld_r) * K + ((ld_p ^ ((ld_r >> 2) & 3)) << 3)) * 2;
-    }
+    // lane byte offset inside a wave copy (NW is even, so row >> 3 = NW*i + w has the parity of w)
+    const int voff = SPR == 8 ? ((wave * RPI + ld_r) * K + ((ld_p ^ ld_r ^ (wave & 1)) << 3)) * 2
+                              : ((wave * RPI + ld_r) * K + ((ld_p ^ ((ld_r >> 2) & 3)) << 3)) * 2;
     const int pass_bytes = NW * RPI * K * 2;
 
     const int S = K / BK;                                   // real slices
-    const int S_pad = (S + NSTAGE - 1) / NSTAGE * NSTAGE;   // loop trip count (zero slices at the end)
+    constexpr int PERIOD = DEEP ? 6 : 2;                    // slices per trip of the unrolled ring
+    const int S_pad = (S + PERIOD - 1) / PERIOD * PERIOD;   // loop trip count (zero slices at the end)
     const int a_row0 = wm * WM + l32, w_row0 = wn * WN + l32;
-    // slot XOR of operand row 32*t + l32 (t = MFMA tile index inside the wave tile)
-    const int sw_e = SPR == 8 ? ((l32 ^ (l32 >> 3)) & 7) : ((l32 >> 2) & 3);
-    const int sw_o = SPR == 8 ? (sw_e ^ 4) : sw_e;
+    // slot XOR of operand row 32*t + l32 (the same for every MFMA tile t of the wave tile)
+    const int sw = SPR == 8 ? ((l32 & 7) ^ ((l32 >> 3) & 1)) : ((l32 >> 2) & 3);
 
 // copies of K slice t_ into stage_; slices past the end are aimed beyond the resource (which covers
 // this tile's rows only, so the aim is past its end whatever the size of the whole matrix)
-#define RS_GEMM_DMA(stage_, t_)                                                                           \
+#define RS_GEMM_DMA_A(sa_, t_)                                                                            \
     {                                                                                                     \
         const bool real_ = (t_) < S;                                                                      \
         const int kb_ = (t_) * RB;                                                                        \
         _Pragma("unroll") for (int i = 0; i < A_LOADS; ++i)                                               \
-            dma16(rs_a, (stage_) + (i * NW + wave) * 1024, (i & 1) ? voff_o : voff_e, real_ ? i * pass_bytes + kb_ : kPastEnd); \
-        _Pragma("unroll") for (int i = 0; i < W_LOADS; ++i)                                               \
-            dma16(rs_w, (stage_) + BM * RB + (i * NW + wave) * 1024, (i & 1) ? voff_o : voff_e, real_ ? i * pass_bytes + kb_ : kPastEnd); \
+            dma16(rs_a, (sa_) + (i * NW + wave) * 1024, voff, real_ ? i * pass_bytes + kb_ : kPastEnd);   \
     }
-#define RS_GEMM_LOAD_FRAGS(f_, stage_, kk_)                                                               \
+#define RS_GEMM_DMA_W(sw_, t_)                                                                            \
     {                                                                                                     \
-        const int ce_ = ((((kk_) * 2 + g) ^ sw_e) << 4), co_ = ((((kk_) * 2 + g) ^ sw_o) << 4);           \
-        _Pragma("unroll") for (int i = 0; i < TN; ++i)                                                    \
-            (f_).w[i] = *reinterpret_cast<const bf16x8*>((stage_) + (BM + w_row0 + i * 32) * RB + ((i & 1) ? co_ : ce_)); \
-        _Pragma("unroll") for (int j = 0; j < TM; ++j)                                                    \
-            (f_).a[j] = *reinterpret_cast<const bf16x8*>((stage_) + (a_row0 + j * 32) * RB + ((j & 1) ? co_ : ce_)); \
+        const bool real_ = (t_) < S;                                                                      \
+        const int kb_ = (t_) * RB;                                                                        \
+        _Pragma("unroll") for (int i = 0; i < W_LOADS; ++i)                                               \
+            dma16(rs_w, (sw_) + (i * NW + wave) * 1024, voff, real_ ? i * pass_bytes + kb_ : kPastEnd);   \
     }
+#define RS_GEMM_DMA(stage_, t_)                                                                           \
+    {                                                                                                     \
+        RS_GEMM_DMA_A(stage_, t_)                                                                         \
+        RS_GEMM_DMA_W((stage_) + BM * RB, t_)                                                             \
+    }
+#define RS_GEMM_LOAD_FRAGS2(f_, sa_, sw_, kk_)                                                            \
+    {                                                                                                     \
+        const int c_ = ((((kk_) * 2 + g) ^ sw) << 4);                                                     \
+        _Pragma("unroll") for (int i = 0; i < TN; ++i)                                                    \
+            (f_).w[i] = *reinterpret_cast<const bf16x8*>((sw_) + (w_row0 + i * 32) * RB + c_);            \
+        _Pragma("unroll") for (int j = 0; j < TM; ++j)                                                    \
+            (f_).a[j] = *reinterpret_cast<const bf16x8*>((sa_) + (a_row0 + j * 32) * RB + c_);            \
+    }
+#define RS_GEMM_LOAD_FRAGS(f_, stage_, kk_) RS_GEMM_LOAD_FRAGS2(f_, stage_, (stage_) + BM * RB, kk_)
 #define RS_GEMM_MFMA(f_)                                                                                  \
     {                                                                                                     \
         _Pragma("unroll") for (int i = 0; i < TN; ++i)                                                    \
@@ -251,8 +274,41 @@ __global__ __launch_bounds__(WGM* WGN * 64, WGM* WGN / 4) void gemm_bf16_kernel(
         RS_GEMM_INTERLEAVE(1)                                                                             \
     }
 
-    static_assert(NSTAGE == 2 && KK == 4, "the slice schedule below is written for two stages of 64-wide slices");
-    RS_GEMM_DMA(stage0, 0)  // first K slice of the first tile
+// The same slice with three activation stages (sa_ / sw_: this slice, san_ / swn_: the next): the
+// wave waits for slice t+1 only -- the activation rows of slice t+2, requested last, may still be
+// on their way: loads complete in order, and no global store is in flight inside the K loop --
+// and after the barrier requests the weights of slice t+2, then the activation rows of slice t+3.
+#define RS_GEMM_SLICE3(sa_, sw_, san_, swn_, t_)                                                          \
+    {                                                                                                     \
+        RS_GEMM_LOAD_FRAGS2(f1, sa_, sw_, 1)                                                              \
+        RS_GEMM_MFMA(f0)                                                                                  \
+        RS_GEMM_INTERLEAVE(0)                                                                             \
+        RS_GEMM_LOAD_FRAGS2(f0, sa_, sw_, 2)                                                              \
+        RS_GEMM_MFMA(f1)                                                                                  \
+        RS_GEMM_INTERLEAVE(0)                                                                             \
+        RS_GEMM_LOAD_FRAGS2(f1, sa_, sw_, 3)                                                              \
+        RS_GEMM_MFMA(f0)                                                                                  \
+        RS_GEMM_INTERLEAVE(0)                                                                             \
+        __builtin_amdgcn_s_waitcnt(((A_LOADS) & 15) | (((A_LOADS) >> 4) << 14) | 0x0070);                 \
+        __builtin_amdgcn_s_barrier();                                                                     \
+        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup"); /* LDS reads stay below the barrier */     \
+        __builtin_amdgcn_sched_barrier(0);                                                                \
+        RS_GEMM_DMA_W(sw_, (t_) + 2)                                                                      \
+        RS_GEMM_DMA_A(sa_, (t_) + 3)                                                                      \
+        RS_GEMM_LOAD_FRAGS2(f0, san_, swn_, 0)                                                            \
+        RS_GEMM_MFMA(f1)                                                                                  \
+        RS_GEMM_INTERLEAVE(1)                                                                             \
+    }
+
+    static_assert(KK == 4, "the slice schedules are written for 64-wide slices");
+    static_assert(A_LOADS <= 15, "copies in flight across a barrier must fit the counter");
+    // first K slice of the first tile
+    if constexpr (DEEP) {
+        RS_GEMM_DMA_A(sa0, 0)
+        RS_GEMM_DMA_W(sw0, 0)
+    } else {
+        RS_GEMM_DMA(stage0, 0)
+    }
 
     for (;;) {  // one tile per iteration
     // LayerNorm-folded epilogues: fetch the (mean, rstd) of this wave's WM rows now (lane l: rows
@@ -299,12 +355,32 @@ __global__ __launch_bounds__(WGM* WGN * 64, WGM* WGN / 4) void gemm_bf16_kernel(
     Frags<TN, TM> f0, f1;
     __builtin_amdgcn_s_waitcnt(vmcnt_imm(0));
     __syncthreads();
-    RS_GEMM_DMA(stage1, 1)
-    RS_GEMM_LOAD_FRAGS(f0, stage0, 0)
-    __builtin_amdgcn_sched_barrier(0);
-    for (int t = 0; t < S_pad; t += 2) {
-        RS_GEMM_SLICE(stage0, stage1, t)
-        RS_GEMM_SLICE(stage1, stage0, t + 1)
+    if constexpr (DEEP) {
+        // slices 1 and 2 go on their way, the activation rows of slice 2 last (they may stay in
+        // flight across the first barrier).  Three activation stages and two weight stages: six
+        // slices per trip, no way out in between (an exit inside the trip would make the
+        // compiler keep copies of the accumulators for each way out)
+        RS_GEMM_DMA_W(sw1, 1)
+        RS_GEMM_DMA_A(sa1, 1)
+        RS_GEMM_DMA_A(sa2, 2)
+        RS_GEMM_LOAD_FRAGS2(f0, sa0, sw0, 0)
+        __builtin_amdgcn_sched_barrier(0);
+        for (int t = 0; t < S_pad; t += 6) {
+            RS_GEMM_SLICE3(sa0, sw0, sa1, sw1, t)
+            RS_GEMM_SLICE3(sa1, sw1, sa2, sw0, t + 1)
+            RS_GEMM_SLICE3(sa2, sw0, sa0, sw1, t + 2)
+            RS_GEMM_SLICE3(sa0, sw1, sa1, sw0, t + 3)
+            RS_GEMM_SLICE3(sa1, sw0, sa2, sw1, t + 4)
+            RS_GEMM_SLICE3(sa2, sw1, sa0, sw0, t + 5)
+        }
+    } else {
+        RS_GEMM_DMA(stage1, 1)
+        RS_GEMM_LOAD_FRAGS(f0, stage0, 0)
+        __builtin_amdgcn_sched_barrier(0);
+        for (int t = 0; t < S_pad; t += 2) {
+            RS_GEMM_SLICE(stage0, stage1, t)
+            RS_GEMM_SLICE(stage1, stage0, t + 1)
+        }
     }
     __builtin_amdgcn_s_waitcnt(vmcnt_imm(0));  // the trailing (empty) copies too: the stages get reused
     __syncthreads();  // every wave is done with the K-loop stages
@@ -335,7 +411,8 @@ __global__ __launch_bounds__(WGM* WGN * 64, WGM* WGN / 4) void gemm_bf16_kernel(
         constexpr int LPR = WN / 8;                // lanes per row on the way out (16 for WN = 128)
         constexpr int RPS = 64 / LPR;              // rows per step
         static_assert(32 * PITCH + WM * 8 <= EPW, "epilogue staging does not fit");
-        unsigned char* ep = stage1 + wave * EPW;
+        unsigned char* ep = !DEEP ? stage1 + wave * EPW
+                            : wave < 3 ? sa1 + wave * EPW : wave < 6 ? sa2 + (wave - 3) * EPW : sw1 + (wave - 6) * EPW;
         float2* ep_st = reinterpret_cast<float2*>(ep + 32 * PITCH);  // the wave's row statistics
         if (LN_EPI) {
 #pragma unroll
@@ -373,7 +450,14 @@ __global__ __launch_bounds__(WGM* WGN * 64, WGM* WGN / 4) void gemm_bf16_kernel(
                                                   : make_uint4(0u, 0u, 0u, 0u);
                 }
             }
-            if (j == 0) RS_GEMM_DMA(stage0, more ? 0 : S)
+            if (j == 0) {
+                if constexpr (DEEP) {
+                    RS_GEMM_DMA_A(sa0, more ? 0 : S)
+                    RS_GEMM_DMA_W(sw0, more ? 0 : S)
+                } else {
+                    RS_GEMM_DMA(stage0, more ? 0 : S)
+                }
+            }
 #pragma unroll
             for (int i = 0; i < TN; ++i)
 #pragma unroll
@@ -456,6 +540,10 @@ __global__ __launch_bounds__(WGM* WGN * 64, WGM* WGN / 4) void gemm_bf16_kernel(
         if (!more) break;
     }  // tiles
 #undef RS_GEMM_DMA
+#undef RS_GEMM_DMA_A
+#undef RS_GEMM_DMA_W
+#undef RS_GEMM_LOAD_FRAGS2
+#undef RS_GEMM_SLICE3
 #undef RS_GEMM_DECODE
 #undef RS_GEMM_LOAD_FRAGS
 #undef RS_GEMM_MFMA
@@ -888,6 +976,17 @@ static void launch_ring_auto(const GemmArgs& g, hipStream_t s) {
     else launch_ring<128, 128, EPI, DIST>(g, s);
 }
 
+// With a long K (at least 2048, and a slice count that the six-slice trip of the deeper ring pads
+// by under 5 %) the kernel runs with three activation stages: its copies, not its matrix work,
+// set the pace there (fc2 of ViT-B: -5 %); with a short K the tile is mostly prologue and
+// epilogue and the third stage's extra requests cost more than they hide (+2..5 %).
+static bool gemm_deep_stages(int K) {
+    static const int force = [] { const char* e = getenv("RS_GEMM_STAGES"); return e ? atoi(e) : 0; }();  // tuning aid: 2 or 3
+    if (force == 2 || force == 3) return force == 3;
+    const int S = K / 64, pad = (S + 5) / 6 * 6 - S;
+    return K >= 2048 && 20 * pad <= S;
+}
+
 template <int EPI, int DIST>
 static void launch_persistent(const GemmArgs& g, hipStream_t s) {
     using C = GemmCfg;
@@ -896,9 +995,14 @@ static void launch_persistent(const GemmArgs& g, hipStream_t s) {
     const int cus = device_cus();
     const int share = (tiles_m * tiles_n + 7) / 8;
     const int per_xcd = share < cus / 8 ? share : cus / 8;
-    hipLaunchKernelGGL((gemm_bf16_kernel<C::BM, C::BN, C::BK, C::NSTAGE, C::WGM, C::WGN, EPI, DIST>),
-                       dim3(8 * per_xcd), dim3(C::WGM * C::WGN * 64), 0, s, g.a, g.wt, g.bias, g.res, g.out, g.partials,
-                       g.ref, g.post, g.ln, (int)g.M, g.N, g.K, tiles_m, tiles_n, (g.N + 63) / 64, RS_GEMM_GM);
+    if (gemm_deep_stages(g.K))
+        hipLaunchKernelGGL((gemm_bf16_kernel<C::BM, C::BN, C::BK, 3, C::WGM, C::WGN, EPI, DIST>),
+                           dim3(8 * per_xcd), dim3(C::WGM * C::WGN * 64), 0, s, g.a, g.wt, g.bias, g.res, g.out, g.partials,
+                           g.ref, g.post, g.ln, (int)g.M, g.N, g.K, tiles_m, tiles_n, (g.N + 63) / 64, RS_GEMM_GM);
+    else
+        hipLaunchKernelGGL((gemm_bf16_kernel<C::BM, C::BN, C::BK, 2, C::WGM, C::WGN, EPI, DIST>),
+                           dim3(8 * per_xcd), dim3(C::WGM * C::WGN * 64), 0, s, g.a, g.wt, g.bias, g.res, g.out, g.partials,
+                           g.ref, g.post, g.ln, (int)g.M, g.N, g.K, tiles_m, tiles_n, (g.N + 63) / 64, RS_GEMM_GM);
 }
 
 // Choice by shape.  The persistent 256 x 256 kernel has the best matrix-core rate while most CUs
@@ -1075,6 +1179,7 @@ static hipError_t launch_f32(const void* a, const void* w, const void* bias, con
 #define RS_STR(...) RS_STR2(__VA_ARGS__)
 const char* gemm_build_info() {
     return "bf16 gemm: persistent tiles (BM,BN,BK,stages,waves m,waves n) " RS_STR(RS_GEMM_CFG)
+           ", three activation stages when K >= 2048"
            "; ring tiles 128x256x32 and 128x128x32, 3 stages, 4 waves, 2 workgroups per CU, up to 0.5 rounds (1.5 if K <= 512)"
            "; rows behind whole rounds go to a ring kernel when K >= " RS_STR(RS_GEMM_TAIL_MINK) " and the last round is under " RS_STR(RS_GEMM_TAIL_FRAC) " full";
 }
