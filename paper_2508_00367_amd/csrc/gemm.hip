@@ -437,19 +437,23 @@ __global__ __launch_bounds__(WGM* WGN * 64, WGM* WGN / 4) void gemm_bf16_kernel(
                 bv[2 * e + 1] = __uint_as_float(w4[e] & 0xffff0000u);
             }
         }
+        // The residual rows of a 32-row group are requested one group ahead (those of group 0 before
+        // the loop): a group's staging round trip through LDS is far shorter than a trip to memory.
+        constexpr bool RES = EPI == EPI_BIAS_RES || EPI == EPI_BIAS_RES_SHIFT;
+        uint4 res_all[RES ? TM : 1][RES ? 32 / RPS : 1];
+#define RS_GEMM_LOAD_RES(j_)                                                                              \
+    if (RES) {                                                                                            \
+        _Pragma("unroll") for (int st = 0; st < 32 / RPS; ++st) {                                         \
+            const int m = m0_cur + wm * WM + (j_) * 32 + st * RPS + orow;                                 \
+            res_all[RES ? (j_) : 0][st] = (m < M && n_ok) ? *reinterpret_cast<const uint4*>(res + (int64_t)m * N + n) \
+                                                           : make_uint4(0u, 0u, 0u, 0u);                  \
+        }                                                                                                 \
+    }
+        RS_GEMM_LOAD_RES(0)
 #pragma unroll
         for (int j = 0; j < TM; ++j) {
-            // the residual rows of this 32-row group: issued before the staging round trip
-            constexpr bool RES = EPI == EPI_BIAS_RES || EPI == EPI_BIAS_RES_SHIFT;
-            uint4 res_raw[RES ? 32 / RPS : 1];
-            if (RES) {
-#pragma unroll
-                for (int st = 0; st < 32 / RPS; ++st) {
-                    const int m = m0_cur + wm * WM + j * 32 + st * RPS + orow;
-                    res_raw[st] = (m < M && n_ok) ? *reinterpret_cast<const uint4*>(res + (int64_t)m * N + n)
-                                                  : make_uint4(0u, 0u, 0u, 0u);
-                }
-            }
+            if (j + 1 < TM) RS_GEMM_LOAD_RES(j + 1)
+            const uint4 (&res_raw)[RES ? 32 / RPS : 1] = res_all[RES ? j : 0];
             if (j == 0) {
                 if constexpr (DEEP) {
                     RS_GEMM_DMA_A(sa0, more ? 0 : S)
@@ -542,6 +546,7 @@ __global__ __launch_bounds__(WGM* WGN * 64, WGM* WGN / 4) void gemm_bf16_kernel(
 #undef RS_GEMM_DMA
 #undef RS_GEMM_DMA_A
 #undef RS_GEMM_DMA_W
+#undef RS_GEMM_LOAD_RES
 #undef RS_GEMM_LOAD_FRAGS2
 #undef RS_GEMM_SLICE3
 #undef RS_GEMM_DECODE
