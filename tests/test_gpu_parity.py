@@ -505,6 +505,33 @@ def test_gemm_rows_split_between_two_kernels():
     assert norm_err(to_host(outs[0])[rows], ref) < 5e-3
 
 
+@pytest.mark.parametrize("M,K,N", [(300, 3072, 256), (777, 2560, 320), (513, 4096, 128), (260, 2048, 64)])
+def test_persistent_gemm_long_k(M, K, N):
+    """The persistent GEMM keeps three LDS stages for the activation rows when K is long (trip of six
+    slices: 3072 fits, 2560 and 4096 are padded with zero slices, 2048 would be padded by too much and
+    keeps two stages): forced on small ragged problems, against the checker and bit for bit against
+    the 128 x 128 ring kernel, with the residual epilogue."""
+    a = host_round(si.generic(23, 30, (M, K)), "bf16")
+    wgt = host_round(si.generic(23, 31, (K, N), std=0.03), "bf16")
+    b = host_round(si.generic(23, 32, (N,), std=0.5), "bf16")
+    res = host_round(si.generic(23, 33, (M, N)), "bf16")
+    da, dw, db, dres = (to_dev(t, "bf16") for t in (a, wgt, b, res))
+    wt = torch.empty((N, K), device="cuda", dtype=torch.bfloat16)
+    rs.rs_pack_linear(dw, wt)
+    outs = []
+    try:
+        for variant in (1, 3):
+            rs.rs_tune_gemm_variant(variant)
+            out = torch.full((M, N), float("nan"), device="cuda", dtype=torch.bfloat16)
+            rs.rs_linear_fwd(da, wt, db, dres, out, rs.RS_EPI_BIAS_RES)
+            torch.cuda.synchronize()
+            outs.append(out)
+    finally:
+        rs.rs_tune_gemm_variant(0)
+    assert torch.equal(outs[0].view(torch.int16), outs[1].view(torch.int16))
+    assert norm_err(to_host(outs[0]), oracle.linear(a, wgt, b) + res) < 5e-3
+
+
 def test_multi_block_teacher_forced():
     """Four blocks of a ViT-S-like stack with 16 tokens dropped after each: the checker follows
     the GPU's kept set block by block (kept sets may legitimately differ inside the rounding band)."""
