@@ -446,6 +446,36 @@ def test_block_without_pruning_and_null_biases(dtype):
     assert norm_err(to_host(y), ref["xhat"][:, :1]) < TOL[dtype]
 
 
+@pytest.mark.parametrize("seed", [11, 12])
+def test_block_seeded_random_shapes(seed):
+    """Forty seeded random configurations per seed around the kernels' switch-over points: sequence
+    lengths at tile boundaries, MLP widths that take the long-K GEMM path with and without padded
+    trips, every distance, operation choice and GEMM tile variant, prefix 0-2, any keep count."""
+    import random
+    rnd = random.Random(seed)
+    for c in range(40):
+        H = rnd.choice([1, 2, 3, 6, 12])
+        D = 64 * H
+        Dm = rnd.choice([64, 192, 768, 1536, 2048, 2560, 3072, 4096])
+        N = rnd.choice([1, 2, 31, 64, 65, 127, 197, 256, 257, 300, 513, 785])
+        B = rnd.choice([1, 2, 3, 5])
+        if B * N * (D + Dm) > 4_000_000:
+            B = 1
+        P = rnd.choice([0, 1, 2]) if N > 2 else 0
+        K = rnd.randint(0 if P else 1, N - P)
+        dist = rnd.choice([rs.RS_DIST_L2, rs.RS_DIST_L1, rs.RS_DIST_COS])
+        op = rnd.choice([rs.RS_SHIFT_MLP, rs.RS_SHIFT_ATTN, rs.RS_SHIFT_BLOCK, rs.RS_SHIFT_MLP_STREAM])
+        variant = rnd.choice([0, 0, 0, 1, 2, 3, 4])
+        _say("random case %d.%d: B %d N %d D %d Dm %d P %d K %d dist %d op %d variant %d"
+             % (seed, c, B, N, D, Dm, P, K, dist, op, variant))
+        x, w = _block_inputs(1000 * seed + c, B, N, D, Dm, "bf16", std=0.05, spread=0.3, affine_ln=bool(c & 1))
+        try:
+            rs.rs_tune_gemm_variant(variant)
+            _check_block(x, w, H, P, K, "bf16", dist=dist, op=op, pack=bool(c & 2))
+        finally:
+            rs.rs_tune_gemm_variant(0)
+
+
 def test_block_packed_weights_and_determinism():
     x, w = _block_inputs(4, 2, 197, 384, 1536, "bf16")
     a = _run_block(x, w, 6, 1, 150, "bf16", pack=False)
