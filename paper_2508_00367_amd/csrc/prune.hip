@@ -456,8 +456,12 @@ hipError_t launch_select(const float* scores, int32_t* kept_idx, int B, int N, i
         const int64_t tot = (int64_t)B * N;
         hipLaunchKernelGGL(iota_kernel, dim3((unsigned)((tot + 255) / 256)), dim3(256), 0, s, kept_idx, B, N);
     } else {
-        hipLaunchKernelGGL(select_kernel<256>, dim3(B), dim3(256), 0, s, const_cast<float*>(scores), kept_idx, N,
-                           n_prefix, n_keep, (const float*)nullptr, 0, 0);
+        if (N > 1024)
+            hipLaunchKernelGGL(select_kernel<1024>, dim3(B), dim3(1024), 0, s, const_cast<float*>(scores), kept_idx, N,
+                               n_prefix, n_keep, (const float*)nullptr, 0, 0);
+        else
+            hipLaunchKernelGGL(select_kernel<256>, dim3(B), dim3(256), 0, s, const_cast<float*>(scores), kept_idx, N,
+                               n_prefix, n_keep, (const float*)nullptr, 0, 0);
     }
     return hipGetLastError();
 }
@@ -468,12 +472,21 @@ hipError_t launch_select_from_partials(rs_dist dist, const float* partials, int 
                                        int32_t* kept_idx, int B, int N, int n_prefix, int n_keep,
                                        hipStream_t s) {
     if (B == 0) return hipSuccess;
-    if (N <= 256)
+    if (N <= 256) {
         hipLaunchKernelGGL(select_kernel<1024>, dim3(B), dim3(1024), (size_t)N * sizeof(float), s, scores, kept_idx, N,
                            n_prefix, n_keep, partials, slots, (int)dist);
-    else
+    } else if (B < 64) {
+        // a few long sequences (video clips): one workgroup per image would walk its image's slots
+        // alone, one cache line per thread and slot, and spend more time there than selecting.
+        // The scores are formed by a grid over all rows instead (the same additions in the same
+        // order), and the selection reads them back.
+        if (hipError_t e = launch_finalize_scores(dist, partials, slots, scores, (int64_t)B * N, s); e != hipSuccess)
+            return e;
+        return launch_select(scores, kept_idx, B, N, n_prefix, n_keep, s);
+    } else {
         hipLaunchKernelGGL(select_kernel<256>, dim3(B), dim3(256), (size_t)N * sizeof(float), s, scores, kept_idx, N,
                            n_prefix, n_keep, partials, slots, (int)dist);
+    }
     return hipGetLastError();
 }
 
