@@ -380,6 +380,19 @@ def test_block_shapes(dtype, B, N, D, H, Dm, P, K):
     _check_block(x, w, H, P, K, dtype, ln_eps=1e-5)
 
 
+@pytest.mark.parametrize("dist", [rs.RS_DIST_L2, rs.RS_DIST_COS])
+@pytest.mark.parametrize("B,N,K", [(63, 257, 100), (64, 257, 100), (66, 300, 299), (2, 1024, 400), (2, 1025, 1),
+                                   (1, 1300, 650), (64, 256, 128)])
+def test_block_selection_switch_over_points(B, N, K, dist):
+    """The selection inside the bf16 block on both sides of its switch-over points: by counting
+    up to 256 tokens and by radix passes beyond; scores formed by the selection kernel itself
+    (64 images or more) or by a grid over all rows before it (fewer, longer sequences); 256 or
+    1024 threads per image around 1024 tokens.  Kept indices exact on the GPU's own scores."""
+    _say("block selection", B, N, K, dist)
+    x, w = _block_inputs(14, B, N, 64, 128, "bf16", std=0.1, spread=0.3)
+    _check_block(x, w, 1, 1, K, "bf16", dist=dist)
+
+
 @pytest.mark.parametrize("dist", [rs.RS_DIST_L1, rs.RS_DIST_COS])
 def test_block_other_distances(dist):
     x, w = _block_inputs(2, 2, 100, 128, 256, "bf16", std=0.1, spread=0.3)
